@@ -1,0 +1,202 @@
+"""ctypes front end of the plain CPU oracle (oracle/tabed_oracle.c).
+
+TEST INFRASTRUCTURE, NOT PRODUCT: only tests/, __graft_entry__.smoke() and
+bench.py's cpu_baseline leg may import this package.  It shares nothing with
+the HIP library; it works on numpy host arrays only.
+
+The arithmetic lives in the C file; this module only marshals arrays.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tabed_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+FLAG_ACCEPT_MARGIN = 1
+FLAG_SAMPLE_MARGIN = 2
+FLAG_DEGENERATE = 4
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fast-math: summation order is part of the definition)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        _lib.oracle_uniform.restype = C.c_float
+        _lib.oracle_uniform.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32, C.c_int]
+        _lib.oracle_speedup.restype = C.c_double
+        _lib.oracle_speedup.argtypes = [C.c_double] * 3
+        _lib.oracle_softmax.restype = C.c_double
+        _lib.oracle_kl.restype = C.c_double
+        _lib.oracle_tvd.restype = C.c_double
+        _lib.oracle_argmax.restype = C.c_int
+        _lib.oracle_sample_cdf.restype = C.c_int
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def threads() -> int:
+    """Number of OpenMP threads the oracle's parallel loops use."""
+    omp = C.CDLL("libgomp.so.1")
+    omp.omp_get_max_threads.restype = C.c_int
+    return int(omp.omp_get_max_threads())
+
+
+# ---------------------------------------------------------------- primitives
+def philox4x32_10(ctr, key):
+    c = np.ascontiguousarray(ctr, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    out = np.empty(4, dtype=np.uint32)
+    lib().oracle_philox4x32_10(_p(c), _p(k), _p(out))
+    return out
+
+
+def uniform(seed, rnd, b, pos, word):
+    return float(lib().oracle_uniform(seed, rnd, b, pos, word))
+
+
+def speedup(block_eff, gamma, tq_over_tp):
+    return float(lib().oracle_speedup(block_eff, gamma, tq_over_tp))
+
+
+def lm_head(W, H, w_dtype):
+    """W [V,d], H [M,d]: fp32 arrays (w_dtype 0) or uint16 bf16 bit patterns (w_dtype 1)."""
+    V, d = W.shape
+    M = H.shape[0]
+    assert H.shape[1] == d
+    want = np.float32 if w_dtype == 0 else np.uint16
+    W = np.ascontiguousarray(W, dtype=want)
+    H = np.ascontiguousarray(H, dtype=want)
+    L = np.empty((M, V), dtype=np.float32)
+    lib().oracle_lm_head(M, d, V, w_dtype, _p(W), _p(H), _p(L))
+    return L
+
+
+def softmax(logits, T_eff=1.0):
+    x = _f32(logits)
+    V = x.shape[0]
+    p = np.empty(V, dtype=np.float64)
+    logp = np.empty(V, dtype=np.float64)
+    lse = lib().oracle_softmax(_p(x), V, C.c_double(T_eff), _p(p), _p(logp))
+    return p, logp, float(lse)
+
+
+def ensemble(q, w):
+    q = _f64(q)
+    n, V = q.shape
+    w = _f32(w)
+    out = np.empty(V, dtype=np.float64)
+    lib().oracle_ensemble(n, V, _p(q), _p(w), _p(out))
+    return out
+
+
+def argmax(f):
+    f = _f64(f)
+    flag = C.c_uint32(0)
+    v = lib().oracle_argmax(_p(f), f.shape[0], C.byref(flag))
+    return int(v), int(flag.value)
+
+
+def sample_cdf(f, u):
+    f = _f64(f)
+    flag = C.c_uint32(0)
+    v = lib().oracle_sample_cdf(_p(f), f.shape[0], C.c_double(u), C.byref(flag))
+    return int(v), int(flag.value)
+
+
+def kl(p, logp, logq):
+    p, logp, logq = _f64(p), _f64(logp), _f64(logq)
+    return float(lib().oracle_kl(_p(p), _p(logp), _p(logq), p.shape[0]))
+
+
+def tvd(p, q):
+    p, q = _f64(p), _f64(q)
+    return float(lib().oracle_tvd(_p(p), _p(q), p.shape[0]))
+
+
+# ---------------------------------------------------------------- the three calls
+def draft_step(*, V, d, n, B, gamma, w_dtype, seed, rnd, pos, W, H, weights, temperature,
+               draft_logits, draft_lse, draft_tokens, draft_q, flags, u_draft=None):
+    """Alg. 1 lines 5-7 at in-block position `pos`; writes slot/column `pos` of the outputs in place."""
+    assert draft_logits.dtype == np.float32 and draft_logits.shape == (gamma, B, n, V)
+    assert draft_lse.dtype == np.float64 and draft_lse.shape == (gamma, B, n)
+    assert draft_tokens.dtype == np.int32 and draft_tokens.shape == (B, gamma)
+    assert draft_q.dtype == np.float32 and draft_q.shape == (B, gamma)
+    assert flags.dtype == np.uint8 and flags.shape == (B, gamma)
+    want = np.float32 if w_dtype == 0 else np.uint16
+    W = np.ascontiguousarray(W, dtype=want)
+    H = np.ascontiguousarray(H, dtype=want)
+    assert W.shape == (V, d) and H.shape == (B, n, d)
+    weights = _f32(weights)
+    temperature = _f32(temperature)
+    u = None if u_draft is None else _f32(u_draft)
+    lib().oracle_draft_step(V, d, n, B, gamma, w_dtype, C.c_uint64(seed), C.c_uint64(rnd), pos,
+                            _p(W), _p(H), _p(weights), _p(temperature), _p(u),
+                            _p(draft_logits), _p(draft_lse), _p(draft_tokens), _p(draft_q), _p(flags))
+
+
+def verify(*, V, n, B, gamma, distance, seed, rnd, target_logits, draft_logits, draft_tokens,
+           draft_q, weights, temperature, u_acc=None, u_res=None):
+    """Sec. 3 items 2-3 plus per-position distances; returns a dict of fresh output arrays."""
+    target_logits = _f32(target_logits)
+    draft_logits = _f32(draft_logits)
+    assert target_logits.shape == (B, gamma + 1, V) and draft_logits.shape == (gamma, B, n, V)
+    draft_tokens = np.ascontiguousarray(draft_tokens, dtype=np.int32)
+    draft_q = _f32(draft_q)
+    weights = _f32(weights)
+    temperature = _f32(temperature)
+    ua = None if u_acc is None else _f32(u_acc)
+    ur = None if u_res is None else _f32(u_res)
+    out = dict(
+        accept_len=np.zeros(B, dtype=np.int32),
+        out_tokens=np.full((B, gamma + 1), -1, dtype=np.int32),
+        dev=np.zeros((B, gamma, n), dtype=np.float32),
+        n_valid=np.zeros(B, dtype=np.int32),
+        flags=np.zeros((B, gamma + 1), dtype=np.uint8),
+    )
+    lib().oracle_verify(V, n, B, gamma, distance, C.c_uint64(seed), C.c_uint64(rnd),
+                        _p(target_logits), _p(draft_logits), _p(draft_tokens), _p(draft_q),
+                        _p(weights), _p(temperature), _p(ua), _p(ur),
+                        _p(out["accept_len"]), _p(out["out_tokens"]), _p(out["dev"]),
+                        _p(out["n_valid"]), _p(out["flags"]))
+    return out
+
+
+def update_weights(*, n, B, gamma, h, policy, tau_w, eps, dev, n_valid, ring, ring_head, ring_count):
+    """Alg. 1 lines 2-3 (App. B.2 policy); ring state is updated in place; returns weights [B,n]."""
+    assert ring.dtype == np.float32 and ring.shape == (B, h, n)
+    assert ring_head.dtype == np.int32 and ring_count.dtype == np.int32
+    d_ = None if dev is None else _f32(dev)
+    nv = None if n_valid is None else np.ascontiguousarray(n_valid, dtype=np.int32)
+    w = np.empty((B, n), dtype=np.float32)
+    lib().oracle_update_weights(n, B, gamma, h, policy, C.c_double(tau_w), C.c_double(eps),
+                                _p(d_), _p(nv), _p(ring), _p(ring_head), _p(ring_count), _p(w))
+    return w

@@ -1,0 +1,430 @@
+/*
+ * TABED per-round hot path -- plain CPU oracle.
+ *
+ * TEST INFRASTRUCTURE, NOT PRODUCT.  This file is the slow, index-order,
+ * fp64 statement of what one speculative-decoding round of TABED computes.
+ * Only the tests, the smoke check and the benchmark's cpu_baseline leg may
+ * call it.  It shares no code, header, table or helper with the HIP library.
+ *
+ * What it follows (paper sections):
+ *   - Sec. 3 "Preliminaries", items 1-3: draft gamma tokens, verify in
+ *     parallel, accept token y with probability min(1, p(y)/q(y)); at the
+ *     first rejection drop the rest and resample from norm(max(0, p - q)).
+ *   - Sec. 4.1 "Proposed Method" + Algorithm 1: the m drafting methods run
+ *     as one batch through the shared draft model; their distributions are
+ *     mixed by a weighted average (W-Avg) and the next draft token is sampled
+ *     from the mixture; the weights are chosen at the start of a block from
+ *     the accumulated distance e_t^j = sum_{t'} D_KL(p_t' || q_t'^j) over the
+ *     last h verified positions and held for the whole block.
+ *   - App. B.2: the many-draft policy w = softmax([1/e^(1)..1/e^(m)]; tau),
+ *     tau = 1; Sec. 4.1 last paragraph: TVD as the alternative distance.
+ *   - Eq. 1: speedup = block_eff / (gamma * Tq/Tp + 1).
+ *
+ * Notation: n = number of drafting methods (the paper's m), B independent
+ * sequences, V vocabulary, d draft hidden size, gamma block length, h window.
+ *
+ * Readings where the paper is silent are listed in the repository's design
+ * notes; each is marked "reading:" below.
+ *
+ * Pin status: every function below is pinned by tests that do not reuse its
+ * formula (library cross-checks, closed forms, exact enumeration on tiny
+ * vocabularies, the lossless-sampling invariant) EXCEPT oracle_philox4x32_10,
+ * whose published known-answer vectors are not available offline:
+ * "parity unpinned" against those vectors; it is pinned structurally
+ * (inverse permutation written from the definition, uniformity statistics).
+ *
+ * All floating point is fp64 unless a value is an interface value that the
+ * method stores in fp32 (logits, q(y), p(y), dev, ring, weights).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_FLAG_ACCEPT_MARGIN 1u /* accept test closer than 1e-6 relative   */
+#define ORACLE_FLAG_SAMPLE_MARGIN 2u /* CDF edge / arg-max tie closer than 1e-6 */
+#define ORACLE_FLAG_DEGENERATE    4u /* empty residual or CDF never crossed     */
+
+static const double MARGIN = 1e-6;
+
+/* ------------------------------------------------------------------ */
+/* Philox4x32-10 (Salmon et al., SC'11): counter-based generator.      */
+/* ------------------------------------------------------------------ */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    const uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)M0 * c0;
+        uint64_t p1 = (uint64_t)M1 * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += W0; k1 += W1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/*
+ * reading: the uniforms of a round depend only on (seed, round, b, pos):
+ * key = (seed lo, seed hi), counter = (round lo, round hi, b, pos).
+ * For pos < gamma word 0 is the draft-sampling uniform and word 1 the
+ * accept-test uniform; at pos = gamma word 0 drives the residual or bonus
+ * sample.  u = (x >> 8) * 2^-24 lies in [0,1) and is exact in fp32.
+ */
+float oracle_uniform(uint64_t seed, uint64_t round, uint32_t b, uint32_t pos, int word)
+{
+    uint32_t ctr[4] = { (uint32_t)round, (uint32_t)(round >> 32), b, pos };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    oracle_philox4x32_10(ctr, key, out);
+    return (float)(out[word & 3] >> 8) * (1.0f / 16777216.0f);
+}
+
+/* ------------------------------------------------------------------ */
+/* Eq. 1: expected walltime speedup from block efficiency.             */
+/* ------------------------------------------------------------------ */
+double oracle_speedup(double block_eff, double gamma, double tq_over_tp)
+{
+    return block_eff / (gamma * tq_over_tp + 1.0);
+}
+
+/* ------------------------------------------------------------------ */
+/* LM head (Alg. 1 line 5, last layer of M_q): L[r,v] = sum_k H[r,k] W[v,k]. */
+/* Storage values (fp32 or bf16) are upcast exactly; fp64 accumulation in    */
+/* k order; one rounding to fp32 at the end.                                  */
+/* ------------------------------------------------------------------ */
+static double load_elem(const void* base, int dtype, size_t idx)
+{
+    if (dtype == 0) return (double)((const float*)base)[idx];
+    uint32_t bits = (uint32_t)((const uint16_t*)base)[idx] << 16; /* bf16 */
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+void oracle_lm_head(int M, int d, int V, int w_dtype, const void* W, const void* H, float* L)
+{
+    double* a = (double*)malloc((size_t)M * d * sizeof(double));
+    for (size_t i = 0; i < (size_t)M * d; ++i) a[i] = load_elem(H, w_dtype, i);
+#pragma omp parallel
+    {
+        double* wrow = (double*)malloc((size_t)d * sizeof(double));
+#pragma omp for schedule(static)
+        for (int v = 0; v < V; ++v) {
+            for (int k = 0; k < d; ++k) wrow[k] = load_elem(W, w_dtype, (size_t)v * d + k);
+            for (int r = 0; r < M; ++r) {
+                double acc = 0.0;
+                for (int k = 0; k < d; ++k) acc += a[(size_t)r * d + k] * wrow[k];
+                L[(size_t)r * V + v] = (float)acc;
+            }
+        }
+        free(wrow);
+    }
+    free(a);
+}
+
+/* ------------------------------------------------------------------ */
+/* Vocabulary-wide building blocks.                                    */
+/* ------------------------------------------------------------------ */
+
+/* softmax of logits / T_eff; returns log-sum-exp of the scaled logits.
+ * p and logp may be NULL. */
+double oracle_softmax(const float* logits, int V, double T_eff, double* p, double* logp)
+{
+    double m = -INFINITY;
+    for (int v = 0; v < V; ++v) {
+        double s = (double)logits[v] / T_eff;
+        if (s > m) m = s;
+    }
+    double Z = 0.0;
+    for (int v = 0; v < V; ++v) Z += exp((double)logits[v] / T_eff - m);
+    double lse = m + log(Z);
+    for (int v = 0; v < V; ++v) {
+        double lp = (double)logits[v] / T_eff - lse;
+        if (logp) logp[v] = lp;
+        if (p) p[v] = exp(lp);
+    }
+    return lse;
+}
+
+/* W-Avg (Alg. 1 line 6): probability-space weighted average of n rows. */
+void oracle_ensemble(int n, int V, const double* q, const float* w, double* q_ens)
+{
+    for (int v = 0; v < V; ++v) {
+        double acc = 0.0;
+        for (int j = 0; j < n; ++j) acc += (double)w[j] * q[(size_t)j * V + v];
+        q_ens[v] = acc;
+    }
+}
+
+/* reading: arg-max ties go to the lowest index; the decision is flagged when
+ * the runner-up is within 1e-6 relative of the maximum. */
+int oracle_argmax(const double* f, int V, uint32_t* flag)
+{
+    int best = 0;
+    for (int v = 1; v < V; ++v) if (f[v] > f[best]) best = v;
+    double second = -INFINITY;
+    for (int v = 0; v < V; ++v) if (v != best && f[v] > second) second = f[v];
+    if (flag && V > 1 && (f[best] - second) < MARGIN * fabs(f[best])) *flag |= ORACLE_FLAG_SAMPLE_MARGIN;
+    return best;
+}
+
+static int argmax_logits(const float* x, int V)
+{
+    int best = 0;
+    for (int v = 1; v < V; ++v) if (x[v] > x[best]) best = v;
+    return best;
+}
+
+/* reading: Sample(f, u) is the inverse CDF of the (possibly unnormalised)
+ * non-negative f: the smallest v whose inclusive prefix sum exceeds u * Z,
+ * Z = sum f.  If rounding lets no prefix exceed it, the last v with f(v) > 0.
+ * Flagged when u * Z lies within 1e-6 * Z of either edge of the chosen bin. */
+int oracle_sample_cdf(const double* f, int V, double u, uint32_t* flag)
+{
+    double Z = 0.0;
+    for (int v = 0; v < V; ++v) Z += f[v];
+    double target = u * Z;
+    double c = 0.0;
+    for (int v = 0; v < V; ++v) {
+        double prev = c;
+        c += f[v];
+        if (c > target) {
+            if (flag) {
+                if (fabs(c - target) < MARGIN * Z && v + 1 < V) *flag |= ORACLE_FLAG_SAMPLE_MARGIN;
+                if (v > 0 && fabs(prev - target) < MARGIN * Z) *flag |= ORACLE_FLAG_SAMPLE_MARGIN;
+            }
+            return v;
+        }
+    }
+    int last = V - 1;
+    for (int v = V - 1; v >= 0; --v) if (f[v] > 0.0) { last = v; break; }
+    if (flag) *flag |= ORACLE_FLAG_SAMPLE_MARGIN | ORACLE_FLAG_DEGENERATE;
+    return last;
+}
+
+/* D_KL(p || q) = sum_v p(v) (log p(v) - log q(v)), from log-probabilities;
+ * a term with p(v) == 0 contributes 0.  (Sec. 4.1, the formula for e_t^j.) */
+double oracle_kl(const double* p, const double* logp, const double* logq, int V)
+{
+    double acc = 0.0;
+    for (int v = 0; v < V; ++v) if (p[v] > 0.0) acc += p[v] * (logp[v] - logq[v]);
+    return acc;
+}
+
+/* Total variation distance, the alternative D of Sec. 4.1. */
+double oracle_tvd(const double* p, const double* q, int V)
+{
+    double acc = 0.0;
+    for (int v = 0; v < V; ++v) acc += fabs(p[v] - q[v]);
+    return 0.5 * acc;
+}
+
+/* ------------------------------------------------------------------ */
+/* Alg. 1 lines 5-7 for one in-block position, all B sequences.        */
+/* ------------------------------------------------------------------ */
+/* Layouts: W [V,d], H [B,n,d] (w_dtype 0 fp32 / 1 bf16), weights [B,n],
+ * temperature [B] (0 => greedy row), u_draft [B,gamma] or NULL (=> Philox),
+ * draft_logits [gamma,B,n,V], draft_lse [gamma,B,n] (fp64), draft_tokens
+ * [B,gamma], draft_q [B,gamma], flags [B,gamma].
+ * reading: a greedy row takes arg-max decisions but its distributions are the
+ * untempered softmax (T_eff = 1), because the paper runs greedy decoding while
+ * scoring drafts with soft-label KL. */
+void oracle_draft_step(int V, int d, int n, int B, int gamma, int w_dtype,
+                       uint64_t seed, uint64_t round, int pos,
+                       const void* W, const void* H, const float* weights,
+                       const float* temperature, const float* u_draft,
+                       float* draft_logits, double* draft_lse, int32_t* draft_tokens,
+                       float* draft_q, uint8_t* flags)
+{
+    float* L = draft_logits + (size_t)pos * B * n * V;
+    oracle_lm_head(B * n, d, V, w_dtype, W, H, L);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        double T = (double)temperature[b];
+        double T_eff = T > 0.0 ? T : 1.0;
+        double* q = (double*)malloc((size_t)n * V * sizeof(double));
+        double* q_ens = (double*)malloc((size_t)V * sizeof(double));
+        for (int j = 0; j < n; ++j) {
+            double lse = oracle_softmax(L + ((size_t)b * n + j) * V, V, T_eff, q + (size_t)j * V, NULL);
+            draft_lse[((size_t)pos * B + b) * n + j] = lse;
+        }
+        oracle_ensemble(n, V, q, weights + (size_t)b * n, q_ens);
+        uint32_t flag = 0;
+        int y;
+        if (T > 0.0) {
+            float u = u_draft ? u_draft[(size_t)b * gamma + pos]
+                              : oracle_uniform(seed, round, (uint32_t)b, (uint32_t)pos, 0);
+            y = oracle_sample_cdf(q_ens, V, (double)u, &flag);
+        } else {
+            y = oracle_argmax(q_ens, V, &flag);
+        }
+        draft_tokens[(size_t)b * gamma + pos] = y;
+        draft_q[(size_t)b * gamma + pos] = (float)q_ens[y];
+        flags[(size_t)b * gamma + pos] = (uint8_t)flag;
+        free(q); free(q_ens);
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* Sec. 3 items 2-3 + the per-position distances of Alg. 1 line 3.     */
+/* ------------------------------------------------------------------ */
+/* target_logits [B,gamma+1,V]; u_acc [B,gamma] / u_res [B] or NULL (=> Philox).
+ * Outputs: accept_len [B] = k; out_tokens [B,gamma+1] = the k accepted draft
+ * tokens, then one corrected (k < gamma) or bonus (k = gamma) token, then -1;
+ * dev [B,gamma,n] = D(p_i, q_i^(j)) for every i < gamma (meaningful for
+ * i < n_valid); n_valid [B] = min(k+1, gamma); flags [B,gamma+1].
+ * reading: the accept test is u * q(y) < p(y), evaluated in fp32 on the fp32
+ * interface values; greedy rows accept iff y equals the arg-max of the target
+ * logits, and emit that arg-max as corrected / bonus token.
+ * reading: when all gamma tokens are accepted one bonus token is drawn from
+ * p_gamma, so a round emits k+1 tokens.
+ * reading: only positions 0..min(k, gamma-1) have both a verified target
+ * distribution and draft distributions conditioned on kept tokens, hence
+ * n_valid. */
+void oracle_verify(int V, int n, int B, int gamma, int distance,
+                   uint64_t seed, uint64_t round,
+                   const float* target_logits, const float* draft_logits,
+                   const int32_t* draft_tokens, const float* draft_q,
+                   const float* weights, const float* temperature,
+                   const float* u_acc, const float* u_res,
+                   int32_t* accept_len, int32_t* out_tokens, float* dev,
+                   int32_t* n_valid, uint8_t* flags)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        double T = (double)temperature[b];
+        int greedy = !(T > 0.0);
+        double T_eff = greedy ? 1.0 : T;
+        const float* Lt = target_logits + (size_t)b * (gamma + 1) * V;
+        double* p = (double*)malloc((size_t)V * sizeof(double));
+        double* logp = (double*)malloc((size_t)V * sizeof(double));
+        double* q = (double*)malloc((size_t)n * V * sizeof(double));
+        double* logq = (double*)malloc((size_t)n * V * sizeof(double));
+        double* f = (double*)malloc((size_t)V * sizeof(double));
+        uint8_t* fl = flags + (size_t)b * (gamma + 1);
+        for (int i = 0; i <= gamma; ++i) fl[i] = 0;
+
+        int k = 0, rejected = 0;
+        for (int i = 0; i < gamma; ++i) {
+            oracle_softmax(Lt + (size_t)i * V, V, T_eff, p, logp);
+            for (int j = 0; j < n; ++j) {
+                const float* Lq = draft_logits + (((size_t)i * B + b) * n + j) * V;
+                oracle_softmax(Lq, V, T_eff, q + (size_t)j * V, logq + (size_t)j * V);
+                double D = distance == 0 ? oracle_kl(p, logp, logq + (size_t)j * V, V)
+                                         : oracle_tvd(p, q + (size_t)j * V, V);
+                dev[((size_t)b * gamma + i) * n + j] = (float)D;
+            }
+            if (rejected || k < i) continue; /* later positions: distances only */
+            int y = draft_tokens[(size_t)b * gamma + i];
+            int ok;
+            if (greedy) {
+                ok = (y == argmax_logits(Lt + (size_t)i * V, V));
+            } else {
+                float u = u_acc ? u_acc[(size_t)b * gamma + i]
+                                : oracle_uniform(seed, round, (uint32_t)b, (uint32_t)i, 1);
+                float qy = draft_q[(size_t)b * gamma + i];
+                float py = (float)p[y];
+                float lhs = u * qy;
+                ok = lhs < py;
+                double a = (double)lhs, c = (double)py;
+                if (fabs(a - c) < MARGIN * fmax(a, c)) fl[i] |= ORACLE_FLAG_ACCEPT_MARGIN;
+            }
+            if (ok) { k++; continue; }
+            rejected = 1;
+            /* corrected token at the rejected position */
+            int tok;
+            if (greedy) {
+                tok = argmax_logits(Lt + (size_t)i * V, V);
+            } else {
+                oracle_ensemble(n, V, q, weights + (size_t)b * n, f); /* f = q_ens,i */
+                double Z = 0.0;
+                for (int v = 0; v < V; ++v) { f[v] = fmax(0.0, p[v] - f[v]); Z += f[v]; }
+                uint32_t flag = 0;
+                float u = u_res ? u_res[b] : oracle_uniform(seed, round, (uint32_t)b, (uint32_t)gamma, 0);
+                if (!(Z > 0.0)) { /* reading: empty residual => draw from p itself */
+                    flag |= ORACLE_FLAG_DEGENERATE;
+                    tok = oracle_sample_cdf(p, V, (double)u, &flag);
+                } else {
+                    tok = oracle_sample_cdf(f, V, (double)u, &flag);
+                }
+                fl[i] |= (uint8_t)flag;
+            }
+            out_tokens[(size_t)b * (gamma + 1) + i] = tok;
+        }
+        if (!rejected) { /* all gamma accepted: bonus token from p_gamma */
+            int tok;
+            if (greedy) {
+                tok = argmax_logits(Lt + (size_t)gamma * V, V);
+            } else {
+                oracle_softmax(Lt + (size_t)gamma * V, V, T_eff, p, NULL);
+                uint32_t flag = 0;
+                float u = u_res ? u_res[b] : oracle_uniform(seed, round, (uint32_t)b, (uint32_t)gamma, 0);
+                tok = oracle_sample_cdf(p, V, (double)u, &flag);
+                fl[gamma] |= (uint8_t)flag;
+            }
+            out_tokens[(size_t)b * (gamma + 1) + gamma] = tok;
+        }
+        for (int i = 0; i < k; ++i)
+            out_tokens[(size_t)b * (gamma + 1) + i] = draft_tokens[(size_t)b * gamma + i];
+        for (int i = k + 1; i <= gamma; ++i) out_tokens[(size_t)b * (gamma + 1) + i] = -1;
+        accept_len[b] = k;
+        n_valid[b] = k + 1 < gamma ? k + 1 : gamma;
+        free(p); free(logp); free(q); free(logq); free(f);
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* Alg. 1 lines 2-3 with the App. B.2 many-draft policy.               */
+/* ------------------------------------------------------------------ */
+/* ring [B,h,n] holds the last <= h per-position distance vectors of each
+ * sequence; ring_head [B] is the next slot to overwrite, ring_count [B] the
+ * number of live slots.  dev / n_valid may be NULL (nothing to push).
+ * policy 0: w = softmax((1 / max(e_j, eps)) / tau_w), e_j = sum over the
+ * window; policy 1: equal weights.
+ * reading: an empty window gives equal weights; a window with fewer than h
+ * entries sums what exists; 1/e is clamped by eps; softmax(x; tau) divides
+ * by tau. */
+void oracle_update_weights(int n, int B, int gamma, int h, int policy,
+                           double tau_w, double eps,
+                           const float* dev, const int32_t* n_valid,
+                           float* ring, int32_t* ring_head, int32_t* ring_count,
+                           float* weights)
+{
+    for (int b = 0; b < B; ++b) {
+        if (dev && n_valid) {
+            for (int i = 0; i < n_valid[b]; ++i) {
+                int slot = ring_head[b];
+                for (int j = 0; j < n; ++j)
+                    ring[((size_t)b * h + slot) * n + j] = dev[((size_t)b * gamma + i) * n + j];
+                ring_head[b] = (slot + 1) % h;
+                if (ring_count[b] < h) ring_count[b]++;
+            }
+        }
+        float* w = weights + (size_t)b * n;
+        int count = ring_count[b];
+        if (policy == 1 || count == 0) {
+            for (int j = 0; j < n; ++j) w[j] = (float)(1.0 / n);
+            continue;
+        }
+        double x[64];
+        double xmax = -INFINITY;
+        for (int j = 0; j < n; ++j) {
+            double e = 0.0;
+            for (int t = 0; t < count; ++t) { /* oldest .. newest */
+                int slot = ((ring_head[b] - count + t) % h + h) % h;
+                e += (double)ring[((size_t)b * h + slot) * n + j];
+            }
+            x[j] = (1.0 / fmax(e, eps)) / tau_w;
+            if (x[j] > xmax) xmax = x[j];
+        }
+        double Z = 0.0;
+        for (int j = 0; j < n; ++j) Z += exp(x[j] - xmax);
+        for (int j = 0; j < n; ++j) w[j] = (float)(exp(x[j] - xmax) / Z);
+    }
+}
