@@ -1,0 +1,192 @@
+/*
+ * tabed.h -- C ABI of the TABED per-round hot path on one MI355X (gfx950).
+ *
+ * TABED (Test-time Adaptive Batched Ensemble Drafting) runs n drafting methods
+ * as one batch through a shared draft model, mixes their next-token
+ * distributions with test-time-adaptive weights, and has the target model
+ * verify gamma drafted tokens by speculative sampling.  This library is the
+ * part of one such round that sits behind the two models' transformer bodies:
+ *
+ *   tabed_update_weights   Alg. 1 lines 2-3 with the many-draft policy of
+ *                          App. B.2 (w = softmax(1/e; tau)), incl. the window.
+ *   tabed_draft_step       Alg. 1 lines 5-7 for one in-block position: LM head
+ *                          of the n drafts as one batched GEMM, per-draft
+ *                          softmax, weighted-average ensemble, next token.
+ *   tabed_verify           Sec. 3 items 2-3: accept each drafted token with
+ *                          probability min(1, p/q), resample the first rejected
+ *                          one from norm(max(0, p - q)); plus the per-position
+ *                          distances D(p, q^(j)) of Sec. 4.1 that feed the
+ *                          next tabed_update_weights.
+ *
+ * Notation: n = number of drafting methods (the paper's m), B independent
+ * sequences, V vocabulary size, d draft hidden size, gamma block length,
+ * h observation window (in verified positions).
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers owned by the caller; `cfg` is a
+ *     HOST pointer.  The library allocates, frees and synchronises nothing:
+ *     kernels are enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and the call returns at once.
+ *   - Row-major, innermost index last.  Base pointers 16-byte aligned.
+ *   - Return value: TABED_OK or a negative TABED_E* code.  Argument errors are
+ *     detected on the host before anything is enqueued.
+ *   - `ws` is scratch memory of tabed_workspace_bytes(cfg) bytes.  It must be
+ *     prepared once with tabed_workspace_init() and may then be reused by any
+ *     number of calls with the same cfg on the same stream.  Calls that share
+ *     a workspace must not overlap.
+ *   - A temperature of 0 marks a greedy row: token decisions are arg-max
+ *     (lowest index on ties) and its distributions are the untempered softmax.
+ *   - Uniform random numbers come from Philox4x32-10 with key = cfg->seed and
+ *     counter = (round, b, pos): word 0 at pos < gamma drives the draft sample,
+ *     word 1 the accept test; word 0 at pos = gamma drives the corrected /
+ *     bonus sample; u = (x >> 8) * 2^-24.  Each call also takes optional
+ *     arrays of explicit uniforms that replace them (NULL = Philox).
+ *   - flag bits: TABED_FLAG_* below.  A flagged decision had a margin below
+ *     1e-6 relative and may legitimately differ from a higher-precision
+ *     evaluation.
+ */
+#ifndef TABED_H
+#define TABED_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TABED_MAX_N 16     /* drafting methods                      */
+#define TABED_MAX_GAMMA 32 /* block length                          */
+
+#define TABED_OK 0
+#define TABED_ENULL (-1)        /* a required pointer is NULL                         */
+#define TABED_EINVAL (-2)       /* a cfg field is out of range                        */
+#define TABED_ERANGE (-3)       /* pos >= gamma, n > TABED_MAX_N, ...                 */
+#define TABED_EALIGN (-4)       /* a base pointer is not 16-byte aligned              */
+#define TABED_EUNSUPPORTED (-5) /* valid request this build does not implement        */
+#define TABED_EHIP (-6)         /* a kernel launch failed (see tabed_last_hip_error)  */
+
+#define TABED_FLAG_ACCEPT_MARGIN 1u /* accept test u*q < p closer than 1e-6 relative          */
+#define TABED_FLAG_SAMPLE_MARGIN 2u /* CDF crossing / arg-max runner-up closer than 1e-6      */
+#define TABED_FLAG_DEGENERATE 4u    /* empty residual, CDF never crossed, or token out of range */
+
+typedef struct tabed_cfg {
+    int32_t V;        /* vocabulary size, >= 1                                             */
+    int32_t d;        /* draft hidden size, >= 1 (multiple of 8 when w_dtype = 1)          */
+    int32_t n;        /* drafting methods batched through the draft model, 1..TABED_MAX_N  */
+    int32_t B;        /* independent sequences, >= 1                                       */
+    int32_t gamma;    /* draft block length, 1..TABED_MAX_GAMMA                            */
+    int32_t h;        /* observation window length in verified positions, >= 1             */
+    int32_t w_dtype;  /* storage type of W and H: 0 = fp32, 1 = bf16                       */
+    int32_t distance; /* D of Alg. 1: 0 = KL(p || q) (Sec. 4.1); 1 = TVD (not built yet)   */
+    int32_t policy;   /* 0 = softmax(1/e; tau_w) (App. B.2); 1 = static equal weights      */
+    float tau_w;      /* temperature of the weight softmax, > 0 (paper default 1)          */
+    float eps;        /* e is clamped to >= eps before 1/e, > 0                            */
+    uint64_t seed;    /* Philox key                                                        */
+} tabed_cfg;
+
+/* Bytes of scratch the calls below need for this cfg; 0 if cfg is invalid. */
+size_t tabed_workspace_bytes(const tabed_cfg* cfg);
+
+/* Zeroes the arrival counters inside `ws` (a small fill kernel on `stream`).
+ * Call once after allocating `ws`, before the first draft/verify call. */
+int tabed_workspace_init(const tabed_cfg* cfg, void* ws, void* stream);
+
+/* Static text for an error code. */
+const char* tabed_strerror(int code);
+
+/* hipError_t value of the most recent failed launch on this host thread (0 if none). */
+int tabed_last_hip_error(void);
+
+/*
+ * Alg. 1 lines 5-7 at in-block position `pos` (0 <= pos < gamma) for all B
+ * sequences:  L = H W^T for the n*B rows, q^(j) = softmax(L_j / T),
+ * q = sum_j w_j q^(j), y ~ Sample(q) (arg-max for greedy rows).
+ *
+ *   W            [V,d]            in   LM-head matrix shared by all drafts (w_dtype)
+ *   H            [B,n,d]          in   last hidden state of every draft (w_dtype)
+ *   weights      [B,n]     fp32   in   w*_t, constant over the block (Sec. 4.1)
+ *   temperature  [B]       fp32   in   0 => greedy row
+ *   u_draft      [B,gamma] fp32   in   optional explicit uniforms, column pos is read; NULL => Philox
+ *   draft_logits [gamma,B,n,V] fp32 out slot pos is written
+ *   draft_lse    [gamma,B,n] fp64 out  log-sum-exp of L_j / T, slot pos is written
+ *   draft_tokens [B,gamma] int32  out  column pos is written
+ *   draft_q      [B,gamma] fp32   out  q(y), column pos is written
+ *   flags        [B,gamma] uint8  out  column pos is written
+ */
+int tabed_draft_step(const tabed_cfg* cfg, void* ws, uint64_t round, int32_t pos,
+                     const void* W, const void* H, const float* weights, const float* temperature,
+                     const float* u_draft,
+                     float* draft_logits, double* draft_lse, int32_t* draft_tokens, float* draft_q,
+                     uint8_t* flags, void* stream);
+
+/*
+ * Sec. 3 items 2-3 for all B sequences, given the target's logits at the
+ * gamma drafted positions and one position beyond; plus D(p_i, q_i^(j)) for
+ * every drafted position i and draft j (Sec. 4.1).
+ *
+ *   target_logits [B,gamma+1,V] fp32 in
+ *   draft_logits, draft_lse, draft_tokens, draft_q, weights, temperature: as written by / passed to
+ *                 the gamma tabed_draft_step calls of this round
+ *   u_acc         [B,gamma] fp32  in   optional explicit accept-test uniforms; NULL => Philox
+ *   u_res         [B]       fp32  in   optional explicit uniform of the corrected/bonus sample
+ *   accept_len    [B]       int32 out  k = number of accepted draft tokens, 0..gamma
+ *   out_tokens    [B,gamma+1] int32 out k accepted tokens, then one corrected (k < gamma) or bonus
+ *                 (k = gamma) token, then -1
+ *   dev           [B,gamma,n] fp32 out D(p_i, q_i^(j)); meaningful for i < n_valid[b]
+ *   n_valid       [B]       int32 out  min(k+1, gamma): positions whose distances enter the window
+ *   flags         [B,gamma+1] uint8 out flags of the accept test at i and of the sample emitted at i
+ * A drafted token outside [0,V) is rejected and flagged TABED_FLAG_DEGENERATE.
+ */
+int tabed_verify(const tabed_cfg* cfg, void* ws, uint64_t round,
+                 const float* target_logits, const float* draft_logits, const double* draft_lse,
+                 const int32_t* draft_tokens, const float* draft_q, const float* weights,
+                 const float* temperature, const float* u_acc, const float* u_res,
+                 int32_t* accept_len, int32_t* out_tokens, float* dev, int32_t* n_valid,
+                 uint8_t* flags, void* stream);
+
+/*
+ * Alg. 1 lines 2-3 with the policy of App. B.2: push the distances of the
+ * n_valid[b] verified positions of the finished block into the window, then
+ * w = softmax((1 / max(e_j, eps)) / tau_w) with e_j the window sum.  An empty
+ * window, or policy 1, gives equal weights.
+ *
+ *   dev        [B,gamma,n] fp32  in     may be NULL together with n_valid (nothing to push)
+ *   n_valid    [B]         int32 in
+ *   ring       [B,h,n]     fp32  in/out caller-owned window state (zero-initialised)
+ *   ring_head  [B]         int32 in/out next slot to overwrite
+ *   ring_count [B]         int32 in/out live slots, <= h
+ *   weights    [B,n]       fp32  out
+ */
+int tabed_update_weights(const tabed_cfg* cfg, void* ws, const float* dev, const int32_t* n_valid,
+                         float* ring, int32_t* ring_head, int32_t* ring_count, float* weights,
+                         void* stream);
+
+/*
+ * The uniforms the two calls above would draw: out[b,pos,word] for b < B,
+ * pos <= gamma, word in {0,1}.  out is [B,gamma+1,2] fp32.
+ */
+int tabed_philox_uniforms(const tabed_cfg* cfg, uint64_t round, float* out, void* stream);
+
+/*
+ * Per-kernel timing with HIP events on the launch stream.  While enabled every
+ * kernel launch is bracketed by two events; tabed_prof_read() waits for them
+ * and returns accumulated milliseconds and launch count of kernel `id`
+ * (TABED_K_*), then keeps the totals until tabed_prof_reset().  Off by default;
+ * these three calls create and destroy events and synchronise, unlike the rest.
+ */
+#define TABED_K_LMHEAD 0  /* LM-head GEMM + softmax partials    */
+#define TABED_K_SAMPLE 1  /* ensemble + draft token             */
+#define TABED_K_STATS 2   /* target statistics + distances + accept chain */
+#define TABED_K_RESID 3   /* corrected / bonus token            */
+#define TABED_K_WEIGHTS 4 /* window + weights                   */
+#define TABED_K_COUNT 5
+int tabed_prof_enable(int on);
+int tabed_prof_read(int id, double* total_ms, int64_t* launches);
+int tabed_prof_reset(void);
+const char* tabed_kernel_name(int id);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TABED_H */

@@ -1,0 +1,240 @@
+"""Thin ctypes binding of libtabed.so: same names as the C ABI in include/tabed.h, argument marshalling only.
+
+Tensors are torch CUDA (ROCm) tensors; torch is used for device memory and streams, nothing else.
+Every step of the path runs inside the library's HIP kernels.  There is no fallback: if the library has
+not been built, or a call returns an error code, this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtabed.so")
+
+EXPORTS = [
+    "tabed_workspace_bytes", "tabed_workspace_init", "tabed_strerror", "tabed_last_hip_error",
+    "tabed_draft_step", "tabed_verify", "tabed_update_weights", "tabed_philox_uniforms",
+    "tabed_prof_enable", "tabed_prof_read", "tabed_prof_reset", "tabed_kernel_name",
+]
+
+FLAG_ACCEPT_MARGIN, FLAG_SAMPLE_MARGIN, FLAG_DEGENERATE = 1, 2, 4
+K_LMHEAD, K_SAMPLE, K_STATS, K_RESID, K_WEIGHTS, K_COUNT = 0, 1, 2, 3, 4, 5
+
+
+class TabedCfg(C.Structure):
+    """Mirror of `tabed_cfg`."""
+    _fields_ = [("V", C.c_int32), ("d", C.c_int32), ("n", C.c_int32), ("B", C.c_int32),
+                ("gamma", C.c_int32), ("h", C.c_int32), ("w_dtype", C.c_int32), ("distance", C.c_int32),
+                ("policy", C.c_int32), ("tau_w", C.c_float), ("eps", C.c_float), ("seed", C.c_uint64)]
+
+
+class TabedError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def load():
+    """Load libtabed.so; raises if it has not been built (python -m paper_2601_20357_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise TabedError(f"{LIB_PATH} is missing: build it first (python paper_2601_20357_amd/build.py); "
+                         "there is no CPU fallback")
+    lib = C.CDLL(LIB_PATH)
+    vp, u64, i32 = C.c_void_p, C.c_uint64, C.c_int32
+    cfgp = C.POINTER(TabedCfg)
+    lib.tabed_workspace_bytes.restype = C.c_size_t
+    lib.tabed_workspace_bytes.argtypes = [cfgp]
+    lib.tabed_workspace_init.restype = C.c_int
+    lib.tabed_workspace_init.argtypes = [cfgp, vp, vp]
+    lib.tabed_strerror.restype = C.c_char_p
+    lib.tabed_strerror.argtypes = [C.c_int]
+    lib.tabed_last_hip_error.restype = C.c_int
+    lib.tabed_draft_step.restype = C.c_int
+    lib.tabed_draft_step.argtypes = [cfgp, vp, u64, i32] + [vp] * 11
+    lib.tabed_verify.restype = C.c_int
+    lib.tabed_verify.argtypes = [cfgp, vp, u64] + [vp] * 15
+    lib.tabed_update_weights.restype = C.c_int
+    lib.tabed_update_weights.argtypes = [cfgp, vp] + [vp] * 7
+    lib.tabed_philox_uniforms.restype = C.c_int
+    lib.tabed_philox_uniforms.argtypes = [cfgp, u64, vp, vp]
+    lib.tabed_prof_enable.restype = C.c_int
+    lib.tabed_prof_enable.argtypes = [C.c_int]
+    lib.tabed_prof_read.restype = C.c_int
+    lib.tabed_prof_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.tabed_prof_reset.restype = C.c_int
+    lib.tabed_kernel_name.restype = C.c_char_p
+    lib.tabed_kernel_name.argtypes = [C.c_int]
+    _lib = lib
+    return lib
+
+
+def make_cfg(*, V, d, n, B, gamma, h, w_dtype, distance=0, policy=0, tau_w=1.0, eps=1e-6, seed=0) -> TabedCfg:
+    return TabedCfg(V, d, n, B, gamma, h, w_dtype, distance, policy, tau_w, eps, seed)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        lib = load()
+        msg = lib.tabed_strerror(rc).decode()
+        raise TabedError(f"{what}: {msg} (code {rc}, hip error {lib.tabed_last_hip_error()})")
+
+
+def _ptr(t, dtype=None, numel=None, name="tensor"):
+    """Device pointer of a contiguous CUDA tensor (None -> NULL), with dtype / size checks."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TabedError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise TabedError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TabedError(f"{name} must be {dtype}, got {t.dtype}")
+    if numel is not None and t.numel() != numel:
+        raise TabedError(f"{name} must hold {numel} elements, got {t.numel()}")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def tabed_workspace_bytes(cfg: TabedCfg) -> int:
+    return int(load().tabed_workspace_bytes(C.byref(cfg)))
+
+
+def tabed_workspace_init(cfg: TabedCfg, ws, stream=None):
+    _check(load().tabed_workspace_init(C.byref(cfg), _ptr(ws, name="ws"), _stream(stream)), "tabed_workspace_init")
+
+
+def new_workspace(cfg: TabedCfg, device="cuda:0", stream=None):
+    """Allocate (torch) and prepare a workspace for cfg."""
+    import torch
+    nbytes = tabed_workspace_bytes(cfg)
+    if nbytes == 0:
+        raise TabedError("invalid or unsupported tabed_cfg")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    tabed_workspace_init(cfg, ws, stream)
+    return ws
+
+
+def _store_dtype(cfg):
+    import torch
+    return torch.float32 if cfg.w_dtype == 0 else torch.bfloat16
+
+
+def tabed_draft_step(cfg, ws, rnd, pos, W, H, weights, temperature, draft_logits, draft_lse, draft_tokens,
+                     draft_q, flags, u_draft=None, stream=None):
+    import torch
+    V, d, n, B, g = cfg.V, cfg.d, cfg.n, cfg.B, cfg.gamma
+    sd = _store_dtype(cfg)
+    rc = load().tabed_draft_step(
+        C.byref(cfg), _ptr(ws, torch.uint8, name="ws"), rnd, pos,
+        _ptr(W, sd, V * d, "W"), _ptr(H, sd, B * n * d, "H"),
+        _ptr(weights, torch.float32, B * n, "weights"), _ptr(temperature, torch.float32, B, "temperature"),
+        _ptr(u_draft, torch.float32, B * g, "u_draft"),
+        _ptr(draft_logits, torch.float32, g * B * n * V, "draft_logits"),
+        _ptr(draft_lse, torch.float64, g * B * n, "draft_lse"),
+        _ptr(draft_tokens, torch.int32, B * g, "draft_tokens"), _ptr(draft_q, torch.float32, B * g, "draft_q"),
+        _ptr(flags, torch.uint8, B * g, "flags"), _stream(stream))
+    _check(rc, "tabed_draft_step")
+
+
+def tabed_verify(cfg, ws, rnd, target_logits, draft_logits, draft_lse, draft_tokens, draft_q, weights, temperature,
+                 accept_len, out_tokens, dev, n_valid, flags, u_acc=None, u_res=None, stream=None):
+    import torch
+    V, n, B, g = cfg.V, cfg.n, cfg.B, cfg.gamma
+    rc = load().tabed_verify(
+        C.byref(cfg), _ptr(ws, torch.uint8, name="ws"), rnd,
+        _ptr(target_logits, torch.float32, B * (g + 1) * V, "target_logits"),
+        _ptr(draft_logits, torch.float32, g * B * n * V, "draft_logits"),
+        _ptr(draft_lse, torch.float64, g * B * n, "draft_lse"),
+        _ptr(draft_tokens, torch.int32, B * g, "draft_tokens"), _ptr(draft_q, torch.float32, B * g, "draft_q"),
+        _ptr(weights, torch.float32, B * n, "weights"), _ptr(temperature, torch.float32, B, "temperature"),
+        _ptr(u_acc, torch.float32, B * g, "u_acc"), _ptr(u_res, torch.float32, B, "u_res"),
+        _ptr(accept_len, torch.int32, B, "accept_len"), _ptr(out_tokens, torch.int32, B * (g + 1), "out_tokens"),
+        _ptr(dev, torch.float32, B * g * n, "dev"), _ptr(n_valid, torch.int32, B, "n_valid"),
+        _ptr(flags, torch.uint8, B * (g + 1), "flags"), _stream(stream))
+    _check(rc, "tabed_verify")
+
+
+def tabed_update_weights(cfg, ws, dev, n_valid, ring, ring_head, ring_count, weights, stream=None):
+    import torch
+    n, B, g, h = cfg.n, cfg.B, cfg.gamma, cfg.h
+    rc = load().tabed_update_weights(
+        C.byref(cfg), _ptr(ws, name="ws"),
+        _ptr(dev, torch.float32, B * g * n, "dev"), _ptr(n_valid, torch.int32, B, "n_valid"),
+        _ptr(ring, torch.float32, B * h * n, "ring"), _ptr(ring_head, torch.int32, B, "ring_head"),
+        _ptr(ring_count, torch.int32, B, "ring_count"), _ptr(weights, torch.float32, B * n, "weights"),
+        _stream(stream))
+    _check(rc, "tabed_update_weights")
+
+
+def tabed_philox_uniforms(cfg, rnd, out, stream=None):
+    import torch
+    rc = load().tabed_philox_uniforms(C.byref(cfg), rnd, _ptr(out, torch.float32, cfg.B * (cfg.gamma + 1) * 2, "out"),
+                                      _stream(stream))
+    _check(rc, "tabed_philox_uniforms")
+
+
+def tabed_prof_enable(on: bool):
+    _check(load().tabed_prof_enable(1 if on else 0), "tabed_prof_enable")
+
+
+def tabed_prof_reset():
+    _check(load().tabed_prof_reset(), "tabed_prof_reset")
+
+
+def tabed_prof_read(kernel_id: int):
+    """(total milliseconds, launches) of one kernel since the last reset; waits for its events."""
+    ms, cnt = C.c_double(0), C.c_int64(0)
+    _check(load().tabed_prof_read(kernel_id, C.byref(ms), C.byref(cnt)), "tabed_prof_read")
+    return ms.value, cnt.value
+
+
+def tabed_kernel_name(kernel_id: int) -> str:
+    return load().tabed_kernel_name(kernel_id).decode()
+
+
+class RoundBuffers:
+    """Device buffers one sequence batch needs across rounds (allocation only; no arithmetic here)."""
+
+    def __init__(self, cfg: TabedCfg, device="cuda:0"):
+        import torch
+        V, n, B, g, h = cfg.V, cfg.n, cfg.B, cfg.gamma, cfg.h
+        z = lambda shape, dt: torch.zeros(shape, dtype=dt, device=device)
+        self.cfg = cfg
+        self.ws = new_workspace(cfg, device)
+        self.weights = z((B, n), torch.float32)
+        self.ring = z((B, h, n), torch.float32)
+        self.ring_head = z((B,), torch.int32)
+        self.ring_count = z((B,), torch.int32)
+        self.draft_logits = z((g, B, n, V), torch.float32)
+        self.draft_lse = z((g, B, n), torch.float64)
+        self.draft_tokens = z((B, g), torch.int32)
+        self.draft_q = z((B, g), torch.float32)
+        self.draft_flags = z((B, g), torch.uint8)
+        self.accept_len = z((B,), torch.int32)
+        self.out_tokens = z((B, g + 1), torch.int32)
+        self.dev = z((B, g, n), torch.float32)
+        self.n_valid = z((B,), torch.int32)
+        self.verify_flags = z((B, g + 1), torch.uint8)
+
+    def update_weights(self, first: bool, stream=None):
+        tabed_update_weights(self.cfg, self.ws, None if first else self.dev, None if first else self.n_valid,
+                             self.ring, self.ring_head, self.ring_count, self.weights, stream)
+
+    def draft_step(self, rnd, pos, W, H, temperature, u_draft=None, stream=None):
+        tabed_draft_step(self.cfg, self.ws, rnd, pos, W, H, self.weights, temperature, self.draft_logits,
+                         self.draft_lse, self.draft_tokens, self.draft_q, self.draft_flags, u_draft, stream)
+
+    def verify(self, rnd, target_logits, temperature, u_acc=None, u_res=None, stream=None):
+        tabed_verify(self.cfg, self.ws, rnd, target_logits, self.draft_logits, self.draft_lse, self.draft_tokens,
+                     self.draft_q, self.weights, temperature, self.accept_len, self.out_tokens, self.dev,
+                     self.n_valid, self.verify_flags, u_acc, u_res, stream)

@@ -1,0 +1,227 @@
+// C ABI of the TABED hot path (see include/tabed.h): argument validation on the host, workspace
+// layout, launch sequencing, optional per-kernel event timing.  No allocation, no synchronisation,
+// except inside the tabed_prof_* calls.
+#include <mutex>
+#include <vector>
+
+#include "internal.h"
+
+namespace tabed {
+
+static thread_local int g_last_hip_error = 0;
+
+static size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+int validate_cfg(const tabed_cfg* c) {
+    if (c == nullptr) return TABED_ENULL;
+    if (c->V < 1 || c->d < 1 || c->B < 1 || c->h < 1 || c->n < 1 || c->gamma < 1) return TABED_EINVAL;
+    if (c->n > TABED_MAX_N || c->gamma > TABED_MAX_GAMMA) return TABED_ERANGE;
+    if (c->w_dtype != 0 && c->w_dtype != 1) return TABED_EINVAL;
+    if (c->w_dtype == 1 && (c->d % 8) != 0) return TABED_EINVAL;
+    if (c->distance != 0 && c->distance != 1) return TABED_EINVAL;
+    if (c->policy != 0 && c->policy != 1) return TABED_EINVAL;
+    if (!(c->tau_w > 0.f) || !(c->eps > 0.f)) return TABED_EINVAL;
+    if ((long long)c->B * c->n > (1ll << 24)) return TABED_ERANGE;
+    if (c->distance == 1) return TABED_EUNSUPPORTED;
+    return TABED_OK;
+}
+
+WsLayout ws_layout(const tabed_cfg& c) {
+    WsLayout L;
+    L.M = c.n * c.B;
+    L.NT = (c.V + kTileV - 1) / kTileV;
+    L.C2 = (c.V + kChunkV - 1) / kChunkV;
+    L.C3max = (c.V + kBlock * 4 - 1) / (kBlock * 4);
+    L.NSEG = (c.V + kSegV - 1) / kSegV;
+    L.C5 = (c.V + kChunkV - 1) / kChunkV;
+    L.RS = kStatHdr + c.n;
+    size_t off = 0;
+    L.off_tickets = off; off = align_up(off + sizeof(uint32_t) * 3 * (size_t)c.B);
+    L.off_pm = off;      off = align_up(off + sizeof(float) * (size_t)L.M * L.NT);
+    L.off_ps = off;      off = align_up(off + sizeof(float) * (size_t)L.M * L.NT);
+    L.off_cand = off;    off = align_up(off + sizeof(Top2Rec) * (size_t)c.B * L.C2);
+    L.off_stats = off;   off = align_up(off + sizeof(double) * (size_t)c.B * (c.gamma + 1) * L.C3max * L.RS);
+    L.off_lsep = off;    off = align_up(off + sizeof(double) * 2 * (size_t)c.B * (c.gamma + 1));
+    L.off_amax = off;    off = align_up(off + sizeof(int32_t) * (size_t)c.B * (c.gamma + 1));
+    L.off_seg = off;     off = align_up(off + sizeof(double) * 2 * (size_t)c.B * L.NSEG);
+    L.total = off;
+    return L;
+}
+
+// ---------------------------------------------------------------- event timing
+struct ProfRec {
+    int id;
+    hipEvent_t start, stop;
+};
+static std::mutex g_prof_mu;
+static bool g_prof_on = false;
+static std::vector<ProfRec> g_prof_pending;
+static double g_prof_ms[TABED_K_COUNT];
+static int64_t g_prof_n[TABED_K_COUNT];
+
+bool prof_on() { return g_prof_on; }
+void prof_begin(int id, hipStream_t s) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    ProfRec r;
+    r.id = id;
+    if (hipEventCreate(&r.start) != hipSuccess) return;
+    if (hipEventCreate(&r.stop) != hipSuccess) { (void)hipEventDestroy(r.start); return; }
+    (void)hipEventRecord(r.start, s);
+    g_prof_pending.push_back(r);
+}
+void prof_end(int id, hipStream_t s) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    for (size_t i = g_prof_pending.size(); i-- > 0;)
+        if (g_prof_pending[i].id == id) { (void)hipEventRecord(g_prof_pending[i].stop, s); return; }
+}
+static void prof_drain() {
+    for (ProfRec& r : g_prof_pending) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.stop) == hipSuccess && hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
+            g_prof_ms[r.id] += (double)ms;
+            g_prof_n[r.id] += 1;
+        }
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    g_prof_pending.clear();
+}
+
+static int fail_hip(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return TABED_EHIP;
+}
+static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+}  // namespace tabed
+
+using namespace tabed;
+
+extern "C" {
+
+size_t tabed_workspace_bytes(const tabed_cfg* cfg) {
+    if (validate_cfg(cfg) != TABED_OK) return 0;
+    return ws_layout(*cfg).total;
+}
+
+int tabed_workspace_init(const tabed_cfg* cfg, void* ws, void* stream) {
+    const int rc = validate_cfg(cfg);
+    if (rc != TABED_OK) return rc;
+    if (ws == nullptr) return TABED_ENULL;
+    if (misaligned(ws)) return TABED_EALIGN;
+    const hipError_t e = launch_ws_init(*cfg, ws_layout(*cfg), static_cast<char*>(ws), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? TABED_OK : fail_hip(e);
+}
+
+const char* tabed_strerror(int code) {
+    switch (code) {
+        case TABED_OK: return "ok";
+        case TABED_ENULL: return "a required pointer is NULL";
+        case TABED_EINVAL: return "a configuration field is out of range";
+        case TABED_ERANGE: return "an index or count exceeds the supported range";
+        case TABED_EALIGN: return "a base pointer is not 16-byte aligned";
+        case TABED_EUNSUPPORTED: return "valid request that this build does not implement";
+        case TABED_EHIP: return "a kernel launch failed";
+        default: return "unknown error code";
+    }
+}
+
+int tabed_last_hip_error(void) { return g_last_hip_error; }
+
+int tabed_draft_step(const tabed_cfg* cfg, void* ws, uint64_t round, int32_t pos, const void* W, const void* H,
+                     const float* weights, const float* temperature, const float* u_draft, float* draft_logits,
+                     double* draft_lse, int32_t* draft_tokens, float* draft_q, uint8_t* flags, void* stream) {
+    const int rc = validate_cfg(cfg);
+    if (rc != TABED_OK) return rc;
+    if (!ws || !W || !H || !weights || !temperature || !draft_logits || !draft_lse || !draft_tokens || !draft_q || !flags)
+        return TABED_ENULL;
+    if (pos < 0 || pos >= cfg->gamma) return TABED_ERANGE;
+    if (misaligned(ws) || misaligned(W) || misaligned(H) || misaligned(draft_logits) || misaligned(draft_lse))
+        return TABED_EALIGN;
+    const WsLayout L = ws_layout(*cfg);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float* slot = draft_logits + (size_t)pos * L.M * cfg->V;
+    hipError_t e = launch_lmhead(*cfg, L, static_cast<char*>(ws), W, H, temperature, slot, s);
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_sample(*cfg, L, static_cast<char*>(ws), round, pos, slot, weights, temperature, u_draft, draft_lse,
+                      draft_tokens, draft_q, flags, s);
+    return e == hipSuccess ? TABED_OK : fail_hip(e);
+}
+
+int tabed_verify(const tabed_cfg* cfg, void* ws, uint64_t round, const float* target_logits,
+                 const float* draft_logits, const double* draft_lse, const int32_t* draft_tokens,
+                 const float* draft_q, const float* weights, const float* temperature, const float* u_acc,
+                 const float* u_res, int32_t* accept_len, int32_t* out_tokens, float* dev, int32_t* n_valid,
+                 uint8_t* flags, void* stream) {
+    const int rc = validate_cfg(cfg);
+    if (rc != TABED_OK) return rc;
+    if (!ws || !target_logits || !draft_logits || !draft_lse || !draft_tokens || !draft_q || !weights ||
+        !temperature || !accept_len || !out_tokens || !dev || !n_valid || !flags)
+        return TABED_ENULL;
+    if (misaligned(ws) || misaligned(target_logits) || misaligned(draft_logits) || misaligned(draft_lse))
+        return TABED_EALIGN;
+    const WsLayout L = ws_layout(*cfg);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_stats(*cfg, L, static_cast<char*>(ws), round, target_logits, draft_logits, draft_lse,
+                                draft_tokens, draft_q, temperature, u_acc, accept_len, out_tokens, dev, n_valid,
+                                flags, s);
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_resid(*cfg, L, static_cast<char*>(ws), round, target_logits, draft_logits, draft_lse, weights,
+                     temperature, u_res, accept_len, out_tokens, flags, s);
+    return e == hipSuccess ? TABED_OK : fail_hip(e);
+}
+
+int tabed_update_weights(const tabed_cfg* cfg, void* ws, const float* dev, const int32_t* n_valid, float* ring,
+                         int32_t* ring_head, int32_t* ring_count, float* weights, void* stream) {
+    (void)ws;
+    const int rc = validate_cfg(cfg);
+    if (rc != TABED_OK) return rc;
+    if (!ring || !ring_head || !ring_count || !weights) return TABED_ENULL;
+    if ((dev == nullptr) != (n_valid == nullptr)) return TABED_ENULL;
+    const hipError_t e = launch_weights(*cfg, dev, n_valid, ring, ring_head, ring_count, weights,
+                                        static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? TABED_OK : fail_hip(e);
+}
+
+int tabed_philox_uniforms(const tabed_cfg* cfg, uint64_t round, float* out, void* stream) {
+    const int rc = validate_cfg(cfg);
+    if (rc != TABED_OK) return rc;
+    if (!out) return TABED_ENULL;
+    const hipError_t e = launch_philox(*cfg, round, out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? TABED_OK : fail_hip(e);
+}
+
+int tabed_prof_enable(int on) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof_on = (on != 0);
+    return TABED_OK;
+}
+
+int tabed_prof_read(int id, double* total_ms, int64_t* launches) {
+    if (id < 0 || id >= TABED_K_COUNT) return TABED_ERANGE;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    prof_drain();
+    if (total_ms) *total_ms = g_prof_ms[id];
+    if (launches) *launches = g_prof_n[id];
+    return TABED_OK;
+}
+
+int tabed_prof_reset(void) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    prof_drain();
+    for (int i = 0; i < TABED_K_COUNT; ++i) { g_prof_ms[i] = 0.0; g_prof_n[i] = 0; }
+    return TABED_OK;
+}
+
+const char* tabed_kernel_name(int id) {
+    switch (id) {
+        case TABED_K_LMHEAD: return "lmhead";
+        case TABED_K_SAMPLE: return "sample";
+        case TABED_K_STATS: return "stats";
+        case TABED_K_RESID: return "resid";
+        case TABED_K_WEIGHTS: return "weights";
+        default: return "?";
+    }
+}
+
+}  // extern "C"

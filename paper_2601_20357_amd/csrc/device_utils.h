@@ -1,0 +1,160 @@
+// Device-side helpers shared by the TABED kernels: wave64 / workgroup reductions,
+// Philox4x32-10, guarded vector loads.  gfx950 only (wavefront = 64 lanes).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "internal.h"
+
+namespace tabed {
+
+constexpr float kMargin = 1e-6f;        // decisions closer than this (relative) are flagged
+
+// ---------------------------------------------------------------- wave64 butterflies (deterministic order)
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// Workgroup reductions over kBlock threads through a 4-entry LDS array.  Two barriers each, so the
+// scratch array can be reused by the next call.
+__device__ __forceinline__ float block_max(float v, float* lds4) {
+    v = wave_max(v);
+    if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = fmaxf(fmaxf(lds4[0], lds4[1]), fmaxf(lds4[2], lds4[3]));
+    __syncthreads();
+    return r;
+}
+__device__ __forceinline__ double block_sum(double v, double* lds4) {
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double r = (lds4[0] + lds4[1]) + (lds4[2] + lds4[3]);
+    __syncthreads();
+    return r;
+}
+
+// Inclusive prefix sum across the 64 lanes of a wave (Hillis-Steele, fixed order).
+__device__ __forceinline__ double wave_inclusive_scan(double v) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        double up = __shfl_up(v, o);
+        if (lane >= o) v += up;
+    }
+    return v;
+}
+
+// Exclusive prefix of one value per thread over the whole workgroup, in thread order; *total = sum.
+__device__ __forceinline__ double block_exclusive_scan(double v, double* lds4, double* total) {
+    double inc = wave_inclusive_scan(v);
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    if (lane == 63) lds4[w] = inc;
+    __syncthreads();
+    double base = 0.0;
+    for (int i = 0; i < w; ++i) base += lds4[i];
+    *total = ((lds4[0] + lds4[1]) + lds4[2]) + lds4[3];
+    __syncthreads();
+    return base + inc - v;
+}
+
+// ---------------------------------------------------------------- arg-max with runner-up
+struct Top2 {
+    float v1;  // maximum
+    int i1;    // its lowest index
+    float v2;  // largest value among all other elements
+};
+__device__ __forceinline__ Top2 top2_empty() { return Top2{-INFINITY, 0x7fffffff, -INFINITY}; }
+__device__ __forceinline__ Top2 top2_merge(const Top2& a, const Top2& b) {
+    const bool b_wins = (b.v1 > a.v1) || (b.v1 == a.v1 && b.i1 < a.i1);
+    Top2 r;
+    if (b_wins) { r.v1 = b.v1; r.i1 = b.i1; r.v2 = fmaxf(a.v1, b.v2); }
+    else        { r.v1 = a.v1; r.i1 = a.i1; r.v2 = fmaxf(a.v2, b.v1); }
+    return r;
+}
+__device__ __forceinline__ Top2 top2_push(const Top2& a, float x, int idx) {
+    return top2_merge(a, Top2{x, idx, -INFINITY});
+}
+__device__ __forceinline__ Top2 wave_top2(Top2 t) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        Top2 other{__shfl_xor(t.v1, o), __shfl_xor(t.i1, o), __shfl_xor(t.v2, o)};
+        t = top2_merge(t, other);
+    }
+    return t;
+}
+
+// Plain (value, lowest index) arg-max.
+struct ArgMax {
+    float v;
+    int i;
+};
+__device__ __forceinline__ ArgMax argmax_merge(const ArgMax& a, const ArgMax& b) {
+    return ((b.v > a.v) || (b.v == a.v && b.i < a.i)) ? b : a;
+}
+__device__ __forceinline__ ArgMax wave_argmax(ArgMax t) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        ArgMax other{__shfl_xor(t.v, o), __shfl_xor(t.i, o)};
+        t = argmax_merge(t, other);
+    }
+    return t;
+}
+
+// ---------------------------------------------------------------- Philox4x32-10 (Salmon et al., SC'11)
+struct U4 {
+    uint32_t x, y, z, w;
+};
+__device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                             uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    return U4{c0, c1, c2, c3};
+}
+__device__ __forceinline__ float u01(uint32_t x) { return (float)(x >> 8) * (1.0f / 16777216.0f); }
+
+// Uniform of (seed, round, b, pos): word 0 or 1 of the Philox block.
+__device__ __forceinline__ float tabed_uniform(uint64_t seed, uint64_t round, uint32_t b, uint32_t pos, int word) {
+    U4 r = philox4x32_10((uint32_t)round, (uint32_t)(round >> 32), b, pos, (uint32_t)seed, (uint32_t)(seed >> 32));
+    return u01(word == 0 ? r.x : r.y);
+}
+
+// ---------------------------------------------------------------- guarded row loads
+// Four consecutive logits starting at element v (v % 4 == 0) of a row of V floats; elements past the end
+// of the row come back as -inf.  VEC needs V % 4 == 0 and a 16-byte aligned row.
+template <bool VEC>
+__device__ __forceinline__ float4 load4(const float* __restrict__ row, int v, int V) {
+    const float ninf = -INFINITY;
+    if (VEC) {
+        if (v < V) return *reinterpret_cast<const float4*>(row + v);
+        return make_float4(ninf, ninf, ninf, ninf);
+    }
+    float4 r;
+    r.x = (v + 0 < V) ? row[v + 0] : ninf;
+    r.y = (v + 1 < V) ? row[v + 1] : ninf;
+    r.z = (v + 2 < V) ? row[v + 2] : ninf;
+    r.w = (v + 3 < V) ? row[v + 3] : ninf;
+    return r;
+}
+
+__device__ __forceinline__ float f4get(const float4& a, int e) { return e == 0 ? a.x : e == 1 ? a.y : e == 2 ? a.z : a.w; }
+
+}  // namespace tabed

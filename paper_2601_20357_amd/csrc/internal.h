@@ -1,0 +1,82 @@
+// Host-side plumbing shared by the TABED translation units: workspace layout, launcher prototypes,
+// per-kernel event timing.  Not part of the public ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/tabed.h"
+
+namespace tabed {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;     // every vocab-pass kernel runs 4 waves per workgroup
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kTileV = 32;      // width of one softmax-partial tile written by the LM-head epilogue
+constexpr int kSegV = 256;      // width of one CDF segment of the corrected/bonus sampler (one wave x float4)
+constexpr int kChunkV = 4096;   // vocabulary span of one workgroup in the full-row passes (256 threads x 4 float4)
+constexpr int kStatHdr = 4;     // doubles before the per-draft sums in a chunk record: max, Z, argmax value, argmax index
+
+struct Top2Rec {                // chunk candidate of the greedy draft arg-max
+    float v1;
+    int i1;
+    float v2;
+    int pad;
+};
+
+// Where everything lives inside the caller's workspace (byte offsets, 256-byte aligned).
+struct WsLayout {
+    int M, NT, C2, C3max, NSEG, C5, RS;
+    size_t off_tickets;  // uint32 [3][B]: arrival counters of sample / stats / resid kernels
+    size_t off_pm;       // float  [M][NT] tile maxima of scaled logits
+    size_t off_ps;       // float  [M][NT] tile sums of exp(scaled logit - tile max)
+    size_t off_cand;     // Top2Rec [B][C2]
+    size_t off_stats;    // double [B][gamma+1][C3max][RS]
+    size_t off_lsep;     // double [B][gamma+1] log-sum-exp of scaled target rows
+    size_t off_amax;     // int32  [B][gamma+1] arg-max of target rows
+    size_t off_seg;      // double [B][2][NSEG] segment masses: residual, target
+    size_t total;
+};
+WsLayout ws_layout(const tabed_cfg& c);
+int validate_cfg(const tabed_cfg* c);
+
+// ---------------------------------------------------------------- launchers (each enqueues on `s`)
+hipError_t launch_ws_init(const tabed_cfg& c, const WsLayout& L, char* ws, hipStream_t s);
+
+hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& L, char* ws, const void* W, const void* H,
+                         const float* temperature, float* logits /* slot pos: [M,V] */, hipStream_t s);
+
+hipError_t launch_sample(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round, int pos,
+                         const float* logits /* slot pos */, const float* weights, const float* temperature,
+                         const float* u_draft, double* draft_lse, int32_t* draft_tokens, float* draft_q,
+                         uint8_t* flags, hipStream_t s);
+
+hipError_t launch_stats(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round,
+                        const float* target_logits, const float* draft_logits, const double* draft_lse,
+                        const int32_t* draft_tokens, const float* draft_q, const float* temperature,
+                        const float* u_acc, int32_t* accept_len, int32_t* out_tokens, float* dev,
+                        int32_t* n_valid, uint8_t* flags, hipStream_t s);
+
+hipError_t launch_resid(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round,
+                        const float* target_logits, const float* draft_logits, const double* draft_lse,
+                        const float* weights, const float* temperature, const float* u_res,
+                        const int32_t* accept_len, int32_t* out_tokens, uint8_t* flags, hipStream_t s);
+
+hipError_t launch_weights(const tabed_cfg& c, const float* dev, const int32_t* n_valid, float* ring,
+                          int32_t* ring_head, int32_t* ring_count, float* weights, hipStream_t s);
+
+hipError_t launch_philox(const tabed_cfg& c, uint64_t round, float* out, hipStream_t s);
+
+// ---------------------------------------------------------------- event timing
+bool prof_on();
+void prof_begin(int id, hipStream_t s);
+void prof_end(int id, hipStream_t s);
+struct ProfScope {
+    int id;
+    hipStream_t s;
+    bool on;
+    ProfScope(int id_, hipStream_t s_) : id(id_), s(s_), on(prof_on()) { if (on) prof_begin(id, s); }
+    ~ProfScope() { if (on) prof_end(id, s); }
+};
+
+}  // namespace tabed

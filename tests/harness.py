@@ -1,0 +1,183 @@
+"""Shared machinery of the GPU parity tests: run SD rounds through the C ABI (via the binding) and through
+the CPU oracle on the same seeded inputs, and compare element by element.
+
+Tolerances (derived in the repository's design notes):
+  logits        |dL| <= 1e-5 * max|L|   (exact bf16 products, fp32 MFMA accumulation vs fp64)  and <= 2e-2 (budget)
+  lse           |d| <= 2e-6
+  q(y), p       relative 1e-5
+  dev (KL)      |d| <= 1e-5 * |dev| + 1e-6
+  weights       |d| <= 1e-5 * w + 1e-6   (end to end; the isolated kernel is tested to 1e-6 relative)
+  integers      bit-exact unless the decision that produced them is flagged (margin < 1e-6) on either side
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2601_20357_amd import binding, synth
+
+DEV = "cuda:0"
+
+
+def to_dev_store(x: np.ndarray, w_dtype: int) -> torch.Tensor:
+    """Storage array (fp32 or bf16 bit patterns) -> device tensor of the matching torch dtype."""
+    if w_dtype == 0:
+        return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(DEV)
+    return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def cfg_of(wl: synth.Workload, seed=0, policy=0, tau_w=1.0, eps=1e-6):
+    return binding.make_cfg(V=wl.V, d=wl.d, n=wl.n, B=wl.B, gamma=wl.gamma, h=wl.h, w_dtype=wl.w_dtype,
+                            policy=policy, tau_w=tau_w, eps=eps, seed=seed)
+
+
+class OracleSide:
+    def __init__(self, oracle, wl, seed=0, policy=0, tau_w=1.0, eps=1e-6):
+        self.o, self.wl, self.seed, self.policy, self.tau_w, self.eps = oracle, wl, seed, policy, tau_w, eps
+        B, n, g, h, V = wl.B, wl.n, wl.gamma, wl.h, wl.V
+        self.ring = np.zeros((B, h, n), np.float32)
+        self.head = np.zeros(B, np.int32)
+        self.count = np.zeros(B, np.int32)
+        self.dev = None
+        self.n_valid = None
+
+    def round(self, rnd, W, H, target, temp, u_draft=None, u_acc=None, u_res=None):
+        wl, o = self.wl, self.o
+        B, n, g, V = wl.B, wl.n, wl.gamma, wl.V
+        w = o.update_weights(n=n, B=B, gamma=g, h=wl.h, policy=self.policy, tau_w=self.tau_w, eps=self.eps,
+                             dev=self.dev, n_valid=self.n_valid, ring=self.ring, ring_head=self.head,
+                             ring_count=self.count)
+        dl = np.zeros((g, B, n, V), np.float32)
+        lse = np.zeros((g, B, n), np.float64)
+        tok = np.zeros((B, g), np.int32)
+        dq = np.zeros((B, g), np.float32)
+        fl = np.zeros((B, g), np.uint8)
+        for pos in range(g):
+            o.draft_step(V=V, d=wl.d, n=n, B=B, gamma=g, w_dtype=wl.w_dtype, seed=self.seed, rnd=rnd, pos=pos, W=W,
+                         H=H[pos], weights=w, temperature=temp, draft_logits=dl, draft_lse=lse, draft_tokens=tok,
+                         draft_q=dq, flags=fl, u_draft=u_draft)
+        out = o.verify(V=V, n=n, B=B, gamma=g, distance=0, seed=self.seed, rnd=rnd, target_logits=target,
+                       draft_logits=dl, draft_tokens=tok, draft_q=dq, weights=w, temperature=temp, u_acc=u_acc,
+                       u_res=u_res)
+        self.dev, self.n_valid = out["dev"], out["n_valid"]
+        out.update(weights=w, draft_logits=dl, draft_lse=lse, draft_tokens=tok, draft_q=dq, draft_flags=fl)
+        return out
+
+
+class GpuSide:
+    def __init__(self, wl, seed=0, policy=0, tau_w=1.0, eps=1e-6):
+        self.wl = wl
+        self.cfg = cfg_of(wl, seed, policy, tau_w, eps)
+        self.buf = binding.RoundBuffers(self.cfg, DEV)
+        self.first = True
+
+    def round(self, rnd, W_t, H, target, temp, u_draft=None, u_acc=None, u_res=None):
+        wl, buf = self.wl, self.buf
+        t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV)
+        temp_t, tgt_t = t(temp), t(target)
+        ud, ua, ur = t(u_draft), t(u_acc), t(u_res)
+        buf.update_weights(self.first)
+        self.first = False
+        for pos in range(wl.gamma):
+            buf.draft_step(rnd, pos, W_t, to_dev_store(H[pos], wl.w_dtype), temp_t, ud)
+        buf.verify(rnd, tgt_t, temp_t, ua, ur)
+        torch.cuda.synchronize()
+        c = lambda x: x.cpu().numpy()
+        return dict(weights=c(buf.weights), draft_logits=c(buf.draft_logits), draft_lse=c(buf.draft_lse),
+                    draft_tokens=c(buf.draft_tokens), draft_q=c(buf.draft_q), draft_flags=c(buf.draft_flags),
+                    accept_len=c(buf.accept_len), out_tokens=c(buf.out_tokens), dev=c(buf.dev),
+                    n_valid=c(buf.n_valid), flags=c(buf.verify_flags))
+
+    def resync_from(self, orc: OracleSide):
+        """After a flagged divergence: continue from the oracle's window state (HIP input <- oracle is allowed)."""
+        self.buf.ring.copy_(torch.from_numpy(orc.ring).to(DEV))
+        self.buf.ring_head.copy_(torch.from_numpy(orc.head).to(DEV))
+        self.buf.ring_count.copy_(torch.from_numpy(orc.count).to(DEV))
+        self.buf.dev.copy_(torch.from_numpy(orc.dev).to(DEV))
+        self.buf.n_valid.copy_(torch.from_numpy(orc.n_valid).to(DEV))
+
+
+class Tally:
+    def __init__(self):
+        self.decisions = 0
+        self.flagged_divergences = 0
+        self.max_logit_err = 0.0
+        self.max_q_rel = 0.0
+        self.max_dev_err = 0.0
+        self.max_w_err = 0.0
+
+    def __repr__(self):
+        return (f"decisions={self.decisions} flagged_divergences={self.flagged_divergences} "
+                f"max|dL|={self.max_logit_err:.2e} max rel dq={self.max_q_rel:.2e} "
+                f"max|ddev|={self.max_dev_err:.2e} max|dw|={self.max_w_err:.2e}")
+
+
+def compare_round(g, o, wl, tally: Tally, check_logits=True):
+    """Element-by-element comparison of one round.  Returns True if every sequence stayed in lock-step;
+    False if a flagged decision diverged (the caller then resyncs the window state)."""
+    B, n, gamma = wl.B, wl.n, wl.gamma
+    np.testing.assert_allclose(g["weights"], o["weights"], rtol=1e-5, atol=1e-6)
+    tally.max_w_err = max(tally.max_w_err, float(np.max(np.abs(g["weights"] - o["weights"]))))
+    if check_logits:
+        scale = float(np.max(np.abs(o["draft_logits"])))
+        err = float(np.max(np.abs(g["draft_logits"] - o["draft_logits"])))
+        tally.max_logit_err = max(tally.max_logit_err, err)
+        assert err <= 1e-5 * max(scale, 1.0) and err <= 2e-2, (err, scale)
+    np.testing.assert_allclose(g["draft_lse"], o["draft_lse"], rtol=0, atol=2e-6)
+    lock = True
+    for b in range(B):
+        alive = True      # this sequence still comparable in this round
+        for pos in range(gamma):
+            tally.decisions += 1
+            if g["draft_tokens"][b, pos] != o["draft_tokens"][b, pos]:
+                flagged = (g["draft_flags"][b, pos] | o["draft_flags"][b, pos]) & binding.FLAG_SAMPLE_MARGIN
+                assert flagged, f"unflagged draft token mismatch b={b} pos={pos}: {g['draft_tokens'][b]} vs {o['draft_tokens'][b]}"
+                tally.flagged_divergences += 1
+                alive = False
+                break
+            rel = abs(float(g["draft_q"][b, pos]) - float(o["draft_q"][b, pos])) / max(float(o["draft_q"][b, pos]), 1e-30)
+            tally.max_q_rel = max(tally.max_q_rel, rel)
+            assert rel <= 1e-5, (b, pos, g["draft_q"][b, pos], o["draft_q"][b, pos])
+        # distances do not depend on any decision: always comparable
+        d_g, d_o = g["dev"][b], o["dev"][b]
+        derr = np.abs(d_g - d_o)
+        tally.max_dev_err = max(tally.max_dev_err, float(derr.max()))
+        assert np.all(derr <= 1e-5 * np.abs(d_o) + 1e-6), (b, d_g, d_o)
+        if not alive:
+            lock = False
+            continue
+        tally.decisions += 1
+        kg, ko = int(g["accept_len"][b]), int(o["accept_len"][b])
+        if kg != ko:
+            i = min(kg, ko)
+            flagged = (g["flags"][b, i] | o["flags"][b, i]) & binding.FLAG_ACCEPT_MARGIN
+            assert flagged, f"unflagged accept-length mismatch b={b}: {kg} vs {ko}"
+            tally.flagged_divergences += 1
+            lock = False
+            continue
+        assert g["n_valid"][b] == o["n_valid"][b] == min(ko + 1, gamma)
+        assert np.array_equal(g["out_tokens"][b, :ko], o["out_tokens"][b, :ko])
+        assert np.all(g["out_tokens"][b, ko + 1:] == -1)
+        tally.decisions += 1
+        if g["out_tokens"][b, ko] != o["out_tokens"][b, ko]:
+            flagged = (g["flags"][b, ko] | o["flags"][b, ko]) & binding.FLAG_SAMPLE_MARGIN
+            assert flagged, f"unflagged emitted-token mismatch b={b} k={ko}: {g['out_tokens'][b]} vs {o['out_tokens'][b]}"
+            tally.flagged_divergences += 1
+            # the emitted token does not enter the window state: still in lock-step
+    return lock
+
+
+def run_rounds(oracle, wl, rounds, temp, seed=0, policy=0, check_logits=True, uniforms=None, W=None):
+    """Drive both sides for `rounds` rounds with state carried over; returns the tally."""
+    W = synth.make_lm_head(wl) if W is None else W
+    W_t = to_dev_store(W, wl.w_dtype)
+    orc, gpu = OracleSide(oracle, wl, seed, policy), GpuSide(wl, seed, policy)
+    tally = Tally()
+    for rnd in range(rounds):
+        H, target = synth.make_round(wl, W, rnd)
+        u = uniforms(rnd) if uniforms else {}
+        o = orc.round(rnd, W, H, target, temp, **u)
+        g = gpu.round(rnd, W_t, H, target, temp, **u)
+        if not compare_round(g, o, wl, tally, check_logits):
+            gpu.resync_from(orc)
+    return tally

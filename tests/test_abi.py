@@ -1,0 +1,98 @@
+"""CPU-side checks of the boundary: the library loads, exports every symbol the public header declares,
+and rejects bad arguments on the host before anything is enqueued (no GPU is touched here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2601_20357_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "tabed.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2601_20357_amd import build
+        build.build_library()
+    return binding.load()
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(tabed_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_three_calls():
+    names = declared_functions()
+    for must in ("tabed_draft_step", "tabed_update_weights", "tabed_verify", "tabed_workspace_bytes"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} declared in include/tabed.h but not exported by libtabed.so"
+    assert sorted(binding.EXPORTS) == declared_functions()
+
+
+def test_cfg_struct_matches_header_field_order():
+    text = open(HEADER).read()
+    body = re.search(r"typedef struct tabed_cfg \{(.*?)\} tabed_cfg;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"\b(?:int32_t|float|uint64_t)\s+([A-Za-z_]+);", body)
+    assert fields == [f[0] for f in binding.TabedCfg._fields_]
+    assert C.sizeof(binding.TabedCfg) == 9 * 4 + 2 * 4 + 4 + 8      # 4 bytes of padding before the 64-bit seed
+
+
+def good_cfg(**kw):
+    base = dict(V=32000, d=768, n=4, B=16, gamma=5, h=8, w_dtype=1)
+    base.update(kw)
+    return binding.make_cfg(**base)
+
+
+def test_workspace_bytes_and_cfg_validation(lib):
+    assert binding.tabed_workspace_bytes(good_cfg()) > 2 * 64 * 1000 * 4
+    assert binding.tabed_workspace_bytes(good_cfg(V=1, d=8, n=1, B=1, gamma=1, h=1)) > 0
+    for bad in (dict(V=0), dict(n=0), dict(n=17), dict(gamma=0), dict(gamma=33), dict(h=0), dict(B=0),
+                dict(d=100), dict(w_dtype=2), dict(tau_w=0.0), dict(eps=0.0), dict(policy=5), dict(distance=7)):
+        assert binding.tabed_workspace_bytes(good_cfg(**bad)) == 0, bad
+    assert binding.tabed_workspace_bytes(good_cfg(d=100, w_dtype=0)) > 0      # fp32 storage has no d % 8 rule
+    assert binding.tabed_workspace_bytes(good_cfg(V=32001)) > 0               # ragged vocabularies are fine
+
+
+def test_error_codes_are_returned_before_any_launch(lib):
+    cfg = good_cfg()
+    fake = C.c_void_p(0x1000)          # 16-byte aligned, never dereferenced on the host
+    odd = C.c_void_p(0x1008)
+    # NULL pointers
+    rc = lib.tabed_draft_step(C.byref(cfg), None, 0, 0, *([fake] * 10), None)
+    assert rc == -1
+    rc = lib.tabed_verify(C.byref(cfg), fake, 0, None, *([fake] * 14), None)
+    assert rc == -1
+    rc = lib.tabed_update_weights(C.byref(cfg), fake, fake, None, fake, fake, fake, fake, None)
+    assert rc == -1                     # dev without n_valid
+    # position outside the block
+    args = [fake] * 4 + [None] + [fake] * 5
+    assert lib.tabed_draft_step(C.byref(cfg), fake, 0, 5, *args, None) == -3
+    assert lib.tabed_draft_step(C.byref(cfg), fake, 0, -1, *args, None) == -3
+    # misaligned base pointer
+    args = [odd] + [fake] * 3 + [None] + [fake] * 5
+    assert lib.tabed_draft_step(C.byref(cfg), fake, 0, 0, *args, None) == -4
+    # invalid / unsupported configuration
+    assert lib.tabed_draft_step(C.byref(good_cfg(n=99)), fake, 0, 0, *([fake] * 10), None) == -3
+    assert lib.tabed_draft_step(C.byref(good_cfg(V=-4)), fake, 0, 0, *([fake] * 10), None) == -2
+    assert lib.tabed_verify(C.byref(good_cfg(distance=1)), fake, 0, *([fake] * 15), None) == -5
+    assert lib.tabed_workspace_init(C.byref(cfg), None, None) == -1
+    for code in (0, -1, -2, -3, -4, -5, -6):
+        assert lib.tabed_strerror(code).decode() not in ("", "unknown error code")
+    assert lib.tabed_strerror(-99).decode() == "unknown error code"
+    assert [binding.tabed_kernel_name(i) for i in range(binding.K_COUNT)] == ["lmhead", "sample", "stats", "resid", "weights"]
+
+
+def test_binding_refuses_host_tensors(lib):
+    import torch
+    cfg = good_cfg(V=8, d=8, n=1, B=1, gamma=1, h=1, w_dtype=0)
+    with pytest.raises(binding.TabedError):
+        binding.tabed_philox_uniforms(cfg, 0, torch.zeros(4))

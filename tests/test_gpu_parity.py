@@ -1,0 +1,170 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_20357_amd import binding, synth
+
+import harness
+from harness import DEV
+
+pytestmark = pytest.mark.gpu
+
+TINY = synth.WORKLOADS["tiny"]
+SERVING = synth.WORKLOADS["serving"]
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ Philox: two implementations, same bits
+def test_philox_uniforms_bit_equal_to_oracle(oracle):
+    cfg = binding.make_cfg(V=8, d=8, n=1, B=64, gamma=15, h=1, w_dtype=0, seed=0x123456789ABCDEF)
+    out = torch.zeros((64, 16, 2), dtype=torch.float32, device=DEV)
+    for rnd in (0, 1, 77, (1 << 40) + 5):
+        binding.tabed_philox_uniforms(cfg, rnd, out)
+        got = out.cpu().numpy()
+        ref = np.array([[[oracle.uniform(cfg.seed, rnd, b, p, w) for w in (0, 1)] for p in range(16)] for b in range(64)],
+                       dtype=np.float32)
+        assert np.array_equal(got, ref)
+
+
+# ------------------------------------------------------------------ the paper-scale tiny configuration, 64 rounds
+@pytest.mark.parametrize("mode", ["greedy", "one"])
+def test_tiny_64_rounds_state_carried(oracle, mode):
+    _say(f"tiny {mode}")
+    tally = harness.run_rounds(oracle, TINY, TINY.rounds, synth.make_temperature(TINY, mode))
+    _say(tally)
+    assert tally.flagged_divergences <= 2
+
+
+# ------------------------------------------------------------------ shapes that span several tiles with ragged tails
+SHAPES = [
+    # V,     d,   n, B, gamma, h, w_dtype, temperature
+    (1000,   64,  2, 3, 3,     4, 1, "one"),        # bf16, V not a multiple of 64
+    (4099,   72,  3, 5, 4,     5, 1, "mixed07"),    # V % 4 != 0: scalar loads; d not a multiple of 64
+    (8200,   128, 4, 2, 2,     3, 1, "greedy"),     # two full 4096-chunks and an 8-element tail
+    (33,     8,   1, 1, 1,     1, 1, "one"),        # one draft, one token
+    (257,    40,  16, 2, 2,    2, 0, "one"),        # maximum number of drafts, fp32 storage
+    (5000,   64,  5, 70, 2,    3, 1, "mixed07"),    # more rows than one 64-row MFMA tile
+    (1,      8,   2, 2, 2,     2, 0, "one"),        # single-token vocabulary
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: f"V{s[0]}d{s[1]}n{s[2]}B{s[3]}g{s[4]}")
+def test_shapes_and_edges(oracle, shape):
+    V, d, n, B, gamma, h, w_dtype, mode = shape
+    _say(f"shape {shape}")
+    wl = synth.scaled(SERVING, V=V, d=d, n=n, B=B, gamma=gamma, h=h, w_dtype=w_dtype, cfg_id=40 + V % 7)
+    tally = harness.run_rounds(oracle, wl, 6, synth.make_temperature(wl, mode))
+    _say(tally)
+    assert tally.flagged_divergences <= max(2, tally.decisions // 50)
+
+
+def test_static_policy_and_other_tau(oracle):
+    wl = synth.scaled(SERVING, V=2048, d=64, B=4, cfg_id=51)
+    t = harness.run_rounds(oracle, wl, 4, synth.make_temperature(wl, "one"), policy=1)
+    assert t.max_w_err == 0.0
+
+
+# ------------------------------------------------------------------ explicit uniforms, including the edges of [0,1)
+def test_explicit_uniform_edges(oracle):
+    wl = synth.scaled(SERVING, V=3000, d=64, n=3, B=8, gamma=3, h=4, cfg_id=52)
+    edge = np.array([0.0, 1 - 2.0 ** -24, 0.5, 0.25, 2.0 ** -24, 0.75, 0.999, 0.001], np.float32)
+
+    def uniforms(rnd):
+        return dict(u_draft=np.tile(np.roll(edge, rnd)[:, None], (1, wl.gamma)),
+                    u_acc=np.tile(np.roll(edge, rnd + 3)[:, None], (1, wl.gamma)),
+                    u_res=np.roll(edge, rnd + 5).copy())
+    tally = harness.run_rounds(oracle, wl, 8, synth.make_temperature(wl, "one"), uniforms=uniforms)
+    _say(tally)
+
+
+def test_identical_draft_and_target_always_accepts(oracle):
+    """n = 1 and target logits equal to the draft's: p == q, every token accepted, bonus token emitted."""
+    wl = synth.scaled(SERVING, V=2000, d=64, n=1, B=4, gamma=4, h=4, cfg_id=53, target="draft0", sigma=0.0)
+    W = synth.make_lm_head(wl)
+    gpu = harness.GpuSide(wl)
+    H, target = synth.make_round(wl, W, 0)
+    g = gpu.round(0, harness.to_dev_store(W, wl.w_dtype), H, target, synth.make_temperature(wl, "one"))
+    # the recipe's matmul and the kernel's differ in the last bits, so p/q is 1 +- 1e-6: accepted unless u ~ 1
+    assert np.all(g["accept_len"] == wl.gamma)
+    assert np.all(g["out_tokens"] >= 0)
+    assert np.all(g["dev"] < 1e-6)
+
+
+def test_out_of_range_draft_token_is_rejected_not_dereferenced(oracle):
+    wl = synth.scaled(SERVING, V=1500, d=64, n=2, B=3, gamma=3, h=4, cfg_id=54)
+    W = synth.make_lm_head(wl)
+    gpu = harness.GpuSide(wl)
+    temp = synth.make_temperature(wl, "one")
+    H, target = synth.make_round(wl, W, 0)
+    gpu.round(0, harness.to_dev_store(W, wl.w_dtype), H, target, temp)
+    buf = gpu.buf
+    buf.draft_tokens[1, 0] = wl.V + 12345
+    buf.draft_tokens[2, 1] = -7
+    buf.verify(0, torch.from_numpy(target).to(DEV), torch.from_numpy(temp).to(DEV))
+    torch.cuda.synchronize()
+    assert buf.accept_len[1].item() == 0 and buf.verify_flags[1, 0].item() & binding.FLAG_DEGENERATE
+    assert buf.accept_len[2].item() <= 1
+    assert 0 <= buf.out_tokens[1, 0].item() < wl.V
+
+
+# ------------------------------------------------------------------ the window / weights kernel alone
+def test_update_weights_alone_matches_oracle_bitwise_state(oracle):
+    rng = np.random.default_rng(60)
+    B, n, gamma, h = 37, 7, 5, 6
+    cfg = binding.make_cfg(V=8, d=8, n=n, B=B, gamma=gamma, h=h, w_dtype=0, tau_w=0.5, eps=1e-6)
+    ws = binding.new_workspace(cfg)
+    ring = torch.zeros((B, h, n), device=DEV); head = torch.zeros(B, dtype=torch.int32, device=DEV)
+    count = torch.zeros(B, dtype=torch.int32, device=DEV); w = torch.zeros((B, n), device=DEV)
+    o_ring = np.zeros((B, h, n), np.float32); o_head = np.zeros(B, np.int32); o_count = np.zeros(B, np.int32)
+    for step in range(12):
+        dev = (rng.random((B, gamma, n)) * (10.0 ** rng.uniform(-4, 0.5, (B, 1, 1)))).astype(np.float32)
+        nv = rng.integers(1, gamma + 1, B).astype(np.int32)
+        if step == 0:
+            binding.tabed_update_weights(cfg, ws, None, None, ring, head, count, w)
+            ow = oracle.update_weights(n=n, B=B, gamma=gamma, h=h, policy=0, tau_w=0.5, eps=1e-6, dev=None,
+                                       n_valid=None, ring=o_ring, ring_head=o_head, ring_count=o_count)
+        else:
+            binding.tabed_update_weights(cfg, ws, torch.from_numpy(dev).to(DEV), torch.from_numpy(nv).to(DEV),
+                                         ring, head, count, w)
+            ow = oracle.update_weights(n=n, B=B, gamma=gamma, h=h, policy=0, tau_w=0.5, eps=1e-6, dev=dev,
+                                       n_valid=nv, ring=o_ring, ring_head=o_head, ring_count=o_count)
+        torch.cuda.synchronize()
+        assert np.array_equal(ring.cpu().numpy(), o_ring)
+        assert np.array_equal(head.cpu().numpy(), o_head) and np.array_equal(count.cpu().numpy(), o_count)
+        np.testing.assert_allclose(w.cpu().numpy(), ow, rtol=1e-6, atol=1e-30)
+
+
+# ------------------------------------------------------------------ determinism: same call, same bits
+def test_two_runs_are_bitwise_identical(oracle):
+    wl = synth.scaled(SERVING, V=32000, B=4, cfg_id=55)
+    W = synth.make_lm_head(wl)
+    W_t = harness.to_dev_store(W, wl.w_dtype)
+    temp = synth.make_temperature(wl, "mixed07")
+    H, target = synth.make_round(wl, W, 0)
+    outs = []
+    for _ in range(2):
+        gpu = harness.GpuSide(wl)
+        outs.append(gpu.round(0, W_t, H, target, temp))
+    for key in outs[0]:
+        assert np.array_equal(outs[0][key], outs[1][key]), key
+
+
+# ------------------------------------------------------------------ full size, in the launch configuration bench.py times
+def test_serving_full_size_rounds(oracle):
+    _say("serving full size")
+    tally = harness.run_rounds(oracle, SERVING, 3, synth.make_temperature(SERVING))
+    _say(tally)
+    assert tally.flagged_divergences <= 4
+
+
+def test_llava_full_size_greedy_and_sampling(oracle):
+    wl = synth.WORKLOADS["llava"]
+    for mode in ("greedy", "one"):
+        _say(f"llava {mode}")
+        tally = harness.run_rounds(oracle, wl, 4, synth.make_temperature(wl, mode))
+        _say(tally)
+        assert tally.flagged_divergences <= 2
