@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the TABED hot path on one MI355X.
+
+One step = one speculative-decoding round for all B sequences: tabed_update_weights, gamma x
+tabed_draft_step, tabed_verify -- called through the C ABI exactly as a serving loop would.  The workload
+is the batched-serving configuration the headline metric is quoted on (V=32000, d=768, n=4, B=16, gamma=5,
+h=8, temperature 1); inputs are seeded and synthetic, generated on the GPU before the timed region and
+resident in HBM.  The LM-head matrix is rotated over several device copies between rounds so that it is
+streamed from HBM the way it would be after the target model's forward pass evicted it.
+
+Prints ONE JSON line: the whole-job rate, the roofline of the dominant kernel (measured with HIP events on
+the launch stream in a second, instrumented pass over the same steps) and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="serving", choices=["tiny", "llava", "serving", "lvlm", "stress"])
+    ap.add_argument("--pool", type=int, default=8, help="distinct pre-generated rounds (and W copies) cycled through")
+    ap.add_argument("--w-copies", type=int, default=8, help="device copies of W rotated per round (1 = warm cache)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rounds", type=int, default=12)
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    return ap.parse_args()
+
+
+def gen_inputs(wl, pool, w_copies, device):
+    """Same recipe as paper_2601_20357_amd.synth, drawn with torch on the GPU (inputs, not the method)."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(1000 * wl.cfg_id)
+    sd = torch.float32 if wl.w_dtype == 0 else torch.bfloat16
+    W = (torch.randn((wl.V, wl.d), generator=g, device=device) * 0.02).to(sd)
+    Ws = [W] + [W.clone() for _ in range(w_copies - 1)]
+    if wl.temperature == "mixed07":
+        temp = torch.zeros(wl.B, device=device); temp[1::2] = 0.7
+    elif wl.temperature == "greedy":
+        temp = torch.zeros(wl.B, device=device)
+    else:
+        temp = torch.ones(wl.B, device=device)
+    sig = torch.rand(wl.B, generator=g, device=device) * 1.3 + 0.2
+    Hs, Ts = [], []
+    for r in range(pool):
+        H = torch.randn((wl.gamma + 1, wl.B, wl.n, wl.d), generator=g, device=device).to(sd)
+        shape = (wl.B, wl.gamma + 1, wl.V)
+        if wl.target == "independent":
+            tgt = torch.randn(shape, generator=g, device=device) * wl.sigma
+        else:
+            jstar = (r // 64) % wl.n if wl.target == "switching" else 0
+            base = torch.einsum("ibk,vk->biv", H[:, :, jstar, :].float(), W.float())
+            if wl.target == "student_t":
+                z = torch.randn(shape, generator=g, device=device)
+                chi = torch.randn((3,) + shape, generator=g, device=device).pow(2).sum(0)
+                noise = z / (chi / 3).sqrt() * wl.sigma
+            elif wl.target == "per_seq_sigma":
+                noise = torch.randn(shape, generator=g, device=device) * sig[:, None, None]
+            else:
+                noise = torch.randn(shape, generator=g, device=device) * wl.sigma
+            tgt = base + noise
+        Hs.append(H.contiguous())
+        Ts.append(tgt.float().contiguous())
+    return Ws, Hs, Ts, temp.float().contiguous()
+
+
+def cpu_baseline(wl, rounds):
+    """The oracle as it stands, on this machine's host cores, on `rounds` rounds of the same workload."""
+    import numpy as np
+    import oracle
+    from paper_2601_20357_amd import synth
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import harness
+    W = synth.make_lm_head(wl)
+    temp = synth.make_temperature(wl)
+    side = harness.OracleSide(oracle, wl)
+    inputs = [synth.make_round(wl, W, r) for r in range(rounds)]
+    t0 = time.perf_counter()
+    for r, (H, tgt) in enumerate(inputs):
+        side.round(r, W, H, tgt, temp)
+    dt = time.perf_counter() - t0
+    return {"value": rounds / dt, "unit": "steps/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{rounds} full rounds of the {wl.name} workload (all B={wl.B} sequences), {dt:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2601_20357_amd import binding, synth
+
+    wl = synth.WORKLOADS[args.workload]
+    device = "cuda:0"
+    torch.cuda.set_device(0)
+    binding.load()
+    Ws, Hs, Ts, temp = gen_inputs(wl, args.pool, args.w_copies, device)
+    cfg = binding.make_cfg(V=wl.V, d=wl.d, n=wl.n, B=wl.B, gamma=wl.gamma, h=wl.h, w_dtype=wl.w_dtype, seed=0)
+    buf = binding.RoundBuffers(cfg, device)
+
+    upd_first = buf.prepare_update_weights(True)
+    upd = buf.prepare_update_weights(False)
+    slots = []
+    for r in range(args.pool):
+        W = Ws[r % len(Ws)]
+        drafts = [buf.prepare_draft_step(0, pos, W, Hs[r][pos], temp) for pos in range(wl.gamma)]
+        slots.append((drafts, buf.prepare_verify(0, Ts[r], temp)))
+
+    state = {"step": 0}
+
+    def step():
+        s = state["step"]
+        drafts, ver = slots[s % args.pool]
+        (upd_first if s == 0 else upd)()
+        for c in drafts:
+            c.set_round(s)
+            c()
+        ver.set_round(s)
+        ver()
+        state["step"] = s + 1
+
+    def timed(k):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(k):
+            step()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    for _ in range(args.warmup):
+        step()
+    dt = timed(args.steps)
+    ms_per_step = dt / args.steps * 1e3
+    emitted = float(buf.accept_len.float().mean().item()) + 1.0
+
+    # ---- second, instrumented pass over the same steps: per-kernel HIP-event timing on the launch stream
+    kernels = {}
+    roofline = None
+    M = wl.n * wl.B
+    esz = 4 if wl.w_dtype == 0 else 2
+    lm_bytes = wl.V * wl.d * esz + M * wl.V * 4 + M * wl.d * esz      # W once + logits written once + H
+    lm_flops = 2.0 * M * wl.d * wl.V
+    if not args.no_kernel_timing:
+        binding.tabed_prof_reset()
+        binding.tabed_prof_enable(True)
+        dt_inst = timed(args.steps)
+        binding.tabed_prof_enable(False)
+        for kid in range(binding.K_COUNT):
+            ms, cnt = binding.tabed_prof_read(kid)
+            if cnt:
+                kernels[binding.tabed_kernel_name(kid)] = {"avg_us": ms / cnt * 1e3, "launches": cnt}
+        lm_us = kernels["lmhead"]["avg_us"]
+        achieved = lm_bytes / (lm_us * 1e-6) / 1e9
+        roofline = {"kernel": "lmhead", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "algorithmic_bytes_per_launch": lm_bytes, "avg_launch_us": lm_us,
+                    "mfma_tflops": lm_flops / (lm_us * 1e-6) / 1e12,
+                    "mfma_frac_of_bf16_peak": lm_flops / (lm_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                    "instrumented_ms_per_step": dt_inst / args.steps * 1e3}
+
+    round_bytes = wl.gamma * (lm_bytes + 0) + (wl.B * (wl.gamma + 1) * wl.V * 4 + wl.gamma * M * wl.V * 4) \
+        + wl.B * (1 + wl.n) * wl.V * 4
+    out = {
+        "metric": "ensemble-draft+verify steps/sec", "value": args.steps / dt, "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if wl.w_dtype == 1 else "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: V={wl.V} d={wl.d} n={wl.n} B={wl.B} gamma={wl.gamma} h={wl.h} "
+                               f"temperature={wl.temperature}", "pool_rounds": args.pool, "w_copies": args.w_copies,
+                   "calls_per_step": 2 + wl.gamma},
+        "roofline": roofline,
+        "cpu_baseline": None,
+        "detail": {"kernels": kernels, "mean_tokens_per_round": emitted,
+                   "round_algorithmic_bytes": round_bytes,
+                   "round_frac_of_hbm_roofline": round_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_rounds)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -202,6 +202,25 @@ def tabed_kernel_name(kernel_id: int) -> str:
     return load().tabed_kernel_name(kernel_id).decode()
 
 
+class PreparedCall:
+    """A C-ABI call with its arguments already converted to ctypes, for launch loops where the per-call
+    tensor checks would cost more than the launch.  Built by RoundBuffers.prepare_*; checks happen once."""
+
+    __slots__ = ("fn", "args", "what", "round_arg")
+
+    def __init__(self, fn, args, what, round_arg=None):
+        self.fn, self.args, self.what, self.round_arg = fn, args, what, round_arg
+
+    def set_round(self, rnd: int):
+        """Change the SD round number (the Philox counter) the next call passes."""
+        self.round_arg.value = rnd
+
+    def __call__(self):
+        rc = self.fn(*self.args)
+        if rc != 0:
+            _check(rc, self.what)
+
+
 class RoundBuffers:
     """Device buffers one sequence batch needs across rounds (allocation only; no arithmetic here)."""
 
@@ -225,6 +244,44 @@ class RoundBuffers:
         self.dev = z((B, g, n), torch.float32)
         self.n_valid = z((B,), torch.int32)
         self.verify_flags = z((B, g + 1), torch.uint8)
+
+    # ---- the same three calls with arguments converted once (hot loops)
+    def prepare_update_weights(self, first: bool, stream=None) -> PreparedCall:
+        import torch
+        c = self.cfg
+        vp = C.c_void_p
+        args = [C.byref(c), vp(self.ws.data_ptr()),
+                vp(None if first else self.dev.data_ptr()), vp(None if first else self.n_valid.data_ptr()),
+                vp(self.ring.data_ptr()), vp(self.ring_head.data_ptr()), vp(self.ring_count.data_ptr()),
+                vp(self.weights.data_ptr()), vp(_stream(stream))]
+        return PreparedCall(load().tabed_update_weights, args, "tabed_update_weights")
+
+    def prepare_draft_step(self, rnd, pos, W, H, temperature, u_draft=None, stream=None) -> PreparedCall:
+        import torch
+        c = self.cfg
+        sd = _store_dtype(c)
+        vp = C.c_void_p
+        args = [C.byref(c), vp(self.ws.data_ptr()), C.c_uint64(rnd), C.c_int32(pos),
+                vp(_ptr(W, sd, c.V * c.d, "W")), vp(_ptr(H, sd, c.B * c.n * c.d, "H")),
+                vp(self.weights.data_ptr()), vp(_ptr(temperature, torch.float32, c.B, "temperature")),
+                vp(_ptr(u_draft, torch.float32, c.B * c.gamma, "u_draft")),
+                vp(self.draft_logits.data_ptr()), vp(self.draft_lse.data_ptr()), vp(self.draft_tokens.data_ptr()),
+                vp(self.draft_q.data_ptr()), vp(self.draft_flags.data_ptr()), vp(_stream(stream))]
+        return PreparedCall(load().tabed_draft_step, args, "tabed_draft_step", args[2])
+
+    def prepare_verify(self, rnd, target_logits, temperature, u_acc=None, u_res=None, stream=None) -> PreparedCall:
+        import torch
+        c = self.cfg
+        vp = C.c_void_p
+        args = [C.byref(c), vp(self.ws.data_ptr()), C.c_uint64(rnd),
+                vp(_ptr(target_logits, torch.float32, c.B * (c.gamma + 1) * c.V, "target_logits")),
+                vp(self.draft_logits.data_ptr()), vp(self.draft_lse.data_ptr()), vp(self.draft_tokens.data_ptr()),
+                vp(self.draft_q.data_ptr()), vp(self.weights.data_ptr()),
+                vp(_ptr(temperature, torch.float32, c.B, "temperature")),
+                vp(_ptr(u_acc, torch.float32, c.B * c.gamma, "u_acc")), vp(_ptr(u_res, torch.float32, c.B, "u_res")),
+                vp(self.accept_len.data_ptr()), vp(self.out_tokens.data_ptr()), vp(self.dev.data_ptr()),
+                vp(self.n_valid.data_ptr()), vp(self.verify_flags.data_ptr()), vp(_stream(stream))]
+        return PreparedCall(load().tabed_verify, args, "tabed_verify", args[2])
 
     def update_weights(self, first: bool, stream=None):
         tabed_update_weights(self.cfg, self.ws, None if first else self.dev, None if first else self.n_valid,
