@@ -22,6 +22,7 @@ int validate_cfg(const tabed_cfg* c) {
     if (c->policy != 0 && c->policy != 1) return TABED_EINVAL;
     if (!(c->tau_w > 0.f) || !(c->eps > 0.f)) return TABED_EINVAL;
     if ((long long)c->B * c->n > (1ll << 24)) return TABED_ERANGE;
+    if (c->V > kTileV * kBlock * 20) return TABED_ERANGE;      // 163840: largest vocabulary the sampler tiles
     if (c->distance == 1) return TABED_EUNSUPPORTED;
     return TABED_OK;
 }
@@ -33,7 +34,7 @@ WsLayout ws_layout(const tabed_cfg& c) {
     L.C2 = (c.V + kChunkV - 1) / kChunkV;
     L.C3max = (c.V + kBlock * 4 - 1) / (kBlock * 4);
     L.NSEG = (c.V + kSegV - 1) / kSegV;
-    L.C5 = (c.V + kChunkV - 1) / kChunkV;
+    L.C5 = (c.V + kResidChunkV - 1) / kResidChunkV;
     L.RS = kStatHdr + c.n;
     size_t off = 0;
     L.off_tickets = off; off = align_up(off + sizeof(uint32_t) * 3 * (size_t)c.B);
@@ -41,8 +42,6 @@ WsLayout ws_layout(const tabed_cfg& c) {
     L.off_ps = off;      off = align_up(off + sizeof(float) * (size_t)L.M * L.NT);
     L.off_cand = off;    off = align_up(off + sizeof(Top2Rec) * (size_t)c.B * L.C2);
     L.off_stats = off;   off = align_up(off + sizeof(double) * (size_t)c.B * (c.gamma + 1) * L.C3max * L.RS);
-    L.off_lsep = off;    off = align_up(off + sizeof(double) * 2 * (size_t)c.B * (c.gamma + 1));
-    L.off_amax = off;    off = align_up(off + sizeof(int32_t) * (size_t)c.B * (c.gamma + 1));
     L.off_seg = off;     off = align_up(off + sizeof(double) * 2 * (size_t)c.B * L.NSEG);
     L.total = off;
     return L;
@@ -162,12 +161,9 @@ int tabed_verify(const tabed_cfg* cfg, void* ws, uint64_t round, const float* ta
         return TABED_EALIGN;
     const WsLayout L = ws_layout(*cfg);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = launch_stats(*cfg, L, static_cast<char*>(ws), round, target_logits, draft_logits, draft_lse,
-                                draft_tokens, draft_q, temperature, u_acc, accept_len, out_tokens, dev, n_valid,
-                                flags, s);
-    if (e != hipSuccess) return fail_hip(e);
-    e = launch_resid(*cfg, L, static_cast<char*>(ws), round, target_logits, draft_logits, draft_lse, weights,
-                     temperature, u_res, accept_len, out_tokens, flags, s);
+    const hipError_t e = launch_verify(*cfg, L, static_cast<char*>(ws), round, target_logits, draft_logits, draft_lse,
+                                       draft_tokens, draft_q, weights, temperature, u_acc, u_res, accept_len,
+                                       out_tokens, dev, n_valid, flags, s);
     return e == hipSuccess ? TABED_OK : fail_hip(e);
 }
 

@@ -70,6 +70,26 @@ __device__ __forceinline__ double block_exclusive_scan(double v, double* lds4, d
     return base + inc - v;
 }
 
+// Which thread's run of the prefix contains `target`?  Every thread passes the exclusive prefix and the
+// sum of its run (block_exclusive_scan order).  Returns the lowest thread whose inclusive prefix exceeds
+// target; if rounding lets none exceed it, the highest thread with a non-empty run; -1 if all runs are
+// empty.  Ballots and two small LDS arrays: no same-address atomics.
+__device__ __forceinline__ int block_find_owner(double excl, double run, double target, int* lds_first4,
+                                                int* lds_last4) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const unsigned long long cross = __ballot(run > 0.0 && excl + run > target);
+    const unsigned long long live = __ballot(run > 0.0);
+    if (lane == 0) {
+        lds_first4[w] = cross ? (w * 64 + __ffsll((long long)cross) - 1) : 0x7fffffff;
+        lds_last4[w] = live ? (w * 64 + 63 - __clzll((long long)live)) : -1;
+    }
+    __syncthreads();
+    const int first = min(min(lds_first4[0], lds_first4[1]), min(lds_first4[2], lds_first4[3]));
+    const int last = max(max(lds_last4[0], lds_last4[1]), max(lds_last4[2], lds_last4[3]));
+    __syncthreads();
+    return first != 0x7fffffff ? first : last;
+}
+
 // ---------------------------------------------------------------- arg-max with runner-up
 struct Top2 {
     float v1;  // maximum

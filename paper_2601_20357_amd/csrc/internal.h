@@ -14,7 +14,8 @@ constexpr int kBlock = 256;     // every vocab-pass kernel runs 4 waves per work
 constexpr int kWavesPerBlock = kBlock / kWave;
 constexpr int kTileV = 32;      // width of one softmax-partial tile written by the LM-head epilogue
 constexpr int kSegV = 256;      // width of one CDF segment of the corrected/bonus sampler (one wave x float4)
-constexpr int kChunkV = 4096;   // vocabulary span of one workgroup in the full-row passes (256 threads x 4 float4)
+constexpr int kChunkV = 4096;   // vocabulary span of one workgroup in the greedy arg-max pass (256 threads x 4 float4)
+constexpr int kResidChunkV = 2048;  // vocabulary span of one workgroup in the corrected/bonus sampler (2 segments per wave)
 constexpr int kStatHdr = 4;     // doubles before the per-draft sums in a chunk record: max, Z, argmax value, argmax index
 
 struct Top2Rec {                // chunk candidate of the greedy draft arg-max
@@ -27,13 +28,11 @@ struct Top2Rec {                // chunk candidate of the greedy draft arg-max
 // Where everything lives inside the caller's workspace (byte offsets, 256-byte aligned).
 struct WsLayout {
     int M, NT, C2, C3max, NSEG, C5, RS;
-    size_t off_tickets;  // uint32 [3][B]: arrival counters of sample / stats / resid kernels
+    size_t off_tickets;  // uint32 [3][B]: arrival counters (0: greedy draft arg-max, 2: corrected/bonus sampler)
     size_t off_pm;       // float  [M][NT] tile maxima of scaled logits
     size_t off_ps;       // float  [M][NT] tile sums of exp(scaled logit - tile max)
     size_t off_cand;     // Top2Rec [B][C2]
     size_t off_stats;    // double [B][gamma+1][C3max][RS]
-    size_t off_lsep;     // double [B][gamma+1] log-sum-exp of scaled target rows
-    size_t off_amax;     // int32  [B][gamma+1] arg-max of target rows
     size_t off_seg;      // double [B][2][NSEG] segment masses: residual, target
     size_t total;
 };
@@ -51,16 +50,11 @@ hipError_t launch_sample(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
                          const float* u_draft, double* draft_lse, int32_t* draft_tokens, float* draft_q,
                          uint8_t* flags, hipStream_t s);
 
-hipError_t launch_stats(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round,
-                        const float* target_logits, const float* draft_logits, const double* draft_lse,
-                        const int32_t* draft_tokens, const float* draft_q, const float* temperature,
-                        const float* u_acc, int32_t* accept_len, int32_t* out_tokens, float* dev,
-                        int32_t* n_valid, uint8_t* flags, hipStream_t s);
-
-hipError_t launch_resid(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round,
-                        const float* target_logits, const float* draft_logits, const double* draft_lse,
-                        const float* weights, const float* temperature, const float* u_res,
-                        const int32_t* accept_len, int32_t* out_tokens, uint8_t* flags, hipStream_t s);
+hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round,
+                         const float* target_logits, const float* draft_logits, const double* draft_lse,
+                         const int32_t* draft_tokens, const float* draft_q, const float* weights,
+                         const float* temperature, const float* u_acc, const float* u_res, int32_t* accept_len,
+                         int32_t* out_tokens, float* dev, int32_t* n_valid, uint8_t* flags, hipStream_t s);
 
 hipError_t launch_weights(const tabed_cfg& c, const float* dev, const int32_t* n_valid, float* ring,
                           int32_t* ring_head, int32_t* ring_count, float* weights, hipStream_t s);

@@ -38,54 +38,76 @@ hipError_t launch_philox(const tabed_cfg& c, uint64_t round, float* out, hipStre
     return hipGetLastError();
 }
 
-// One thread per sequence: push the verified positions into the window, sum it, softmax of 1/e.
-// Everything after the fp32 loads is fp64: B*n scalars, latency-bound.
-__global__ void k_weights(int n, int B, int gamma, int h, int policy, double tau_w, double eps,
-                          const float* __restrict__ dev, const int32_t* __restrict__ n_valid,
-                          float* ring, int32_t* ring_head, int32_t* ring_count, float* weights) {
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= B) return;
+// One 64-lane workgroup per sequence.  The window after pushing the nv new positions is the newest
+// min(count + nv, h) entries of (old ring entries ++ new entries); every lane loads its share of them in
+// parallel (no load depends on a store), lane j sums draft j's column in fp64, the softmax of 1/e follows,
+// and only then are the new positions stored into the ring.  B*n scalars: latency-bound.
+__global__ __launch_bounds__(64) void k_weights(int n, int B, int gamma, int h, int policy, double tau_w, double eps,
+                                                const float* __restrict__ dev, const int32_t* __restrict__ n_valid,
+                                                float* ring, int32_t* ring_head, int32_t* ring_count,
+                                                float* weights) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    __shared__ double s_part[64];
+    __shared__ double s_x[TABED_MAX_N];
     int head = ring_head[b], count = ring_count[b];
     head = ((head % h) + h) % h;
     count = count < 0 ? 0 : (count > h ? h : count);
-    float* rb = ring + (size_t)b * h * n;
+    int nv = 0;
     if (dev != nullptr && n_valid != nullptr) {
-        int nv = n_valid[b];
+        nv = n_valid[b];
         nv = nv < 0 ? 0 : (nv > gamma ? gamma : nv);
-        for (int i = 0; i < nv; ++i) {
-            for (int j = 0; j < n; ++j) rb[(size_t)head * n + j] = dev[((size_t)b * gamma + i) * n + j];
-            head = (head + 1) % h;
-            if (count < h) ++count;
+    }
+    const int new_count = (count + nv < h) ? count + nv : h;
+    float* rb = ring + (size_t)b * h * n;
+    const float* db = dev ? dev + (size_t)b * gamma * n : nullptr;
+    const int per = 64 / n;                       // lanes per draft column (n <= 16 => per >= 4)
+    const int j = lane % n, t0 = lane / n;
+    double acc = 0.0;
+    if (lane < per * n) {
+        for (int r = t0; r < new_count; r += per) {   // r-th newest entry of the new window
+            float v;
+            if (r < nv) v = db[(size_t)(nv - 1 - r) * n + j];
+            else        v = rb[(size_t)((((head - 1 - (r - nv)) % h) + h) % h) * n + j];
+            acc += (double)v;
         }
-        ring_head[b] = head;
-        ring_count[b] = count;
     }
-    float* w = weights + (size_t)b * n;
-    if (policy == 1 || count == 0) {
-        const float eq = (float)(1.0 / (double)n);
-        for (int j = 0; j < n; ++j) w[j] = eq;
-        return;
-    }
-    double x[TABED_MAX_N];
-    double xmax = -INFINITY;
-    for (int j = 0; j < n; ++j) {
+    s_part[lane] = acc;
+    __syncthreads();
+    if (lane < n) {
         double e = 0.0;
-        for (int t = 0; t < count; ++t) {            // oldest .. newest
-            const int slot = ((head - count + t) % h + h) % h;
-            e += (double)rb[(size_t)slot * n + j];
-        }
-        x[j] = (1.0 / fmax(e, eps)) / tau_w;
-        xmax = fmax(xmax, x[j]);
+        for (int q = 0; q < per; ++q) e += s_part[q * n + lane];
+        s_x[lane] = (1.0 / fmax(e, eps)) / tau_w;
     }
-    double Z = 0.0;
-    for (int j = 0; j < n; ++j) { x[j] = exp(x[j] - xmax); Z += x[j]; }
-    for (int j = 0; j < n; ++j) w[j] = (float)(x[j] / Z);
+    __syncthreads();
+    if (lane < n) {
+        float w;
+        if (policy == 1 || new_count == 0) {
+            w = (float)(1.0 / (double)n);
+        } else {
+            double xmax = -INFINITY;
+            for (int q = 0; q < n; ++q) xmax = fmax(xmax, s_x[q]);
+            double Z = 0.0;
+            for (int q = 0; q < n; ++q) Z += exp(s_x[q] - xmax);
+            w = (float)(exp(s_x[lane] - xmax) / Z);
+        }
+        weights[(size_t)b * n + lane] = w;
+    }
+    if (nv > 0) {
+        for (int idx = lane; idx < nv * n; idx += 64) {
+            const int i = idx / n, jj = idx % n;
+            if (i >= nv - h) rb[(size_t)((head + i) % h) * n + jj] = db[(size_t)i * n + jj];
+        }
+        if (lane == 0) {
+            ring_head[b] = (head + nv) % h;
+            ring_count[b] = new_count;
+        }
+    }
 }
 
 hipError_t launch_weights(const tabed_cfg& c, const float* dev, const int32_t* n_valid, float* ring,
                           int32_t* ring_head, int32_t* ring_count, float* weights, hipStream_t s) {
     ProfScope prof(TABED_K_WEIGHTS, s);
-    hipLaunchKernelGGL(k_weights, dim3((c.B + 63) / 64), dim3(64), 0, s, c.n, c.B, c.gamma, c.h, c.policy,
+    hipLaunchKernelGGL(k_weights, dim3(c.B), dim3(64), 0, s, c.n, c.B, c.gamma, c.h, c.policy,
                        (double)c.tau_w, (double)c.eps, dev, n_valid, ring, ring_head, ring_count, weights);
     return hipGetLastError();
 }
@@ -95,9 +117,11 @@ hipError_t launch_weights(const tabed_cfg& c, const float* dev, const int32_t* n
 // The LM-head epilogue left, per draft row and per 32-wide vocabulary tile, the tile maximum of the scaled
 // logits and the tile sum of exp(scaled logit - tile maximum).  From those alone this kernel gets every
 // draft's log-sum-exp and the mass of the mixture q = sum_j w_j q^(j) inside every tile; a sampling row
-// therefore reads logits only inside the one tile its uniform falls into.  A greedy row needs the arg-max
-// of q over the whole vocabulary: its row is split over gridDim.x workgroups and the last one to arrive
-// merges the candidates in chunk order.
+// therefore reads logits only inside the one tile its uniform falls into.  The partials of a sequence
+// (n*NT pairs) are staged into LDS in one burst of independent loads when they fit, so the kernel pays two
+// memory round trips (partials, then the chosen tile) instead of one per reduction.  A greedy row needs
+// the arg-max of q over the whole vocabulary: its row is split over gridDim.x workgroups and the last one
+// to arrive merges the candidates (lowest index wins ties, so arrival order does not matter).
 // =====================================================================================================
 struct SampleArgs {
     int V, n, B, gamma, pos, NT, C2;
@@ -116,71 +140,97 @@ struct SampleArgs {
     uint32_t* tickets;
 };
 
-template <bool VEC>
+// TI = tiles per thread, a compile-time bound with NT <= kBlock * TI, so that every phase issues all of its
+// loads before the first use and keeps its tile values in registers.
+template <bool VEC, int TI>
 __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
-    const int b = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
+    const int b = blockIdx.y, c = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = a.n, NT = a.NT, V = a.V;
+    // Workgroup 0 of a sequence always has work, so its temperature load overlaps the loads below; the
+    // other workgroups only exist for greedy rows and leave at once otherwise.
     const float T = a.temperature[b];
-    const bool greedy = !(T > 0.f);
-    if (!greedy && c != 0) return;
-    const float invT = greedy ? 1.f : 1.f / T;
+    if (c != 0 && T > 0.f) return;
 
     __shared__ float s_m[TABED_MAX_N];    // row maximum of scaled logits
-    __shared__ double s_c[TABED_MAX_N];   // w_j / sum_v exp(scaled - max)
+    __shared__ double s_S[TABED_MAX_N];   // sum_v exp(scaled - max)
+    __shared__ double s_c[TABED_MAX_N];   // w_j / S_j
     __shared__ float s_cf[TABED_MAX_N];
-    __shared__ float s_redf[kWavesPerBlock];
     __shared__ double s_redd[kWavesPerBlock];
-    __shared__ int s_owner, s_fallback, s_tile, s_last;
+    __shared__ int s_first[kWavesPerBlock], s_lastw[kWavesPerBlock], s_tile, s_last;
     __shared__ double s_prefix;
     __shared__ Top2 s_top[kWavesPerBlock];
+    __shared__ double s_term[TABED_MAX_N][kTileV];
 
-    // ---- per-draft log-sum-exp from the tile partials
-    for (int j = 0; j < n; ++j) {
-        const float* pmr = a.pm + (size_t)(b * n + j) * NT;
-        const float* psr = a.ps + (size_t)(b * n + j) * NT;
-        float m = -INFINITY;
-        for (int t = tid; t < NT; t += kBlock) m = fmaxf(m, pmr[t]);
-        m = block_max(m, s_redf);
-        double s = 0.0;
-        for (int t = tid; t < NT; t += kBlock) s += (double)(psr[t] * __expf(pmr[t] - m));
-        s = block_sum(s, s_redd);
-        if (tid == 0) {
-            s_m[j] = m;
-            s_c[j] = (double)a.weights[(size_t)b * n + j] / s;
-            s_cf[j] = (float)s_c[j];
-            if (c == 0) a.draft_lse[((size_t)a.pos * a.B + b) * n + j] = (double)m + log(s);
+    const float* pmb = a.pm + (size_t)b * n * NT;      // partials of this sequence: [n][NT]
+    const float* psb = a.ps + (size_t)b * n * NT;
+    const size_t out_idx = (size_t)b * a.gamma + a.pos;
+    const float wj = (tid < n) ? a.weights[(size_t)b * n + tid] : 0.f;
+    const float u = a.u_draft ? a.u_draft[out_idx] : tabed_uniform(a.seed, a.round, (uint32_t)b, (uint32_t)a.pos, 0);
+
+    // ---- per-draft log-sum-exp: one wave per draft row, lanes strided over the row's tiles
+    constexpr int TL = TI * kWavesPerBlock;            // tiles per lane when one wave covers a whole row
+    for (int j = wave; j < n; j += kWavesPerBlock) {
+        float pmv[TL], psv[TL];
+#pragma unroll
+        for (int i = 0; i < TL; ++i) {
+            const int t = lane + i * kWave;
+            pmv[i] = t < NT ? pmb[(size_t)j * NT + t] : -INFINITY;
+            psv[i] = t < NT ? psb[(size_t)j * NT + t] : 0.f;
+        }
+        float ml = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < TL; ++i) ml = fmaxf(ml, pmv[i]);
+        const float M = wave_max(ml);
+        float sl = 0.f;
+#pragma unroll
+        for (int i = 0; i < TL; ++i) sl += (psv[i] > 0.f) ? psv[i] * __expf(pmv[i] - M) : 0.f;
+        const double S = wave_sum((double)sl);
+        if (lane == 0) {
+            s_m[j] = M;
+            s_S[j] = S;
+            if (c == 0) a.draft_lse[((size_t)a.pos * a.B + b) * n + j] = (double)M + log(S);
         }
     }
-    if (tid == 0) { s_owner = kBlock; s_fallback = -1; }
+    const bool greedy = !(T > 0.f);
+    const float invT = greedy ? 1.f : 1.f / T;
+    __syncthreads();
+    if (tid < n) {
+        s_c[tid] = (double)wj / s_S[tid];
+        s_cf[tid] = (float)s_c[tid];
+    }
     __syncthreads();
 
     const float* rows = a.logits + (size_t)b * n * V;
-    const size_t out_idx = (size_t)b * a.gamma + a.pos;
 
     if (!greedy) {
-        // ---- tile masses of the mixture, thread-contiguous runs of tiles, fixed-order prefix
-        const int S = (NT + kBlock - 1) / kBlock;
-        const int t0 = min(NT, tid * S), t1 = min(NT, t0 + S);
-        auto tile_mass = [&](int t) -> double {
-            double acc = 0.0;
-            for (int j = 0; j < n; ++j) {
-                const size_t o = (size_t)(b * n + j) * NT + t;
-                acc += s_c[j] * (double)(a.ps[o] * __expf(a.pm[o] - s_m[j]));
+        // ---- tile masses of the mixture: thread tid owns tiles [tid*TI, tid*TI + TI), kept in registers
+        double mt[TI];
+#pragma unroll
+        for (int i = 0; i < TI; ++i) mt[i] = 0.0;
+        double Z = 0.0;
+#pragma unroll 4
+        for (int j = 0; j < n; ++j) {
+            float pmv[TI], psv[TI];
+#pragma unroll
+            for (int i = 0; i < TI; ++i) {
+                const int t = tid * TI + i;
+                pmv[i] = t < NT ? pmb[(size_t)j * NT + t] : -INFINITY;
+                psv[i] = t < NT ? psb[(size_t)j * NT + t] : 0.f;
             }
-            return acc;
-        };
-        double run = 0.0;
-        for (int t = t0; t < t1; ++t) run += tile_mass(t);
-        double Z;
-        const double excl = block_exclusive_scan(run, s_redd, &Z);
-        const float u = a.u_draft ? a.u_draft[out_idx] : tabed_uniform(a.seed, a.round, (uint32_t)b, (uint32_t)a.pos, 0);
-        const double target = (double)u * Z;
-        if (run > 0.0) {
-            if (excl + run > target) atomicMin(&s_owner, tid);
-            atomicMax(&s_fallback, tid);
+            const double cj = s_c[j];
+            const float mj = s_m[j];
+            Z += cj * s_S[j];
+#pragma unroll
+            for (int i = 0; i < TI; ++i)
+                if (psv[i] > 0.f) mt[i] += cj * (double)(psv[i] * __expf(pmv[i] - mj));
         }
-        __syncthreads();
-        const int owner = s_owner < kBlock ? s_owner : s_fallback;   // -1 only if every mass is zero
+        double run = 0.0;
+#pragma unroll
+        for (int i = 0; i < TI; ++i) run += mt[i];
+        double Zscan;
+        const double excl = block_exclusive_scan(run, s_redd, &Zscan);
+        const double target = (double)u * Z;
+        const int owner = block_find_owner(excl, run, target, s_first, s_lastw);   // -1 only if every mass is zero
         if (owner < 0) {
             if (tid == 0) {
                 a.draft_tokens[out_idx] = 0;
@@ -190,26 +240,33 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
             return;
         }
         if (tid == owner) {
-            double P = excl;
-            int tstar = -1, tlast = t0;
-            double Plast = excl;
-            for (int t = t0; t < t1; ++t) {
-                const double mt = tile_mass(t);
-                if (mt > 0.0) { tlast = t; Plast = P; }
-                if (P + mt > target) { tstar = t; break; }
-                P += mt;
+            double P = excl, Plast = excl;
+            int istar = -1, ilast = 0;
+#pragma unroll
+            for (int i = 0; i < TI; ++i) {
+                if (istar < 0) {
+                    if (mt[i] > 0.0) { ilast = i; Plast = P; }
+                    if (P + mt[i] > target) istar = i;
+                    else P += mt[i];
+                }
             }
-            if (tstar < 0) { tstar = tlast; P = Plast; }
-            s_tile = tstar;
+            if (istar < 0) { istar = ilast; P = Plast; }
+            s_tile = tid * TI + istar;
             s_prefix = P;
         }
         __syncthreads();
+        // ---- the tile's logits: thread (draft j, lane v) -> one round trip for all drafts, summed by wave 0
+        {
+            const int vl = tid & (kTileV - 1), v = s_tile * kTileV + vl;
+            for (int j = tid / kTileV; j < n; j += kBlock / kTileV)
+                s_term[j][vl] = (v < V) ? s_c[j] * (double)__expf(rows[(size_t)j * V + v] * invT - s_m[j]) : 0.0;
+        }
+        __syncthreads();
         if (tid >= kWave) return;
-        // ---- wave 0 resolves the token inside the tile
-        const int lane = tid, v = s_tile * kTileV + lane;
+        const int v = s_tile * kTileV + lane;
         double f = 0.0;
-        if (lane < kTileV && v < V)
-            for (int j = 0; j < n; ++j) f += s_c[j] * (double)__expf(rows[(size_t)j * V + v] * invT - s_m[j]);
+        if (lane < kTileV)
+            for (int j = 0; j < n; ++j) f += s_term[j][lane];
         const double inc = wave_inclusive_scan(f);
         const double cdf = s_prefix + inc;
         const unsigned long long cross = __ballot(cdf > target && f > 0.0);
@@ -251,24 +308,26 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
             if (v + e < V) best = top2_push(best, q[e], v + e);
     }
     best = wave_top2(best);
-    if ((tid & 63) == 0) s_top[tid >> 6] = best;
+    if (lane == 0) s_top[wave] = best;
     __syncthreads();
     if (tid == 0) {
         Top2 t = s_top[0];
         for (int w = 1; w < kWavesPerBlock; ++w) t = top2_merge(t, s_top[w]);
         a.cand[(size_t)b * a.C2 + c] = Top2Rec{t.v1, t.i1, t.v2, 0};
-        __threadfence();
+        __threadfence();                                   // one fence per workgroup: the writer itself
         const uint32_t old = atomicAdd(&a.tickets[b], 1u);
         s_last = (old == (uint32_t)(a.C2 - 1));
     }
     __syncthreads();
-    if (!s_last || tid != 0) return;
+    if (!s_last || tid >= kWave) return;
     __threadfence();
     Top2 t = top2_empty();
-    for (int cc = 0; cc < a.C2; ++cc) {
+    for (int cc = lane; cc < a.C2; cc += kWave) {
         const Top2Rec r = a.cand[(size_t)b * a.C2 + cc];
         t = top2_merge(t, Top2{r.v1, r.i1, r.v2});
     }
+    t = wave_top2(t);
+    if (lane != 0) return;
     a.tickets[b] = 0u;
     const int y = (t.i1 >= 0 && t.i1 < V) ? t.i1 : 0;
     double f = 0.0;
@@ -296,68 +355,77 @@ hipError_t launch_sample(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
     a.cand = reinterpret_cast<Top2Rec*>(ws + L.off_cand);
     a.tickets = reinterpret_cast<uint32_t*>(ws + L.off_tickets) + 0 * c.B;
     const dim3 grid(L.C2, c.B);
-    if (c.V % 4 == 0) hipLaunchKernelGGL(k_sample<true>, grid, dim3(kBlock), 0, s, a);
-    else              hipLaunchKernelGGL(k_sample<false>, grid, dim3(kBlock), 0, s, a);
+    const bool vec = (c.V % 4 == 0);
+    const int ti = (L.NT + kBlock - 1) / kBlock;
+#define TABED_LAUNCH_SAMPLE(TI_)                                                                  \
+    do {                                                                                          \
+        if (vec) hipLaunchKernelGGL((k_sample<true, TI_>), grid, dim3(kBlock), 0, s, a);          \
+        else     hipLaunchKernelGGL((k_sample<false, TI_>), grid, dim3(kBlock), 0, s, a);         \
+    } while (0)
+    if (ti <= 1) TABED_LAUNCH_SAMPLE(1);
+    else if (ti <= 4) TABED_LAUNCH_SAMPLE(4);
+    else if (ti <= 8) TABED_LAUNCH_SAMPLE(8);
+    else if (ti <= 20) TABED_LAUNCH_SAMPLE(20);
+    else return hipErrorInvalidValue;              // V > 163840: validate_cfg rejects it before this point
+#undef TABED_LAUNCH_SAMPLE
     return hipGetLastError();
 }
 
 // =====================================================================================================
-// Target statistics, per-draft KL, accept chain.
+// Target statistics and per-draft KL sums.
 // Grid (chunk, position i <= gamma, sequence b).  Each workgroup reads its chunk of the target row once,
-// and for i < gamma the same chunk of the n draft rows once, and leaves a record
+// and for i < gamma the same chunk of the n draft rows once -- all loads issued before the first use --
+// and leaves a record
 //   { m_c = max scaled target logit, Z_c = sum exp(st - m_c), arg-max of the raw row,
 //     A_jc = sum exp(st - m_c) * (st - s_j)  for every draft j }.
-// Since KL(p || q_j) = sum_v p (st - s_j) - lse_p + lse_j, these records combine exactly (in fp64, in chunk
-// order) once all chunks of a sequence have arrived; the last workgroup of a sequence does that and then
-// walks the accept chain of Sec. 3 item 3.
+// Since KL(p || q_j) = sum_v p (st - s_j) - lse_p + lse_j, the records of a row combine exactly (fp64, chunk
+// order) in the kernel that follows.  N is the number of drafts when known at compile time (0 = run time).
 // =====================================================================================================
 struct StatsArgs {
     int V, n, B, gamma, C3, RS;
-    uint64_t seed, round;
     const float* target;
     const float* dlogits;
-    const double* dlse;
-    const int32_t* dtok;
-    const float* dq;
     const float* temperature;
-    const float* u_acc;
     double* stats;
-    double* lsep;   // [B][gamma+1][2]: row maximum, 1 / sum exp(st - max)
-    int32_t* amax;
-    uint32_t* tickets;
-    int32_t* accept_len;
-    int32_t* out_tokens;
-    float* dev;
-    int32_t* n_valid;
-    uint8_t* flags;
 };
 
-template <bool VEC, int U>
+template <bool VEC, int U, int N>
 __global__ __launch_bounds__(kBlock) void k_stats(StatsArgs a) {
-    const int c = blockIdx.x, i = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
-    const int V = a.V, n = a.n, gamma = a.gamma;
+    const int c = blockIdx.x, i = blockIdx.y, b = blockIdx.z, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int V = a.V, n = (N > 0) ? N : a.n, gamma = a.gamma;
     const float T = a.temperature[b];
-    const bool greedy = !(T > 0.f);
-    const float invT = greedy ? 1.f : 1.f / T;
+    const float invT = (T > 0.f) ? 1.f / T : 1.f;
 
     __shared__ float s_redf[kWavesPerBlock];
     __shared__ double s_redd[kWavesPerBlock];
     __shared__ ArgMax s_am[kWavesPerBlock];
     __shared__ double s_A[kWavesPerBlock][TABED_MAX_N];
-    __shared__ int s_last;
 
     const float* trow = a.target + ((size_t)b * (gamma + 1) + i) * V;
+    const float* qbase = a.dlogits + (((size_t)i * a.B + b) * n) * V;   // only dereferenced when i < gamma
     const int cb = c * (kBlock * 4 * U);
+    const bool drafts = (i < gamma);
+
+    float4 tx[U];
+    float4 dx[(N > 0) ? N : 1][U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) tx[u] = load4<VEC>(trow, cb + (u * kBlock + tid) * 4, V);
+    if (N > 0 && drafts) {
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+#pragma unroll
+            for (int u = 0; u < U; ++u) dx[j][u] = load4<VEC>(qbase + (size_t)j * V, cb + (u * kBlock + tid) * 4, V);
+    }
+
     float st[U * 4], ex[U * 4];
     ArgMax am{-INFINITY, 0x7fffffff};
     float tmax = -INFINITY;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int v = cb + (u * kBlock + tid) * 4;
-        const float4 x = load4<VEC>(trow, v, V);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const float xe = f4get(x, e);
+            const float xe = f4get(tx[u], e);
             if (v + e < V) am = argmax_merge(am, ArgMax{xe, v + e});
             st[u * 4 + e] = xe * invT;
             tmax = fmaxf(tmax, st[u * 4 + e]);
@@ -370,26 +438,42 @@ __global__ __launch_bounds__(kBlock) void k_stats(StatsArgs a) {
         ex[k] = (st[k] > -INFINITY) ? __expf(st[k] - mc) : 0.f;
         zf += ex[k];
     }
-    const double Zc = block_sum((double)zf, s_redd);
+    const double Zw = wave_sum((double)zf);
+    if (lane == 0) s_redd[wave] = Zw;
     am = wave_argmax(am);
-    if ((tid & 63) == 0) s_am[tid >> 6] = am;
+    if (lane == 0) s_am[wave] = am;
 
-    if (i < gamma) {
-        for (int j = 0; j < n; ++j) {
-            const float* qrow = a.dlogits + (((size_t)i * a.B + b) * n + j) * V;
-            float aj = 0.f;
+    if (drafts) {
+        if (N > 0) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int v = cb + (u * kBlock + tid) * 4;
-                const float4 y = load4<VEC>(qrow, v, V);
+            for (int j = 0; j < N; ++j) {
+                float aj = 0.f;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float p = ex[u * 4 + e];
-                    if (p > 0.f) aj += p * (st[u * 4 + e] - f4get(y, e) * invT);
-                }
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float p = ex[u * 4 + e];
+                        if (p > 0.f) aj += p * (st[u * 4 + e] - f4get(dx[j][u], e) * invT);
+                    }
+                const double Aj = wave_sum((double)aj);
+                if (lane == 0) s_A[wave][j] = Aj;
             }
-            const double Aj = wave_sum((double)aj);
-            if ((tid & 63) == 0) s_A[tid >> 6][j] = Aj;
+        } else {
+            for (int j = 0; j < n; ++j) {
+                float aj = 0.f;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int v = cb + (u * kBlock + tid) * 4;
+                    const float4 y = load4<VEC>(qbase + (size_t)j * V, v, V);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float p = ex[u * 4 + e];
+                        if (p > 0.f) aj += p * (st[u * 4 + e] - f4get(y, e) * invT);
+                    }
+                }
+                const double Aj = wave_sum((double)aj);
+                if (lane == 0) s_A[wave][j] = Aj;
+            }
         }
     }
     __syncthreads();
@@ -398,154 +482,72 @@ __global__ __launch_bounds__(kBlock) void k_stats(StatsArgs a) {
         ArgMax t = s_am[0];
         for (int w = 1; w < kWavesPerBlock; ++w) t = argmax_merge(t, s_am[w]);
         rec[0] = (double)mc;
-        rec[1] = Zc;
+        rec[1] = (s_redd[0] + s_redd[1]) + (s_redd[2] + s_redd[3]);
         rec[2] = (double)t.v;
         rec[3] = (double)t.i;
     }
-    if (i < gamma && tid < n) rec[kStatHdr + tid] = (s_A[0][tid] + s_A[1][tid]) + (s_A[2][tid] + s_A[3][tid]);
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const uint32_t old = atomicAdd(&a.tickets[b], 1u);
-        s_last = (old == (uint32_t)((gamma + 1) * a.C3 - 1));
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-
-    // ---- last workgroup of sequence b: combine chunks, distances, accept chain
-    __shared__ double s_rowm[TABED_MAX_GAMMA + 1], s_rowZ[TABED_MAX_GAMMA + 1], s_rowlse[TABED_MAX_GAMMA + 1];
-    __shared__ int s_rowam[TABED_MAX_GAMMA + 1];
-    const double* sb = a.stats + (size_t)b * (gamma + 1) * a.C3 * a.RS;
-    if (tid <= gamma) {
-        const double* r0 = sb + (size_t)tid * a.C3 * a.RS;
-        double m = -INFINITY;
-        for (int cc = 0; cc < a.C3; ++cc) m = fmax(m, r0[(size_t)cc * a.RS]);
-        double Z = 0.0, bv = -INFINITY;
-        int bi = 0;
-        for (int cc = 0; cc < a.C3; ++cc) {
-            const double* r = r0 + (size_t)cc * a.RS;
-            if (r[0] > -INFINITY) Z += r[1] * exp(r[0] - m);
-            if (r[2] > bv) { bv = r[2]; bi = (int)r[3]; }   // chunk order: ties keep the lowest index
-        }
-        s_rowm[tid] = m; s_rowZ[tid] = Z; s_rowlse[tid] = m + log(Z); s_rowam[tid] = bi;
-        a.lsep[((size_t)b * (gamma + 1) + tid) * 2 + 0] = m;
-        a.lsep[((size_t)b * (gamma + 1) + tid) * 2 + 1] = 1.0 / Z;
-        a.amax[(size_t)b * (gamma + 1) + tid] = bi;
-    }
-    __syncthreads();
-    for (int q = tid; q < gamma * n; q += kBlock) {
-        const int ii = q / n, j = q % n;
-        const double* r0 = sb + (size_t)ii * a.C3 * a.RS;
-        double A = 0.0;
-        for (int cc = 0; cc < a.C3; ++cc) {
-            const double* r = r0 + (size_t)cc * a.RS;
-            if (r[0] > -INFINITY) A += r[kStatHdr + j] * exp(r[0] - s_rowm[ii]);
-        }
-        const double kl = A / s_rowZ[ii] - s_rowlse[ii] + a.dlse[((size_t)ii * a.B + b) * n + j];
-        a.dev[((size_t)b * gamma + ii) * n + j] = (float)kl;
-    }
-    if (tid != 0) return;
-    a.tickets[b] = 0u;
-    int k = 0;
-    bool open = true;
-    for (int ii = 0; ii < gamma; ++ii) {
-        uint32_t flag = 0;
-        if (open) {
-            const int y = a.dtok[(size_t)b * gamma + ii];
-            bool ok;
-            if (y < 0 || y >= V) { ok = false; flag |= TABED_FLAG_DEGENERATE; }
-            else if (greedy) ok = (y == s_rowam[ii]);
-            else {
-                const float u = a.u_acc ? a.u_acc[(size_t)b * gamma + ii]
-                                        : tabed_uniform(a.seed, a.round, (uint32_t)b, (uint32_t)ii, 1);
-                const float sty = a.target[((size_t)b * (gamma + 1) + ii) * V + y] * invT;
-                const float py = (float)exp((double)sty - s_rowlse[ii]);
-                const float lhs = u * a.dq[(size_t)b * gamma + ii];
-                ok = lhs < py;
-                if (fabs((double)lhs - (double)py) < (double)kMargin * fmax((double)lhs, (double)py))
-                    flag |= TABED_FLAG_ACCEPT_MARGIN;
-            }
-            if (ok) ++k; else open = false;
-        }
-        a.flags[(size_t)b * (gamma + 1) + ii] = (uint8_t)flag;
-    }
-    a.flags[(size_t)b * (gamma + 1) + gamma] = 0;
-    for (int ii = 0; ii <= gamma; ++ii)
-        a.out_tokens[(size_t)b * (gamma + 1) + ii] = ii < k ? a.dtok[(size_t)b * gamma + ii] : -1;
-    a.accept_len[b] = k;
-    a.n_valid[b] = k + 1 < gamma ? k + 1 : gamma;
+    if (drafts && tid < n) rec[kStatHdr + tid] = (s_A[0][tid] + s_A[1][tid]) + (s_A[2][tid] + s_A[3][tid]);
 }
 
-static int pick_stats_unroll(const tabed_cfg& c) {
+static int pick_stats_unroll(const tabed_cfg& c, int nmax_u) {
     // Largest chunk that still gives the chip a few workgroups per compute unit.
     const long rows = (long)c.B * (c.gamma + 1);
     for (int U : {4, 2}) {
+        if (U > nmax_u) continue;
         const long chunks = (c.V + kBlock * 4 * U - 1) / (kBlock * 4 * U);
         if (rows * chunks >= 512) return U;
     }
     return 1;
 }
 
-hipError_t launch_stats(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round,
-                        const float* target_logits, const float* draft_logits, const double* draft_lse,
-                        const int32_t* draft_tokens, const float* draft_q, const float* temperature,
-                        const float* u_acc, int32_t* accept_len, int32_t* out_tokens, float* dev,
-                        int32_t* n_valid, uint8_t* flags, hipStream_t s) {
-    ProfScope prof(TABED_K_STATS, s);
-    const int U = pick_stats_unroll(c);
-    StatsArgs a;
-    a.V = c.V; a.n = c.n; a.B = c.B; a.gamma = c.gamma; a.RS = L.RS;
-    a.C3 = (c.V + kBlock * 4 * U - 1) / (kBlock * 4 * U);
-    a.seed = c.seed; a.round = round;
-    a.target = target_logits; a.dlogits = draft_logits; a.dlse = draft_lse; a.dtok = draft_tokens;
-    a.dq = draft_q; a.temperature = temperature; a.u_acc = u_acc;
-    a.stats = reinterpret_cast<double*>(ws + L.off_stats);
-    a.lsep = reinterpret_cast<double*>(ws + L.off_lsep);
-    a.amax = reinterpret_cast<int32_t*>(ws + L.off_amax);
-    a.tickets = reinterpret_cast<uint32_t*>(ws + L.off_tickets) + 1 * c.B;
-    a.accept_len = accept_len; a.out_tokens = out_tokens; a.dev = dev; a.n_valid = n_valid; a.flags = flags;
-    const dim3 grid(a.C3, c.gamma + 1, c.B);
-    const bool vec = (c.V % 4 == 0);
-#define TABED_LAUNCH_STATS(VEC_, U_) hipLaunchKernelGGL((k_stats<VEC_, U_>), grid, dim3(kBlock), 0, s, a)
-    if (vec) { if (U == 4) TABED_LAUNCH_STATS(true, 4); else if (U == 2) TABED_LAUNCH_STATS(true, 2); else TABED_LAUNCH_STATS(true, 1); }
-    else     { if (U == 4) TABED_LAUNCH_STATS(false, 4); else if (U == 2) TABED_LAUNCH_STATS(false, 2); else TABED_LAUNCH_STATS(false, 1); }
-#undef TABED_LAUNCH_STATS
-    return hipGetLastError();
+template <bool VEC, int N>
+static void launch_stats_n(int U, dim3 grid, hipStream_t s, const StatsArgs& a) {
+    if (U == 4) {
+        if constexpr (N <= 4) hipLaunchKernelGGL((k_stats<VEC, 4, N>), grid, dim3(kBlock), 0, s, a);
+    } else if (U == 2) {
+        hipLaunchKernelGGL((k_stats<VEC, 2, N>), grid, dim3(kBlock), 0, s, a);
+    } else {
+        hipLaunchKernelGGL((k_stats<VEC, 1, N>), grid, dim3(kBlock), 0, s, a);
+    }
 }
 
 // =====================================================================================================
-// Corrected / bonus token.
-// For a sampling row with k accepted tokens the emitted token comes from f = max(0, p_k - q_k) (k < gamma)
-// or f = p_gamma (k = gamma).  Every wave writes the mass of f over its 256-wide segments; the last
-// workgroup of the sequence prefixes the segment masses in order, finds the segment the uniform falls
-// into, and one wave re-evaluates that segment element by element.  A greedy row just emits the arg-max
-// of target row k found by the statistics kernel.
+// Accept chain, distances, corrected / bonus token.
+// Grid (chunk, sequence b).  Every workgroup of a sequence first combines the chunk records of all
+// gamma+1 target rows (fp64, chunk order), evaluates the gamma accept tests of Sec. 3 item 3 in parallel
+// and takes k = the first failing position.  Workgroup 0 also writes KL(p_i || q_i^(j)) and the
+// bookkeeping outputs.  For a sampling row the emitted token comes from f = max(0, p_k - q_k) (k < gamma)
+// or f = p_gamma (k = gamma): every wave writes the mass of f over its 256-wide segments; the last
+// workgroup of the sequence to arrive prefixes the segment masses in order, finds the segment the uniform
+// falls into, and one wave re-evaluates that segment element by element.  A greedy row emits the arg-max of
+// target row k and needs no vocabulary pass.
 // =====================================================================================================
-struct ResidArgs {
-    int V, n, B, gamma, NSEG, C5;
+struct FinishArgs {
+    int V, n, B, gamma, C3, RS, NSEG, C5;
     uint64_t seed, round;
     const float* target;
     const float* dlogits;
     const double* dlse;
+    const int32_t* dtok;
+    const float* dq;
     const float* weights;
     const float* temperature;
+    const float* u_acc;
     const float* u_res;
-    const int32_t* accept_len;
-    const double* lsep;
-    const int32_t* amax;
+    const double* stats;
     double* seg;          // [B][2][NSEG]
     uint32_t* tickets;
+    int32_t* accept_len;
     int32_t* out_tokens;
+    float* dev;
+    int32_t* n_valid;
     uint8_t* flags;
 };
 
-// exp(x - (hi + lo)) with the rounding error of x - hi carried into a first-order correction, so that a
-// log-sum-exp of magnitude ~10 does not cost the last three bits of the argument.
-__device__ __forceinline__ float exp_shifted(float x, float hi, float lo) {
-    const float s = x - hi;
-    const float err = x - (s + hi);
-    return expf(s) * (1.0f + (err - lo));
+// exp(x - (hi + lo)), lo << 1.  The residual pass only locates a CDF crossing, whose margin (1e-6 of the
+// total mass, flagged) is far above the ~1e-7 |x - hi| relative error of the fast exponential.
+__device__ __forceinline__ float exp_shifted(float x, float hi, float one_minus_lo) {
+    return __expf(x - hi) * one_minus_lo;
 }
 
 struct ResidRow {
@@ -555,84 +557,238 @@ struct ResidRow {
     bool bonus;
 };
 
-// f and p for the four elements starting at v (v % 4 == 0).
-template <bool VEC>
-__device__ __forceinline__ void resid_elems(const ResidRow& r, int n, int V, int v, const float* s_hi,
-                                            const float* s_lo, const float* s_w, float f[4], float p[4]) {
-    const float4 x = load4<VEC>(r.trow, v, V);
+// f and p for S groups of four consecutive elements starting at v[s] (v[s] % 4 == 0; a group at or past V
+// contributes zeros).  Every load is issued before the first use; N is the compile-time number of drafts
+// (0 = run time, one batch of S loads per draft).
+template <bool VEC, int N, int S>
+__device__ __forceinline__ void resid_eval(const ResidRow& r, int n, int V, const int (&v)[S], const float* s_hi,
+                                           const float* s_lo, const float* s_w, float (&f)[S][4], float (&p)[S][4]) {
+    float4 tx[S];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const float xe = f4get(x, e);
-        p[e] = (v + e < V && xe > -INFINITY) ? expf(xe * r.invT - r.pmax) * r.pinvZ : 0.f;
-    }
-    if (r.bonus) {
+    for (int s = 0; s < S; ++s) tx[s] = load4<VEC>(r.trow, v[s], V);
+    float q[S][4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) f[e] = p[e];
-        return;
-    }
-    float q[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int j = 0; j < n; ++j) {
-        const float4 y = load4<VEC>(r.qrows + (size_t)j * V, v, V);
+    for (int s = 0; s < S; ++s)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float ye = f4get(y, e);
-            if (v + e < V && ye > -INFINITY) q[e] += s_w[j] * exp_shifted(ye * r.invT, s_hi[j], s_lo[j]);
+        for (int e = 0; e < 4; ++e) q[s][e] = 0.f;
+    if (!r.bonus) {
+        if (N > 0) {
+            float4 dx[(N > 0) ? N : 1][S];
+#pragma unroll
+            for (int j = 0; j < N; ++j)
+#pragma unroll
+                for (int s = 0; s < S; ++s) dx[j][s] = load4<VEC>(r.qrows + (size_t)j * V, v[s], V);
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+                const float w = s_w[j], hi = s_hi[j], lo = s_lo[j];
+#pragma unroll
+                for (int s = 0; s < S; ++s)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float ye = f4get(dx[j][s], e);
+                        if (ye > -INFINITY) q[s][e] += w * exp_shifted(ye * r.invT, hi, lo);
+                    }
+            }
+        } else {
+            for (int j = 0; j < n; ++j) {
+                float4 y[S];
+#pragma unroll
+                for (int s = 0; s < S; ++s) y[s] = load4<VEC>(r.qrows + (size_t)j * V, v[s], V);
+                const float w = s_w[j], hi = s_hi[j], lo = s_lo[j];
+#pragma unroll
+                for (int s = 0; s < S; ++s)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float ye = f4get(y[s], e);
+                        if (ye > -INFINITY) q[s][e] += w * exp_shifted(ye * r.invT, hi, lo);
+                    }
+            }
         }
     }
 #pragma unroll
-    for (int e = 0; e < 4; ++e) f[e] = fmaxf(0.f, p[e] - q[e]);
+    for (int s = 0; s < S; ++s)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float xe = f4get(tx[s], e);
+            const float pe = (xe > -INFINITY) ? __expf(xe * r.invT - r.pmax) * r.pinvZ : 0.f;
+            p[s][e] = pe;
+            f[s][e] = r.bonus ? pe : fmaxf(0.f, pe - q[s][e]);
+        }
 }
 
-template <bool VEC>
-__global__ __launch_bounds__(kBlock) void k_resid(ResidArgs a) {
+template <bool VEC, int N>
+__global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
+    extern __shared__ __attribute__((aligned(16))) double s_scale[];   // [gamma+1][C3]: exp(m_c - m_row)
     const int c = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int V = a.V, n = a.n, gamma = a.gamma, NSEG = a.NSEG;
-    const float T = a.temperature[b];
-    const bool greedy = !(T > 0.f);
-    int k = a.accept_len[b];
-    k = k < 0 ? 0 : (k > gamma ? gamma : k);
-    const size_t out_idx = (size_t)b * (gamma + 1) + k;
-    if (greedy) {
-        if (c == 0 && tid == 0) a.out_tokens[out_idx] = a.amax[out_idx];
-        return;
-    }
-    __shared__ float s_hi[TABED_MAX_N], s_lo[TABED_MAX_N], s_w[TABED_MAX_N];
+    const int V = a.V, n = (N > 0) ? N : a.n, gamma = a.gamma, NSEG = a.NSEG, C3 = a.C3, RS = a.RS;
+
+    __shared__ double s_rowm[TABED_MAX_GAMMA + 1], s_rowZ[TABED_MAX_GAMMA + 1], s_rowlse[TABED_MAX_GAMMA + 1];
+    __shared__ int s_rowam[TABED_MAX_GAMMA + 1];
+    __shared__ int s_ok[TABED_MAX_GAMMA];
+    __shared__ uint32_t s_aflag[TABED_MAX_GAMMA + 1];
+    __shared__ float s_hi[TABED_MAX_GAMMA][TABED_MAX_N], s_lo[TABED_MAX_GAMMA][TABED_MAX_N], s_w[TABED_MAX_N];
     __shared__ double s_redd[kWavesPerBlock];
-    __shared__ int s_last, s_owner, s_fallback, s_seg;
+    __shared__ int s_last, s_first[kWavesPerBlock], s_lastw[kWavesPerBlock], s_seg;
     __shared__ double s_prefix;
 
+    // ---- everything that does not depend on another load is requested first
+    int y = -1;
+    float rawy = 0.f, uacc = 0.f, qy = 0.f;
+    if (tid < gamma) {
+        y = a.dtok[(size_t)b * gamma + tid];
+        uacc = a.u_acc ? a.u_acc[(size_t)b * gamma + tid] : tabed_uniform(a.seed, a.round, (uint32_t)b, (uint32_t)tid, 1);
+        qy = a.dq[(size_t)b * gamma + tid];
+    }
+    for (int q = tid; q < gamma * n; q += kBlock) {      // draft log-sum-exps of every position, split hi + lo
+        const double l = a.dlse[((size_t)(q / n) * a.B + b) * n + (q % n)];
+        const float hi = (float)l;
+        s_hi[q / n][q % n] = hi;
+        s_lo[q / n][q % n] = (float)(1.0 - (l - (double)hi));      // 1 - lo, the first-order factor of exp(-lo)
+    }
+    if (tid < n) s_w[tid] = a.weights[(size_t)b * n + tid];
+    const float T = a.temperature[b];
+
+    // ---- combine the chunk records of every target row.  A row's C3 chunks sit in an aligned group of
+    //      C3p lanes (C3p = power of two >= C3), so one wave combines 64 / C3p rows per pass with one
+    //      load round trip; rows with more than 64 chunks fall back to one wave per row.
+    const double* sb = a.stats + (size_t)b * (gamma + 1) * C3 * RS;
+    if (C3 <= kWave) {
+        int C3p = 1;
+        while (C3p < C3) C3p <<= 1;
+        const int rows_per_pass = kWave / C3p;
+        const int cc = lane & (C3p - 1);
+        for (int row0 = wave * rows_per_pass; row0 <= gamma; row0 += kWavesPerBlock * rows_per_pass) {
+            const int row = row0 + lane / C3p;
+            const bool live = (row <= gamma && cc < C3);
+            double r0v = -INFINITY, r1v = 0.0;
+            ArgMax am{-INFINITY, 0x7fffffff};
+            if (live) {
+                const double* r = sb + ((size_t)row * C3 + cc) * RS;
+                r0v = r[0]; r1v = r[1];
+                am = ArgMax{(float)r[2], (int)r[3]};
+            }
+            double m = r0v;
+            for (int o = C3p >> 1; o > 0; o >>= 1) m = fmax(m, __shfl_xor(m, o));
+            const double sc = (r0v > -INFINITY) ? exp(r0v - m) : 0.0;
+            if (live) s_scale[row * C3 + cc] = sc;
+            double Z = r1v * sc;
+            for (int o = C3p >> 1; o > 0; o >>= 1) {
+                Z += __shfl_xor(Z, o);
+                const ArgMax other{__shfl_xor(am.v, o), __shfl_xor(am.i, o)};
+                am = argmax_merge(am, other);
+            }
+            if (live && cc == 0) { s_rowm[row] = m; s_rowZ[row] = Z; s_rowlse[row] = m + log(Z); s_rowam[row] = am.i; }
+        }
+    } else {
+        for (int row = wave; row <= gamma; row += kWavesPerBlock) {
+            const double* r0 = sb + (size_t)row * C3 * RS;
+            double m = -INFINITY;
+            for (int cc = lane; cc < C3; cc += kWave) m = fmax(m, r0[(size_t)cc * RS]);
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) m = fmax(m, __shfl_xor(m, o));
+            double Z = 0.0;
+            ArgMax am{-INFINITY, 0x7fffffff};
+            for (int cc = lane; cc < C3; cc += kWave) {
+                const double* r = r0 + (size_t)cc * RS;
+                const double sc = (r[0] > -INFINITY) ? exp(r[0] - m) : 0.0;
+                s_scale[row * C3 + cc] = sc;
+                Z += r[1] * sc;
+                am = argmax_merge(am, ArgMax{(float)r[2], (int)r[3]});
+            }
+            Z = wave_sum(Z);
+            am = wave_argmax(am);
+            if (lane == 0) { s_rowm[row] = m; s_rowZ[row] = Z; s_rowlse[row] = m + log(Z); s_rowam[row] = am.i; }
+        }
+    }
+    const bool greedy = !(T > 0.f);
+    if (greedy && c != 0) return;
+    const float invT = greedy ? 1.f : 1.f / T;
+    const bool y_ok = (y >= 0 && y < V);
+    if (tid < gamma && y_ok && !greedy) rawy = a.target[((size_t)b * (gamma + 1) + tid) * V + y];
+    __syncthreads();
+
+    // ---- gamma accept tests in parallel, k = first failure
+    if (tid < gamma) {
+        uint32_t flag = 0;
+        bool ok;
+        if (!y_ok) { ok = false; flag |= TABED_FLAG_DEGENERATE; }
+        else if (greedy) ok = (y == s_rowam[tid]);
+        else {
+            const float py = (float)exp((double)(rawy * invT) - s_rowlse[tid]);
+            const float lhs = uacc * qy;
+            ok = lhs < py;
+            if (fabs((double)lhs - (double)py) < (double)kMargin * fmax((double)lhs, (double)py))
+                flag |= TABED_FLAG_ACCEPT_MARGIN;
+        }
+        s_ok[tid] = ok ? 1 : 0;
+        s_aflag[tid] = flag;
+    }
+    if (tid == gamma) s_aflag[gamma] = 0;
+    __syncthreads();
+    int k = 0;
+    while (k < gamma && s_ok[k]) ++k;
+    const size_t out_idx = (size_t)b * (gamma + 1) + k;
+
+    // ---- this workgroup's share of the residual (or bonus) row: 2 segments per wave, loads first
     ResidRow r;
     r.bonus = (k == gamma);
-    r.invT = 1.f / T;
+    r.invT = invT;
     r.trow = a.target + out_idx * V;
-    r.pmax = (float)a.lsep[out_idx * 2 + 0];
-    r.pinvZ = (float)a.lsep[out_idx * 2 + 1];
-    r.qrows = r.bonus ? nullptr : a.dlogits + ((size_t)k * a.B + b) * n * V;
-    if (tid < n && !r.bonus) {
-        const double l = a.dlse[((size_t)k * a.B + b) * n + tid];
-        s_hi[tid] = (float)l;
-        s_lo[tid] = (float)(l - (double)s_hi[tid]);
-        s_w[tid] = a.weights[(size_t)b * n + tid];
+    r.pmax = (float)s_rowm[k];
+    r.pinvZ = (float)(1.0 / s_rowZ[k]);
+    r.qrows = r.bonus ? a.dlogits : a.dlogits + ((size_t)k * a.B + b) * n * V;
+    const float* hi_k = s_hi[r.bonus ? 0 : k];
+    const float* lo_k = s_lo[r.bonus ? 0 : k];
+    constexpr int kSegPerChunk = kResidChunkV / kSegV;            // 8
+    constexpr int kSegPerWave = kSegPerChunk / kWavesPerBlock;    // 2
+    float f[kSegPerWave][4], p[kSegPerWave][4];
+    int vs[kSegPerWave];
+    if (!greedy) {
+#pragma unroll
+        for (int s = 0; s < kSegPerWave; ++s) vs[s] = (c * kSegPerChunk + wave + s * kWavesPerBlock) * kSegV + lane * 4;
+        resid_eval<VEC, N, kSegPerWave>(r, n, V, vs, hi_k, lo_k, s_w, f, p);
     }
-    if (tid == 0) { s_owner = kBlock; s_fallback = -1; }
-    __syncthreads();
+
+    if (c == 0) {
+        // ---- distances: thread per (position, draft), chunks in order with the scales computed above
+        for (int q = tid; q < gamma * n; q += kBlock) {
+            const int ii = q / n, j = q % n;
+            const double* r0 = sb + (size_t)ii * C3 * RS + kStatHdr + j;
+            double A = 0.0;
+#pragma unroll 8
+            for (int cc = 0; cc < C3; ++cc) A += r0[(size_t)cc * RS] * s_scale[ii * C3 + cc];
+            const double kl = A / s_rowZ[ii] - s_rowlse[ii] + a.dlse[((size_t)ii * a.B + b) * n + j];
+            a.dev[((size_t)b * gamma + ii) * n + j] = (float)kl;
+        }
+        if (tid <= gamma) {
+            // accepted prefix, -1 padding, flags of the tests that were evaluated; slot k belongs to the sampler
+            if (tid != k) {
+                a.out_tokens[(size_t)b * (gamma + 1) + tid] = tid < k ? y : -1;
+                a.flags[(size_t)b * (gamma + 1) + tid] = (uint8_t)(tid < k ? s_aflag[tid] : 0u);
+            } else if (greedy) {
+                a.out_tokens[out_idx] = s_rowam[k];
+                a.flags[out_idx] = (uint8_t)s_aflag[k];
+            }
+        }
+        if (tid == 0) {
+            a.accept_len[b] = k;
+            a.n_valid[b] = k + 1 < gamma ? k + 1 : gamma;
+        }
+    }
+    if (greedy) return;
 
     double* segR = a.seg + ((size_t)b * 2 + 0) * NSEG;
     double* segP = a.seg + ((size_t)b * 2 + 1) * NSEG;
-    constexpr int kSegPerChunk = kChunkV / kSegV;
-    for (int sidx = wave; sidx < kSegPerChunk; sidx += kWavesPerBlock) {
-        const int seg = c * kSegPerChunk + sidx;
-        if (seg >= NSEG) break;
-        const int v = seg * kSegV + lane * 4;
-        float f[4] = {0.f, 0.f, 0.f, 0.f}, p[4] = {0.f, 0.f, 0.f, 0.f};
-        if (v < V) resid_elems<VEC>(r, n, V, v, s_hi, s_lo, s_w, f, p);
-        const double mf = wave_sum((double)((f[0] + f[1]) + (f[2] + f[3])));
-        const double mp = wave_sum((double)((p[0] + p[1]) + (p[2] + p[3])));
-        if (lane == 0) { segR[seg] = mf; segP[seg] = mp; }
+#pragma unroll
+    for (int s = 0; s < kSegPerWave; ++s) {
+        const int seg = c * kSegPerChunk + wave + s * kWavesPerBlock;
+        const double mf = (double)wave_sum((f[s][0] + f[s][1]) + (f[s][2] + f[s][3]));
+        const double mp = (double)wave_sum((p[s][0] + p[s][1]) + (p[s][2] + p[s][3]));
+        if (lane == 0 && seg < NSEG) { segR[seg] = mf; segP[seg] = mp; }
     }
-    __threadfence();
-    __syncthreads();
+    __syncthreads();                                       // every wave's stores are complete ...
     if (tid == 0) {
+        __threadfence();                                   // ... and one fence publishes them device-wide
         const uint32_t old = atomicAdd(&a.tickets[b], 1u);
         s_last = (old == (uint32_t)(a.C5 - 1));
     }
@@ -644,30 +800,25 @@ __global__ __launch_bounds__(kBlock) void k_resid(ResidArgs a) {
     // ---- last workgroup of sequence b: locate the segment, then the token
     const int S = (NSEG + kBlock - 1) / kBlock;
     const int g0 = min(NSEG, tid * S), g1 = min(NSEG, g0 + S);
-    uint32_t flag = 0;
-    const double* mass = segR;
+    uint32_t flag = s_aflag[k];
+    double runR = 0.0, runP = 0.0;
+    for (int g = g0; g < g1; ++g) { runR += segR[g]; runP += segP[g]; }
+    double run = runP;
+    const double* mass = segP;
     if (!r.bonus) {
-        double run = 0.0;
-        for (int g = g0; g < g1; ++g) run += segR[g];
-        const double Zr = block_sum(run, s_redd);
-        if (!(Zr > 0.0)) { mass = segP; r.bonus = true; flag |= TABED_FLAG_DEGENERATE; }   // empty residual: draw from p_k
+        const double Zr = block_sum(runR, s_redd);
+        if (Zr > 0.0) { run = runR; mass = segR; }
+        else { r.bonus = true; flag |= TABED_FLAG_DEGENERATE; }   // empty residual: draw from p_k
     }
-    double run = 0.0;
-    for (int g = g0; g < g1; ++g) run += mass[g];
     double Z;
     const double excl = block_exclusive_scan(run, s_redd, &Z);
     const float u = a.u_res ? a.u_res[b] : tabed_uniform(a.seed, a.round, (uint32_t)b, (uint32_t)gamma, 0);
     const double target = (double)u * Z;
-    if (run > 0.0) {
-        if (excl + run > target) atomicMin(&s_owner, tid);
-        atomicMax(&s_fallback, tid);
-    }
-    __syncthreads();
-    const int owner = s_owner < kBlock ? s_owner : s_fallback;
+    const int owner = block_find_owner(excl, run, target, s_first, s_lastw);
     if (owner < 0) {
         if (tid == 0) {
             a.out_tokens[out_idx] = 0;
-            a.flags[out_idx] |= (uint8_t)(TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE);
+            a.flags[out_idx] = (uint8_t)(flag | TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE);
         }
         return;
     }
@@ -686,53 +837,79 @@ __global__ __launch_bounds__(kBlock) void k_resid(ResidArgs a) {
     }
     __syncthreads();
     if (tid >= kWave) return;
-    const int v = s_seg * kSegV + lane * 4;
-    float f[4] = {0.f, 0.f, 0.f, 0.f}, p[4] = {0.f, 0.f, 0.f, 0.f};
-    if (v < V) resid_elems<VEC>(r, n, V, v, s_hi, s_lo, s_w, f, p);
-    const double l1 = (double)f[0], l2 = l1 + (double)f[1], l3 = l2 + (double)f[2], l4 = l3 + (double)f[3];
+    const int v1[1] = {s_seg * kSegV + lane * 4};
+    float f1[1][4], p1[1][4];
+    resid_eval<VEC, N, 1>(r, n, V, v1, hi_k, lo_k, s_w, f1, p1);
+    const int v = v1[0];
+    const double l1 = (double)f1[0][0], l2 = l1 + (double)f1[0][1], l3 = l2 + (double)f1[0][2], l4 = l3 + (double)f1[0][3];
     const double base = s_prefix + (wave_inclusive_scan(l4) - l4);
     const double cdf[4] = {base + l1, base + l2, base + l3, base + l4};
     int hit = -1, lastlive = -1;
 #pragma unroll
     for (int e = 3; e >= 0; --e) {
-        if (f[e] > 0.f && cdf[e] > target) hit = e;
-        if (lastlive < 0 && f[e] > 0.f) lastlive = e;
+        if (f1[0][e] > 0.f && cdf[e] > target) hit = e;
+        if (lastlive < 0 && f1[0][e] > 0.f) lastlive = e;
     }
     const unsigned long long cross = __ballot(hit >= 0);
     const unsigned long long live = __ballot(lastlive >= 0);
-    int pick, e;
-    if (cross) { pick = __ffsll((long long)cross) - 1; e = hit; }
-    else if (live) { pick = 63 - __clzll((long long)live); e = lastlive; flag |= TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE; }
-    else { pick = 0; e = 0; flag |= TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE; }
+    int pick;
+    if (cross) pick = __ffsll((long long)cross) - 1;
+    else if (live) { pick = 63 - __clzll((long long)live); flag |= TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE; }
+    else { pick = 0; flag |= TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE; }
     if (lane == pick) {
+        const int e = cross ? hit : (live ? lastlive : 0);
         const int tok = v + e;
         const double tol = (double)kMargin * Z;
-        const double hi_edge = cdf[e], lo_edge = cdf[e] - (double)f[e];
+        const double fe = (double)(e == 0 ? f1[0][0] : e == 1 ? f1[0][1] : e == 2 ? f1[0][2] : f1[0][3]);
+        const double hi_edge = e == 0 ? cdf[0] : e == 1 ? cdf[1] : e == 2 ? cdf[2] : cdf[3];
         if (fabs(hi_edge - target) < tol && tok + 1 < V) flag |= TABED_FLAG_SAMPLE_MARGIN;
-        if (tok > 0 && fabs(lo_edge - target) < tol) flag |= TABED_FLAG_SAMPLE_MARGIN;
+        if (tok > 0 && fabs((hi_edge - fe) - target) < tol) flag |= TABED_FLAG_SAMPLE_MARGIN;
         a.out_tokens[out_idx] = tok < V ? tok : V - 1;
-        a.flags[out_idx] |= (uint8_t)flag;
+        a.flags[out_idx] = (uint8_t)flag;
     }
 }
 
-hipError_t launch_resid(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round,
-                        const float* target_logits, const float* draft_logits, const double* draft_lse,
-                        const float* weights, const float* temperature, const float* u_res,
-                        const int32_t* accept_len, int32_t* out_tokens, uint8_t* flags, hipStream_t s) {
+hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round,
+                         const float* target_logits, const float* draft_logits, const double* draft_lse,
+                         const int32_t* draft_tokens, const float* draft_q, const float* weights,
+                         const float* temperature, const float* u_acc, const float* u_res, int32_t* accept_len,
+                         int32_t* out_tokens, float* dev, int32_t* n_valid, uint8_t* flags, hipStream_t s) {
+    const bool vec = (c.V % 4 == 0);
+    const int ncomp = (vec && (c.n == 2 || c.n == 4 || c.n == 8)) ? c.n : 0;   // compile-time draft counts
+    const int U = pick_stats_unroll(c, ncomp == 8 ? 2 : 4);
+    const int C3 = (c.V + kBlock * 4 * U - 1) / (kBlock * 4 * U);
+    {
+        ProfScope prof(TABED_K_STATS, s);
+        StatsArgs a;
+        a.V = c.V; a.n = c.n; a.B = c.B; a.gamma = c.gamma; a.RS = L.RS; a.C3 = C3;
+        a.target = target_logits; a.dlogits = draft_logits; a.temperature = temperature;
+        a.stats = reinterpret_cast<double*>(ws + L.off_stats);
+        const dim3 grid(C3, c.gamma + 1, c.B);
+        if (!vec) launch_stats_n<false, 0>(U, grid, s, a);
+        else if (ncomp == 2) launch_stats_n<true, 2>(U, grid, s, a);
+        else if (ncomp == 4) launch_stats_n<true, 4>(U, grid, s, a);
+        else if (ncomp == 8) launch_stats_n<true, 8>(U, grid, s, a);
+        else launch_stats_n<true, 0>(U, grid, s, a);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     ProfScope prof(TABED_K_RESID, s);
-    ResidArgs a;
-    a.V = c.V; a.n = c.n; a.B = c.B; a.gamma = c.gamma; a.NSEG = L.NSEG; a.C5 = L.C5;
+    FinishArgs a;
+    a.V = c.V; a.n = c.n; a.B = c.B; a.gamma = c.gamma; a.C3 = C3; a.RS = L.RS; a.NSEG = L.NSEG; a.C5 = L.C5;
     a.seed = c.seed; a.round = round;
-    a.target = target_logits; a.dlogits = draft_logits; a.dlse = draft_lse; a.weights = weights;
-    a.temperature = temperature; a.u_res = u_res; a.accept_len = accept_len;
-    a.lsep = reinterpret_cast<const double*>(ws + L.off_lsep);
-    a.amax = reinterpret_cast<const int32_t*>(ws + L.off_amax);
+    a.target = target_logits; a.dlogits = draft_logits; a.dlse = draft_lse; a.dtok = draft_tokens; a.dq = draft_q;
+    a.weights = weights; a.temperature = temperature; a.u_acc = u_acc; a.u_res = u_res;
+    a.stats = reinterpret_cast<const double*>(ws + L.off_stats);
     a.seg = reinterpret_cast<double*>(ws + L.off_seg);
     a.tickets = reinterpret_cast<uint32_t*>(ws + L.off_tickets) + 2 * c.B;
-    a.out_tokens = out_tokens; a.flags = flags;
+    a.accept_len = accept_len; a.out_tokens = out_tokens; a.dev = dev; a.n_valid = n_valid; a.flags = flags;
     const dim3 grid(L.C5, c.B);
-    if (c.V % 4 == 0) hipLaunchKernelGGL(k_resid<true>, grid, dim3(kBlock), 0, s, a);
-    else              hipLaunchKernelGGL(k_resid<false>, grid, dim3(kBlock), 0, s, a);
+    const size_t lds = sizeof(double) * (size_t)(c.gamma + 1) * C3;
+    if (!vec) hipLaunchKernelGGL((k_finish<false, 0>), grid, dim3(kBlock), lds, s, a);
+    else if (ncomp == 2) hipLaunchKernelGGL((k_finish<true, 2>), grid, dim3(kBlock), lds, s, a);
+    else if (ncomp == 4) hipLaunchKernelGGL((k_finish<true, 4>), grid, dim3(kBlock), lds, s, a);
+    else if (ncomp == 8) hipLaunchKernelGGL((k_finish<true, 8>), grid, dim3(kBlock), lds, s, a);
+    else hipLaunchKernelGGL((k_finish<true, 0>), grid, dim3(kBlock), lds, s, a);
     return hipGetLastError();
 }
 
