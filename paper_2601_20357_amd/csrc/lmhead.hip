@@ -33,25 +33,26 @@ __device__ __forceinline__ float half_sum(float v) {
 }
 
 // Epilogue of one 32x32 accumulator tile: lane holds column (lane % 32) and the 16 rows
-// 8*(r/4) + 4*(lane/32) + r%4.  Writes logits and the tile's softmax partials.
-__device__ __forceinline__ void store_tile_32x32(const f32x16& acc, int m_base, int v_base, int M, int V, int n,
-                                                 int NT, const float* __restrict__ temperature,
-                                                 float* __restrict__ L, float* __restrict__ pm,
-                                                 float* __restrict__ ps) {
+// 8*(r/4) + 4*(lane/32) + r%4 of the block that starts at row m_base.  Writes logits and the tile's softmax
+// partials.  inv_t[i] = 1/T of row m_table0 + i (an LDS table filled by the caller).
+__device__ __forceinline__ void store_tile_32x32(const f32x16& acc, int m_base, int v_base, int M, int V, int NT,
+                                                 const float* inv_t, int m_table0, float* __restrict__ L,
+                                                 float* __restrict__ pm, float* __restrict__ ps) {
     if (v_base >= V) return;
     const int lane = threadIdx.x & 63;
     const int col = lane & 31, half = lane >> 5;
     const int v = v_base + col;
     const int tile = v_base / kTileV;
+    const bool vlive = (v < V);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int m = m_base + 8 * (r / 4) + 4 * half + (r % 4);
         const bool live = (m < M);          // uniform over the half-wave
         const float x = acc[r];
         float s = -INFINITY;
-        if (live && v < V) {
+        if (live && vlive) {
             L[(size_t)m * V + v] = x;
-            s = x * row_inv_temperature(temperature, m, n);
+            s = x * inv_t[m - m_table0];
         }
         const float mx = half_max(s);
         const float e = (s > -INFINITY) ? __expf(s - mx) : 0.f;
@@ -77,8 +78,10 @@ __global__ __launch_bounds__(kBlock) void k_lmhead_bf16(int M, int d, int V, int
                                                         float* __restrict__ ps) {
     __shared__ __attribute__((aligned(16))) uint16_t sA[kBM][kBK + kPad];
     __shared__ __attribute__((aligned(16))) uint16_t sB[kBN][kBK + kPad];
+    __shared__ float s_invt[kBM];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int v0 = blockIdx.x * kBN, m0 = blockIdx.y * kBM;
+    if (tid < kBM && m0 + tid < M) s_invt[tid] = row_inv_temperature(temperature, m0 + tid, n);
     const int wm = wave >> 1, wn = wave & 1;
     const uint16_t* Wg = reinterpret_cast<const uint16_t*>(W);
     const uint16_t* Hg = reinterpret_cast<const uint16_t*>(H);
@@ -118,7 +121,122 @@ __global__ __launch_bounds__(kBlock) void k_lmhead_bf16(int M, int d, int V, int
         }
         __syncthreads();
     }
-    store_tile_32x32(acc, m0 + wm * 32, v0 + wn * 32, M, V, n, NT, temperature, L, pm, ps);
+    store_tile_32x32(acc, m0 + wm * 32, v0 + wn * 32, M, V, NT, s_invt, m0, L, pm, ps);
+}
+
+// ---------------------------------------------------------------- bf16, skinny M (<= 64 rows): W-streaming kernel
+// With n*B <= 64 rows the GEMM moves 2*d bytes of W per n*B*2*d flops: it is bound by streaming W from HBM
+// once, not by the matrix cores.  Design:
+//   * 8 waves per workgroup, one workgroup per compute unit.  All of H (<= 64 x d bf16) is staged once into
+//     LDS (rows padded by 16 bytes, so the 16-byte A-operand reads of 16 consecutive rows hit distinct banks).
+//   * A pair of waves owns one 32-row vocabulary tile; each wave of the pair takes one half of K.  The whole
+//     half-tile of W (KH k-blocks of 32 rows x 128 bytes) is requested up front with coalesced 16-byte loads
+//     (8 lanes cover one row's 128 bytes), so a wave keeps KH*4 KB in flight -- that, not occupancy, is what
+//     saturates HBM.  W is read exactly once; no wave shares W with another.
+//   * The MFMA B operand wants "lane = vocabulary row, 8 consecutive k": each k-block goes through a
+//     wave-private 32 x 144-byte LDS patch that only re-maps lanes (write coalesced layout, read operand
+//     layout); LDS ops of one wave execute in order, so the patch needs no barrier.
+//   * The two K-halves meet through the same patches (one workgroup barrier), each wave finishing one 32-row
+//     block of the 64 x 32 result: logits store + softmax partials of the tile.
+// KH = k-blocks (of 64) per wave = d / 128; MT = 32-row blocks of M (1 or 2).
+constexpr int kSkinnyWaves = 8;
+constexpr int kSkinnyThreads = kSkinnyWaves * 64;
+constexpr int kPatchBytes = 32 * 144;
+
+template <int KH, int MT>
+__global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, int n, int NT, int num_tiles,
+                                                                  const uint16_t* __restrict__ W,
+                                                                  const uint16_t* __restrict__ H,
+                                                                  const float* __restrict__ temperature,
+                                                                  float* __restrict__ L, float* __restrict__ pm,
+                                                                  float* __restrict__ ps) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    __shared__ float s_invt[64];
+    constexpr int d = KH * 128;
+    constexpr int CH = d / 8;                       // 16-byte chunks per row of H / W
+    constexpr int HROW = CH * 16 + 16;              // padded LDS row of H in bytes
+    unsigned char* const ldsH = lds;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int pair = wave & 3, khalf = wave >> 2;
+    unsigned char* const patch = lds + MT * 32 * HROW + wave * kPatchBytes;
+    unsigned char* const partner_patch = lds + MT * 32 * HROW + (wave ^ 4) * kPatchBytes;
+    const int nn = lane & 31, half = lane >> 5;
+    if (tid < M) s_invt[tid] = row_inv_temperature(temperature, tid, n);
+
+    // ---- request H first (it must land before any MFMA), then this wave's first half-tile of W
+    u32x4 hreg[MT * KH];
+#pragma unroll
+    for (int q = 0; q < MT * KH; ++q) {
+        // rows >= M are clamped, not zeroed: their results are never stored
+        const int p = tid + q * kSkinnyThreads, row = min(p / CH, M - 1), c = p % CH;
+        hreg[q] = *reinterpret_cast<const u32x4*>(H + (size_t)row * d + c * 8);
+    }
+    const int lrow = lane >> 3, lchunk = lane & 7;  // coalesced load layout: instruction i covers rows 8i..8i+7
+    u32x4 wreg[KH][4];
+    auto request_tile = [&](int tile) {
+        // vocabulary rows >= V (ragged last tile, idle pair of the last group) are clamped to row V-1: the
+        // epilogue masks them, so no load needs a predicate
+        const int v0 = tile * 32;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int v = min(v0 + 8 * i + lrow, V - 1);
+            const uint16_t* src = W + (size_t)v * d + (size_t)khalf * (KH * 64) + lchunk * 8;
+#pragma unroll
+            for (int kb = 0; kb < KH; ++kb) wreg[kb][i] = *reinterpret_cast<const u32x4*>(src + kb * 64);
+        }
+    };
+    request_tile(blockIdx.x * 4 + pair);
+#pragma unroll
+    for (int q = 0; q < MT * KH; ++q) {
+        const int p = tid + q * kSkinnyThreads, row = p / CH, c = p % CH;
+        *reinterpret_cast<u32x4*>(ldsH + row * HROW + c * 16) = hreg[q];
+    }
+    __syncthreads();
+
+    for (int g = blockIdx.x;; g += gridDim.x) {    // tile group g = 4 tiles, one per wave pair; trip count is
+        const int this_tile = g * 4 + pair;        // uniform over the workgroup (barriers inside)
+        f32x16 acc[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < KH; ++kb) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                *reinterpret_cast<u32x4*>(patch + (8 * i + lrow) * 144 + lchunk * 16) = wreg[kb][i];
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const bf16x8 bv = *reinterpret_cast<const bf16x8*>(patch + nn * 144 + (2 * ks + half) * 16);
+                const int hc = (khalf * KH + kb) * 8 + 2 * ks + half;       // chunk index inside H's row
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const bf16x8 av = *reinterpret_cast<const bf16x8*>(ldsH + (mt * 32 + nn) * HROW + hc * 16);
+                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[mt], 0, 0, 0);
+                }
+            }
+        }
+        const bool more = ((g + (int)gridDim.x) * 4 < num_tiles);   // this workgroup has another tile group
+        if (more) request_tile(this_tile + (int)gridDim.x * 4);
+
+        // ---- the two K-halves meet: each wave hands the partner the 32-row block the partner finishes
+        //      (MT == 2: wave khalf finishes block khalf; MT == 1: the khalf == 0 wave finishes block 0)
+        f32x16 fin = acc[0], giv = acc[MT - 1];
+        if (MT == 2 && khalf == 1) { fin = acc[MT - 1]; giv = acc[0]; }
+        if (MT == 2 || khalf == 1) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) *reinterpret_cast<float*>(patch + r * 256 + lane * 4) = giv[r];
+        }
+        __syncthreads();
+        if (MT == 2 || khalf == 0) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) fin[r] += *reinterpret_cast<const float*>(partner_patch + r * 256 + lane * 4);
+            if (this_tile < num_tiles)
+                store_tile_32x32(fin, (MT == 2) ? khalf * 32 : 0, this_tile * 32, M, V, NT, s_invt, 0, L, pm, ps);
+        }
+        if (!more) break;
+        __syncthreads();                               // partner finished reading this wave's patch
+    }
 }
 
 // ---------------------------------------------------------------- fp32 operands: one output per thread
@@ -152,6 +270,44 @@ __global__ __launch_bounds__(kBlock) void k_lmhead_f32(int M, int d, int V, int 
     }
 }
 
+static bool skinny_applies(const tabed_cfg& c, int M) {
+    if (c.w_dtype != 1 || M > 64 || c.d % 128 != 0) return false;
+    const int KH = c.d / 128, MT = (M + 31) / 32;
+    if (KH != 4 && KH != 6 && KH != 7 && KH != 8) return false;
+    const size_t lds = (size_t)MT * 32 * (c.d * 2 + 16) + (size_t)kSkinnyWaves * kPatchBytes;
+    return lds <= 160 * 1024;
+}
+
+template <int KH, int MT>
+static void launch_skinny_t(const tabed_cfg& c, const WsLayout& Lay, int M, const void* W, const void* H,
+                            const float* temperature, float* logits, float* pm, float* ps, hipStream_t s) {
+    const size_t lds = (size_t)MT * 32 * (KH * 256 + 16) + (size_t)kSkinnyWaves * kPatchBytes;
+    static bool attr_set = false;                      // raise the dynamic-LDS limit of this instantiation once
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_lmhead_skinny<KH, MT>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr_set = true;
+    }
+    const int num_tiles = Lay.NT;
+    int cus = 256;
+    const int groups = (num_tiles + 3) / 4;
+    const dim3 grid(groups < cus ? groups : cus);
+    hipLaunchKernelGGL((k_lmhead_skinny<KH, MT>), grid, dim3(kSkinnyThreads), lds, s, M, c.V, c.n, Lay.NT, num_tiles,
+                       static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), temperature, logits, pm, ps);
+}
+
+static void launch_skinny(const tabed_cfg& c, const WsLayout& Lay, int M, const void* W, const void* H,
+                          const float* temperature, float* logits, float* pm, float* ps, hipStream_t s) {
+    const int KH = c.d / 128, MT = (M + 31) / 32;
+#define TABED_SKINNY(KH_)                                                                              \
+    if (KH == KH_) {                                                                                   \
+        if (MT == 1) launch_skinny_t<KH_, 1>(c, Lay, M, W, H, temperature, logits, pm, ps, s);         \
+        else         launch_skinny_t<KH_, 2>(c, Lay, M, W, H, temperature, logits, pm, ps, s);         \
+    }
+    TABED_SKINNY(4) TABED_SKINNY(6) TABED_SKINNY(7) TABED_SKINNY(8)
+#undef TABED_SKINNY
+}
+
 hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& Lay, char* ws, const void* W, const void* H,
                          const float* temperature, float* logits, hipStream_t s) {
     ProfScope prof(TABED_K_LMHEAD, s);
@@ -162,6 +318,8 @@ hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& Lay, char* ws, cons
         const dim3 grid(Lay.NT, (M + 7) / 8);
         hipLaunchKernelGGL(k_lmhead_f32, grid, dim3(kBlock), 0, s, M, c.d, c.V, c.n, Lay.NT,
                            static_cast<const float*>(W), static_cast<const float*>(H), temperature, logits, pm, ps);
+    } else if (skinny_applies(c, M)) {
+        launch_skinny(c, Lay, M, W, H, temperature, logits, pm, ps, s);
     } else {
         const dim3 grid((c.V + kBN - 1) / kBN, (M + kBM - 1) / kBM);
         hipLaunchKernelGGL(k_lmhead_bf16, grid, dim3(kBlock), 0, s, M, c.d, c.V, c.n, Lay.NT,

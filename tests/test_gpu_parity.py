@@ -49,6 +49,12 @@ SHAPES = [
     (257,    40,  16, 2, 2,    2, 0, "one"),        # maximum number of drafts, fp32 storage
     (5000,   64,  5, 70, 2,    3, 1, "mixed07"),    # more rows than one 64-row MFMA tile
     (1,      8,   2, 2, 2,     2, 0, "one"),        # single-token vocabulary
+    # shapes that take the W-streaming LM-head kernel (bf16, n*B <= 64, d in {512, 768, 896, 1024})
+    (1000,   512, 2, 3, 2,     4, 1, "one"),        # one 32-row block of M, ragged last vocabulary tile
+    (2084,   896, 4, 8, 2,     3, 1, "mixed07"),    # n*B = 32, tile count not a multiple of 4
+    (4099,  1024, 4, 16, 2,    3, 1, "one"),        # n*B = 64, V % 4 != 0
+    (40000,  768, 4, 16, 1,    3, 1, "one"),        # more tile groups than workgroups: persistent loop runs twice
+    (33000,  768, 3, 11, 2,    3, 1, "greedy"),     # n*B = 33: second row block almost empty
 ]
 
 
