@@ -64,6 +64,51 @@ __device__ __forceinline__ void store_tile_32x32(const f32x16& acc, int m_base, 
     }
 }
 
+// Epilogue of one 32x32 accumulator tile held TRANSPOSED: lane holds result row m_base + lane % 32 and the 16
+// vocabulary entries v_base + 8*(r/4) + 4*(lane/32) + r%4.  The softmax partials of a row are then a
+// 16-value in-register reduction plus one exchange between the two half-waves, and every lane stores four
+// runs of four consecutive logits.  inv_t[m] = 1/T of row m (LDS table).
+__device__ __forceinline__ void store_tile_32x32_t(const f32x16& acc, int m_base, int v_base, int M, int V, int NT,
+                                                   const float* inv_t, float* __restrict__ L,
+                                                   float* __restrict__ pm, float* __restrict__ ps) {
+    if (v_base >= V) return;
+    const int lane = threadIdx.x & 63;
+    const int col = lane & 31, half = lane >> 5;
+    const int m = m_base + col;
+    const bool live = (m < M);
+    const float it = live ? inv_t[m] : 1.f;
+    float sc[16];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int v = v_base + 8 * (r / 4) + 4 * half + (r % 4);
+        sc[r] = (live && v < V) ? acc[r] * it : -INFINITY;
+        mx = fmaxf(mx, sc[r]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    float sum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum += (sc[r] > -INFINITY) ? __expf(sc[r] - mx) : 0.f;
+    sum += __shfl_xor(sum, 32);
+    if (live && half == 0) {
+        pm[(size_t)m * NT + v_base / kTileV] = mx;
+        ps[(size_t)m * NT + v_base / kTileV] = sum;
+    }
+    if (!live) return;
+    float* row = L + (size_t)m * V;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int v4 = v_base + 8 * g + 4 * half;
+        if ((V & 3) == 0) {
+            if (v4 < V) *reinterpret_cast<float4*>(row + v4) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (v4 + e < V) row[v4 + e] = acc[4 * g + e];
+        }
+    }
+}
+
 // ---------------------------------------------------------------- bf16, any shape: LDS-tiled MFMA GEMM
 // Workgroup tile 64 (rows) x 64 (vocabulary) x 64 (k); wave w owns the 32x32 quadrant (w/2, w%2).
 // Both operands are K-contiguous in memory, which is exactly the per-lane 8-element run the MFMA wants,
@@ -139,6 +184,12 @@ __global__ __launch_bounds__(kBlock) void k_lmhead_bf16(int M, int d, int V, int
 //   * The two K-halves meet through the same patches (one workgroup barrier), each wave finishing one 32-row
 //     block of the 64 x 32 result: logits store + softmax partials of the tile.
 // KH = k-blocks (of 64) per wave = d / 128; MT = 32-row blocks of M (1 or 2).
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global
+// load (vmcnt(0)); here that would stall the kernel until all of W has arrived.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 constexpr int kSkinnyWaves = 8;
 constexpr int kSkinnyThreads = kSkinnyWaves * 64;
 constexpr int kPatchBytes = 32 * 144;
@@ -171,27 +222,35 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
         const int p = tid + q * kSkinnyThreads, row = min(p / CH, M - 1), c = p % CH;
         hreg[q] = *reinterpret_cast<const u32x4*>(H + (size_t)row * d + c * 8);
     }
+    // Every wave's H requests enter the memory pipeline before any wave's W requests (a bare barrier: no
+    // wait for data), so H is not queued behind 190 KB of W and the staging barrier below comes early.
+    __builtin_amdgcn_s_barrier();
     const int lrow = lane >> 3, lchunk = lane & 7;  // coalesced load layout: instruction i covers rows 8i..8i+7
     u32x4 wreg[KH][4];
     auto request_tile = [&](int tile) {
         // vocabulary rows >= V (ragged last tile, idle pair of the last group) are clamped to row V-1: the
         // epilogue masks them, so no load needs a predicate
         const int v0 = tile * 32;
+        const uint16_t* src[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int v = min(v0 + 8 * i + lrow, V - 1);
-            const uint16_t* src = W + (size_t)v * d + (size_t)khalf * (KH * 64) + lchunk * 8;
-#pragma unroll
-            for (int kb = 0; kb < KH; ++kb) wreg[kb][i] = *reinterpret_cast<const u32x4*>(src + kb * 64);
+            src[i] = W + (size_t)v * d + (size_t)khalf * (KH * 64) + lchunk * 8;
         }
+        // k-block-major issue order: loads return in order, so k-block 0 is complete after 4 loads, not 19
+#pragma unroll
+        for (int kb = 0; kb < KH; ++kb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) wreg[kb][i] = *reinterpret_cast<const u32x4*>(src[i] + kb * 64);
     };
     request_tile(blockIdx.x * 4 + pair);
+    __builtin_amdgcn_sched_barrier(0);             // keep every W request ahead of the first wait on H
 #pragma unroll
     for (int q = 0; q < MT * KH; ++q) {
         const int p = tid + q * kSkinnyThreads, row = p / CH, c = p % CH;
         *reinterpret_cast<u32x4*>(ldsH + row * HROW + c * 16) = hreg[q];
     }
-    __syncthreads();
+    lds_barrier();                                 // also publishes s_invt
 
     for (int g = blockIdx.x;; g += gridDim.x) {    // tile group g = 4 tiles, one per wave pair; trip count is
         const int this_tile = g * 4 + pair;        // uniform over the workgroup (barriers inside)
@@ -212,7 +271,8 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
                     const bf16x8 av = *reinterpret_cast<const bf16x8*>(ldsH + (mt * 32 + nn) * HROW + hc * 16);
-                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[mt], 0, 0, 0);
+                    // W fragment as the row operand: the accumulator comes out as [vocabulary][result row]
+                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv, av, acc[mt], 0, 0, 0);
                 }
             }
         }
@@ -225,17 +285,22 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
         if (MT == 2 && khalf == 1) { fin = acc[MT - 1]; giv = acc[0]; }
         if (MT == 2 || khalf == 1) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) *reinterpret_cast<float*>(patch + r * 256 + lane * 4) = giv[r];
+            for (int g = 0; g < 4; ++g)
+                *reinterpret_cast<float4*>(patch + g * 1024 + lane * 16) =
+                    make_float4(giv[4 * g], giv[4 * g + 1], giv[4 * g + 2], giv[4 * g + 3]);
         }
-        __syncthreads();
+        lds_barrier();
         if (MT == 2 || khalf == 0) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) fin[r] += *reinterpret_cast<const float*>(partner_patch + r * 256 + lane * 4);
+            for (int g = 0; g < 4; ++g) {
+                const float4 o = *reinterpret_cast<const float4*>(partner_patch + g * 1024 + lane * 16);
+                fin[4 * g] += o.x; fin[4 * g + 1] += o.y; fin[4 * g + 2] += o.z; fin[4 * g + 3] += o.w;
+            }
             if (this_tile < num_tiles)
-                store_tile_32x32(fin, (MT == 2) ? khalf * 32 : 0, this_tile * 32, M, V, NT, s_invt, 0, L, pm, ps);
+                store_tile_32x32_t(fin, (MT == 2) ? khalf * 32 : 0, this_tile * 32, M, V, NT, s_invt, L, pm, ps);
         }
         if (!more) break;
-        __syncthreads();                               // partner finished reading this wave's patch
+        lds_barrier();                                 // partner finished reading this wave's patch
     }
 }
 
