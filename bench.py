@@ -23,6 +23,10 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# HBM bytes per LM-head launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each in its own run, scaled by what
+# the counters read for a plain 256 MiB device copy): profiles/serving_hbm_traffic.md.  None = not measured.
+MEASURED_LMHEAD_TRAFFIC_BYTES = {"serving": (50.05 + 9.22) * 1e6}
+
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
 
@@ -38,6 +42,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rounds", type=int, default=12)
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MB",
+                    help="only run a plain device copy of MB megabytes 10 times: the known-size kernel against "
+                         "which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     return ap.parse_args()
 
 
@@ -107,6 +114,17 @@ def main():
     import torch
     from paper_2601_20357_amd import binding, synth
 
+    if args.calibrate_copy:
+        nbytes = args.calibrate_copy << 20
+        src = torch.ones(nbytes // 4, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "device copy", "bytes_read_per_launch": nbytes,
+                          "bytes_written_per_launch": nbytes, "launches": 10}), flush=True)
+        return
+
     wl = synth.WORKLOADS[args.workload]
     device = "cuda:0"
     torch.cuda.set_device(0)
@@ -161,16 +179,20 @@ def main():
         binding.tabed_prof_reset()
         binding.tabed_prof_enable(True)
         dt_inst = timed(args.steps)
+        for _ in range(200):                       # cost of one event pair + one dispatch, same stream
+            binding.tabed_prof_null()
         binding.tabed_prof_enable(False)
         for kid in range(binding.K_COUNT):
             ms, cnt = binding.tabed_prof_read(kid)
             if cnt:
                 kernels[binding.tabed_kernel_name(kid)] = {"avg_us": ms / cnt * 1e3, "launches": cnt}
-        lm_us = kernels["lmhead"]["avg_us"]
+        lm_us = kernels["lmhead"]["avg_us"]                 # raw event figure: includes the event-pair overhead
+        null_us = kernels.get("null", {}).get("avg_us", 0.0)
         achieved = lm_bytes / (lm_us * 1e-6) / 1e9
         roofline = {"kernel": "lmhead", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_LMHEAD_TRAFFIC_BYTES.get(wl.name),
                     "algorithmic_bytes_per_launch": lm_bytes, "avg_launch_us": lm_us,
+                    "event_pair_overhead_us": null_us, "avg_launch_us_net_of_event_overhead": lm_us - null_us,
                     "mfma_tflops": lm_flops / (lm_us * 1e-6) / 1e12,
                     "mfma_frac_of_bf16_peak": lm_flops / (lm_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                     "instrumented_ms_per_step": dt_inst / args.steps * 1e3}

@@ -180,11 +180,16 @@ int tabed_philox_uniforms(const tabed_cfg* cfg, uint64_t round, float* out, void
 #define TABED_K_STATS 2   /* target statistics + distances + accept chain */
 #define TABED_K_RESID 3   /* corrected / bonus token            */
 #define TABED_K_WEIGHTS 4 /* window + weights                   */
-#define TABED_K_COUNT 5
+#define TABED_K_NULL 5    /* empty kernel, see tabed_prof_null  */
+#define TABED_K_COUNT 6
 int tabed_prof_enable(int on);
 int tabed_prof_read(int id, double* total_ms, int64_t* launches);
 int tabed_prof_reset(void);
 const char* tabed_kernel_name(int id);
+/* Launches an empty kernel on `stream`, bracketed like the others when timing is enabled: what
+ * tabed_prof_read(TABED_K_NULL, ...) then reports is the cost of the event pair plus one dispatch,
+ * i.e. how much the per-kernel figures above exceed the kernels' own run time. */
+int tabed_prof_null(void* stream);
 
 #ifdef __cplusplus
 }

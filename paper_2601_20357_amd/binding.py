@@ -15,11 +15,11 @@ LIB_PATH = os.path.join(_HERE, "libtabed.so")
 EXPORTS = [
     "tabed_workspace_bytes", "tabed_workspace_init", "tabed_strerror", "tabed_last_hip_error",
     "tabed_draft_step", "tabed_verify", "tabed_update_weights", "tabed_philox_uniforms",
-    "tabed_prof_enable", "tabed_prof_read", "tabed_prof_reset", "tabed_kernel_name",
+    "tabed_prof_enable", "tabed_prof_read", "tabed_prof_reset", "tabed_kernel_name", "tabed_prof_null",
 ]
 
 FLAG_ACCEPT_MARGIN, FLAG_SAMPLE_MARGIN, FLAG_DEGENERATE = 1, 2, 4
-K_LMHEAD, K_SAMPLE, K_STATS, K_RESID, K_WEIGHTS, K_COUNT = 0, 1, 2, 3, 4, 5
+K_LMHEAD, K_SAMPLE, K_STATS, K_RESID, K_WEIGHTS, K_NULL, K_COUNT = 0, 1, 2, 3, 4, 5, 6
 
 
 class TabedCfg(C.Structure):
@@ -69,6 +69,8 @@ def load():
     lib.tabed_prof_reset.restype = C.c_int
     lib.tabed_kernel_name.restype = C.c_char_p
     lib.tabed_kernel_name.argtypes = [C.c_int]
+    lib.tabed_prof_null.restype = C.c_int
+    lib.tabed_prof_null.argtypes = [vp]
     _lib = lib
     return lib
 
@@ -196,6 +198,10 @@ def tabed_prof_read(kernel_id: int):
     ms, cnt = C.c_double(0), C.c_int64(0)
     _check(load().tabed_prof_read(kernel_id, C.byref(ms), C.byref(cnt)), "tabed_prof_read")
     return ms.value, cnt.value
+
+
+def tabed_prof_null(stream=None):
+    _check(load().tabed_prof_null(_stream(stream)), "tabed_prof_null")
 
 
 def tabed_kernel_name(kernel_id: int) -> str:

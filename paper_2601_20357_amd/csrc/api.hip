@@ -209,6 +209,11 @@ int tabed_prof_reset(void) {
     return TABED_OK;
 }
 
+int tabed_prof_null(void* stream) {
+    const hipError_t e = launch_null(static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? TABED_OK : fail_hip(e);
+}
+
 const char* tabed_kernel_name(int id) {
     switch (id) {
         case TABED_K_LMHEAD: return "lmhead";
@@ -216,6 +221,7 @@ const char* tabed_kernel_name(int id) {
         case TABED_K_STATS: return "stats";
         case TABED_K_RESID: return "resid";
         case TABED_K_WEIGHTS: return "weights";
+        case TABED_K_NULL: return "null";
         default: return "?";
     }
 }

@@ -59,6 +59,8 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
 hipError_t launch_weights(const tabed_cfg& c, const float* dev, const int32_t* n_valid, float* ring,
                           int32_t* ring_head, int32_t* ring_count, float* weights, hipStream_t s);
 
+hipError_t launch_null(hipStream_t s);
+
 hipError_t launch_philox(const tabed_cfg& c, uint64_t round, float* out, hipStream_t s);
 
 // ---------------------------------------------------------------- event timing

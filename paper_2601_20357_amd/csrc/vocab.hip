@@ -22,6 +22,14 @@ hipError_t launch_ws_init(const tabed_cfg& c, const WsLayout& L, char* ws, hipSt
     return hipGetLastError();
 }
 
+__global__ void k_null() {}
+
+hipError_t launch_null(hipStream_t s) {
+    ProfScope prof(TABED_K_NULL, s);
+    hipLaunchKernelGGL(k_null, dim3(1), dim3(64), 0, s);
+    return hipGetLastError();
+}
+
 __global__ void k_philox(uint64_t seed, uint64_t round, int B, int npos, float* out) {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= B * npos) return;
