@@ -14,6 +14,7 @@ namespace tabed {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 __device__ __forceinline__ float row_inv_temperature(const float* temperature, int row, int n) {
     const float T = temperature[row / n];
@@ -100,6 +101,7 @@ __device__ __forceinline__ void store_tile_32x32_t(const f32x16& acc, int m_base
     for (int g = 0; g < 4; ++g) {
         const int v4 = v_base + 8 * g + 4 * half;
         if ((V & 3) == 0) {
+            // plain stores: streaming (nontemporal) stores measured 8 % slower for this kernel on MI355X
             if (v4 < V) *reinterpret_cast<float4*>(row + v4) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
         } else {
 #pragma unroll
@@ -214,7 +216,7 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
     const int nn = lane & 31, half = lane >> 5;
     if (tid < M) s_invt[tid] = row_inv_temperature(temperature, tid, n);
 
-    // ---- request H first (it must land before any MFMA), then this wave's first half-tile of W
+    // ---- request H first (it must land before any MFMA)
     u32x4 hreg[MT * KH];
 #pragma unroll
     for (int q = 0; q < MT * KH; ++q) {
@@ -222,35 +224,39 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
         const int p = tid + q * kSkinnyThreads, row = min(p / CH, M - 1), c = p % CH;
         hreg[q] = *reinterpret_cast<const u32x4*>(H + (size_t)row * d + c * 8);
     }
-    // Every wave's H requests enter the memory pipeline before any wave's W requests (a bare barrier: no
-    // wait for data), so H is not queued behind 190 KB of W and the staging barrier below comes early.
-    __builtin_amdgcn_s_barrier();
     const int lrow = lane >> 3, lchunk = lane & 7;  // coalesced load layout: instruction i covers rows 8i..8i+7
     u32x4 wreg[KH][4];
-    auto request_tile = [&](int tile) {
-        // vocabulary rows >= V (ragged last tile, idle pair of the last group) are clamped to row V-1: the
-        // epilogue masks them, so no load needs a predicate
-        const int v0 = tile * 32;
-        const uint16_t* src[4];
+    // Requests of one k-block (4 coalesced 16-byte loads per lane).  Vocabulary rows >= V (ragged last tile,
+    // idle pair of the last group) are clamped to row V-1: the epilogue masks them, so no load is predicated.
+    // (element offsets from W, not pointers: a pointer carried in an array degrades to a flat address and
+    // flat loads also count as LDS traffic, which would stall every LDS read behind them)
+    auto aim_tile = [&](size_t (&off)[4], int tile) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int v = min(v0 + 8 * i + lrow, V - 1);
-            src[i] = W + (size_t)v * d + (size_t)khalf * (KH * 64) + lchunk * 8;
+            const int v = min(tile * 32 + 8 * i + lrow, V - 1);
+            off[i] = (size_t)v * d + (size_t)khalf * (KH * 64) + lchunk * 8;
         }
-        // k-block-major issue order: loads return in order, so k-block 0 is complete after 4 loads, not 19
-#pragma unroll
-        for (int kb = 0; kb < KH; ++kb)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) wreg[kb][i] = *reinterpret_cast<const u32x4*>(src[i] + kb * 64);
     };
-    request_tile(blockIdx.x * 4 + pair);
-    __builtin_amdgcn_sched_barrier(0);             // keep every W request ahead of the first wait on H
+    auto request_kblock = [&](const size_t (&off)[4], int kb) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) wreg[kb][i] = *reinterpret_cast<const u32x4*>(W + off[i] + kb * 64);
+    };
+    // H lands in LDS and the workgroup meets BEFORE the first W request goes out.  Measured on MI355X: a
+    // compute unit accepts only a bounded number of outstanding requests, so issuing a whole half-tile takes
+    // about as long as streaming it, and with W queued behind it H came back ~5 us late.  So: H alone first
+    // (~1.7 us), then W k-block by k-block, kPF k-blocks ahead of the one being multiplied.
 #pragma unroll
     for (int q = 0; q < MT * KH; ++q) {
         const int p = tid + q * kSkinnyThreads, row = p / CH, c = p % CH;
         *reinterpret_cast<u32x4*>(ldsH + row * HROW + c * 16) = hreg[q];
     }
     lds_barrier();                                 // also publishes s_invt
+    constexpr int kPF = (KH < 3) ? KH : 3;
+    size_t src[4];                                 // the tile whose k-blocks are being requested
+    aim_tile(src, blockIdx.x * 4 + pair);
+#pragma unroll
+    for (int kb = 0; kb < kPF; ++kb) request_kblock(src, kb);
+    __builtin_amdgcn_sched_barrier(0);
 
     for (int g = blockIdx.x;; g += gridDim.x) {    // tile group g = 4 tiles, one per wave pair; trip count is
         const int this_tile = g * 4 + pair;        // uniform over the workgroup (barriers inside)
@@ -259,11 +265,20 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
+        const bool more = ((g + (int)gridDim.x) * 4 < num_tiles);   // this workgroup has another tile group
+        size_t nsrc[4];
+        aim_tile(nsrc, more ? this_tile + (int)gridDim.x * 4 : this_tile);
 #pragma unroll
         for (int kb = 0; kb < KH; ++kb) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 *reinterpret_cast<u32x4*>(patch + (8 * i + lrow) * 144 + lchunk * 16) = wreg[kb][i];
+            // the registers of k-block kb are free again: request the k-block kPF ahead (of this tile, or of
+            // the workgroup's next tile once this one is fully requested)
+            __builtin_amdgcn_sched_barrier(0);
+            if (kb + kPF < KH) request_kblock(src, kb + kPF);
+            else if (more) request_kblock(nsrc, kb + kPF - KH);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 const bf16x8 bv = *reinterpret_cast<const bf16x8*>(patch + nn * 144 + (2 * ks + half) * 16);
@@ -276,8 +291,6 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
                 }
             }
         }
-        const bool more = ((g + (int)gridDim.x) * 4 < num_tiles);   // this workgroup has another tile group
-        if (more) request_tile(this_tile + (int)gridDim.x * 4);
 
         // ---- the two K-halves meet: each wave hands the partner the 32-row block the partner finishes
         //      (MT == 2: wave khalf finishes block khalf; MT == 1: the khalf == 0 wave finishes block 0)
@@ -300,6 +313,8 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
                 store_tile_32x32_t(fin, (MT == 2) ? khalf * 32 : 0, this_tile * 32, M, V, NT, s_invt, L, pm, ps);
         }
         if (!more) break;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) src[i] = nsrc[i];
         lds_barrier();                                 // partner finished reading this wave's patch
     }
 }
