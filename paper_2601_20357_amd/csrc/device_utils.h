@@ -90,6 +90,39 @@ __device__ __forceinline__ int block_find_owner(double excl, double run, double 
     return first != 0x7fffffff ? first : last;
 }
 
+// ---------------------------------------------------------------- publishing partial results across workgroups
+// "Last workgroup done" hand-over without a release/acquire fence.  On gfx950 an agent-scope fence writes
+// back and invalidates the whole L2 of the XCD (measured 2-3 us per fence inside these kernels); device-scope
+// atomic accesses instead go to the coherence point directly.  Protocol: every partial result is written
+// with publish_store(); the workgroup then meets at __syncthreads(), which also waits until those stores
+// have been acknowledged; one thread bumps the arrival counter with arrive(); the workgroup that sees the
+// final count reads the partial results with published_load() only.
+__device__ __forceinline__ void publish_store(double* p, double v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void publish_store(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void publish_store(int* p, int v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double published_load(const double* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float published_load(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int published_load(const int* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Returns true in the workgroup whose arrival completes `expected`; that workgroup also re-arms the counter.
+__device__ __forceinline__ bool arrive(uint32_t* counter, uint32_t expected) {
+    const uint32_t old = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old != expected - 1) return false;
+    __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return true;
+}
+
 // ---------------------------------------------------------------- arg-max with runner-up
 struct Top2 {
     float v1;  // maximum

@@ -321,22 +321,22 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
     if (tid == 0) {
         Top2 t = s_top[0];
         for (int w = 1; w < kWavesPerBlock; ++w) t = top2_merge(t, s_top[w]);
-        a.cand[(size_t)b * a.C2 + c] = Top2Rec{t.v1, t.i1, t.v2, 0};
-        __threadfence();                                   // one fence per workgroup: the writer itself
-        const uint32_t old = atomicAdd(&a.tickets[b], 1u);
-        s_last = (old == (uint32_t)(a.C2 - 1));
+        Top2Rec* rec = &a.cand[(size_t)b * a.C2 + c];
+        publish_store(&rec->v1, t.v1);
+        publish_store(&rec->i1, t.i1);
+        publish_store(&rec->v2, t.v2);
     }
+    __syncthreads();                                       // the candidate's stores are acknowledged
+    if (tid == 0) s_last = arrive(&a.tickets[b], (uint32_t)a.C2) ? 1 : 0;
     __syncthreads();
     if (!s_last || tid >= kWave) return;
-    __threadfence();
     Top2 t = top2_empty();
     for (int cc = lane; cc < a.C2; cc += kWave) {
-        const Top2Rec r = a.cand[(size_t)b * a.C2 + cc];
-        t = top2_merge(t, Top2{r.v1, r.i1, r.v2});
+        const Top2Rec* r = &a.cand[(size_t)b * a.C2 + cc];
+        t = top2_merge(t, Top2{published_load(&r->v1), published_load(&r->i1), published_load(&r->v2)});
     }
     t = wave_top2(t);
     if (lane != 0) return;
-    a.tickets[b] = 0u;
     const int y = (t.i1 >= 0 && t.i1 < V) ? t.i1 : 0;
     double f = 0.0;
     for (int j = 0; j < n; ++j) f += s_c[j] * (double)__expf(rows[(size_t)j * V + y] * invT - s_m[j]);
@@ -792,25 +792,19 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
         const int seg = c * kSegPerChunk + wave + s * kWavesPerBlock;
         const double mf = (double)wave_sum((f[s][0] + f[s][1]) + (f[s][2] + f[s][3]));
         const double mp = (double)wave_sum((p[s][0] + p[s][1]) + (p[s][2] + p[s][3]));
-        if (lane == 0 && seg < NSEG) { segR[seg] = mf; segP[seg] = mp; }
+        if (lane == 0 && seg < NSEG) { publish_store(&segR[seg], mf); publish_store(&segP[seg], mp); }
     }
-    __syncthreads();                                       // every wave's stores are complete ...
-    if (tid == 0) {
-        __threadfence();                                   // ... and one fence publishes them device-wide
-        const uint32_t old = atomicAdd(&a.tickets[b], 1u);
-        s_last = (old == (uint32_t)(a.C5 - 1));
-    }
+    __syncthreads();                                       // every wave's mass stores are acknowledged
+    if (tid == 0) s_last = arrive(&a.tickets[b], (uint32_t)a.C5) ? 1 : 0;
     __syncthreads();
     if (!s_last) return;
-    __threadfence();
-    if (tid == 0) a.tickets[b] = 0u;
 
     // ---- last workgroup of sequence b: locate the segment, then the token
     const int S = (NSEG + kBlock - 1) / kBlock;
     const int g0 = min(NSEG, tid * S), g1 = min(NSEG, g0 + S);
     uint32_t flag = s_aflag[k];
     double runR = 0.0, runP = 0.0;
-    for (int g = g0; g < g1; ++g) { runR += segR[g]; runP += segP[g]; }
+    for (int g = g0; g < g1; ++g) { runR += published_load(&segR[g]); runP += published_load(&segP[g]); }
     double run = runP;
     const double* mass = segP;
     if (!r.bonus) {
@@ -834,7 +828,7 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
         double P = excl, Plast = excl;
         int gstar = -1, glast = g0;
         for (int g = g0; g < g1; ++g) {
-            const double mg = mass[g];
+            const double mg = published_load(&mass[g]);
             if (mg > 0.0) { glast = g; Plast = P; }
             if (P + mg > target) { gstar = g; break; }
             P += mg;
