@@ -10,21 +10,59 @@ namespace tabed {
 
 constexpr float kMargin = 1e-6f;        // decisions closer than this (relative) are flagged
 
-// ---------------------------------------------------------------- wave64 butterflies (deterministic order)
+// ---------------------------------------------------------------- wave64 reductions (deterministic order)
+// Four DPP steps (lane^1, lane^2, mirror within 8, mirror within 16) leave every lane of a 16-lane row with
+// the row's result; the four row results are then read as scalars (v_readlane) and combined in row order.
+// No LDS traffic and no index registers, unlike ds_bpermute-based shuffles.
+constexpr int kDppXor1 = 0xB1;          // quad_perm:[1,0,3,2]
+constexpr int kDppXor2 = 0x4E;          // quad_perm:[2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;   // lane i <- lane 7 - i   (within 8)
+constexpr int kDppMirror = 0x140;       // lane i <- lane 15 - i  (within 16)
+
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __builtin_bit_cast(float, dpp_i32<CTRL>(__builtin_bit_cast(int, v)));
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+    const long long b = __builtin_bit_cast(long long, v);
+    const unsigned lo = (unsigned)dpp_i32<CTRL>((int)(unsigned)b), hi = (unsigned)dpp_i32<CTRL>((int)(unsigned)(b >> 32));
+    return __builtin_bit_cast(double, (long long)(((unsigned long long)hi << 32) | lo));
+}
+__device__ __forceinline__ float lane_f32(float v, int lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+__device__ __forceinline__ double lane_f64(double v, int lane) {
+    const long long b = __builtin_bit_cast(long long, v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, lane);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(b >> 32), lane);
+    return __builtin_bit_cast(double, (long long)(((unsigned long long)hi << 32) | lo));
+}
+
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
+    v = fmaxf(v, dpp_f32<kDppXor1>(v));
+    v = fmaxf(v, dpp_f32<kDppXor2>(v));
+    v = fmaxf(v, dpp_f32<kDppHalfMirror>(v));
+    v = fmaxf(v, dpp_f32<kDppMirror>(v));
+    return fmaxf(fmaxf(lane_f32(v, 0), lane_f32(v, 16)), fmaxf(lane_f32(v, 32), lane_f32(v, 48)));
 }
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
+    v += dpp_f32<kDppXor1>(v);
+    v += dpp_f32<kDppXor2>(v);
+    v += dpp_f32<kDppHalfMirror>(v);
+    v += dpp_f32<kDppMirror>(v);
+    return (lane_f32(v, 0) + lane_f32(v, 16)) + (lane_f32(v, 32) + lane_f32(v, 48));
 }
 __device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
+    v += dpp_f64<kDppXor1>(v);
+    v += dpp_f64<kDppXor2>(v);
+    v += dpp_f64<kDppHalfMirror>(v);
+    v += dpp_f64<kDppMirror>(v);
+    return (lane_f64(v, 0) + lane_f64(v, 16)) + (lane_f64(v, 32) + lane_f64(v, 48));
 }
 
 // Workgroup reductions over kBlock threads through a 4-entry LDS array.  Two barriers each, so the
@@ -140,13 +178,21 @@ __device__ __forceinline__ Top2 top2_merge(const Top2& a, const Top2& b) {
 __device__ __forceinline__ Top2 top2_push(const Top2& a, float x, int idx) {
     return top2_merge(a, Top2{x, idx, -INFINITY});
 }
+template <int CTRL>
+__device__ __forceinline__ Top2 top2_dpp_step(const Top2& t) {
+    return top2_merge(t, Top2{dpp_f32<CTRL>(t.v1), dpp_i32<CTRL>(t.i1), dpp_f32<CTRL>(t.v2)});
+}
+__device__ __forceinline__ Top2 top2_at(const Top2& t, int lane) {
+    return Top2{lane_f32(t.v1, lane), __builtin_amdgcn_readlane(t.i1, lane), lane_f32(t.v2, lane)};
+}
+// NB: merging a candidate with a copy of itself must not happen (it would count the maximum as its own
+// runner-up); the DPP steps below always pair disjoint lane groups.
 __device__ __forceinline__ Top2 wave_top2(Top2 t) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        Top2 other{__shfl_xor(t.v1, o), __shfl_xor(t.i1, o), __shfl_xor(t.v2, o)};
-        t = top2_merge(t, other);
-    }
-    return t;
+    t = top2_dpp_step<kDppXor1>(t);
+    t = top2_dpp_step<kDppXor2>(t);
+    t = top2_dpp_step<kDppHalfMirror>(t);
+    t = top2_dpp_step<kDppMirror>(t);
+    return top2_merge(top2_merge(top2_at(t, 0), top2_at(t, 16)), top2_merge(top2_at(t, 32), top2_at(t, 48)));
 }
 
 // Plain (value, lowest index) arg-max.
@@ -157,13 +203,19 @@ struct ArgMax {
 __device__ __forceinline__ ArgMax argmax_merge(const ArgMax& a, const ArgMax& b) {
     return ((b.v > a.v) || (b.v == a.v && b.i < a.i)) ? b : a;
 }
+template <int CTRL>
+__device__ __forceinline__ ArgMax argmax_dpp_step(const ArgMax& t) {
+    return argmax_merge(t, ArgMax{dpp_f32<CTRL>(t.v), dpp_i32<CTRL>(t.i)});
+}
+__device__ __forceinline__ ArgMax argmax_at(const ArgMax& t, int lane) {
+    return ArgMax{lane_f32(t.v, lane), __builtin_amdgcn_readlane(t.i, lane)};
+}
 __device__ __forceinline__ ArgMax wave_argmax(ArgMax t) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        ArgMax other{__shfl_xor(t.v, o), __shfl_xor(t.i, o)};
-        t = argmax_merge(t, other);
-    }
-    return t;
+    t = argmax_dpp_step<kDppXor1>(t);
+    t = argmax_dpp_step<kDppXor2>(t);
+    t = argmax_dpp_step<kDppHalfMirror>(t);
+    t = argmax_dpp_step<kDppMirror>(t);
+    return argmax_merge(argmax_merge(argmax_at(t, 0), argmax_at(t, 16)), argmax_merge(argmax_at(t, 32), argmax_at(t, 48)));
 }
 
 // ---------------------------------------------------------------- Philox4x32-10 (Salmon et al., SC'11)
