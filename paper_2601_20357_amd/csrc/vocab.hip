@@ -149,11 +149,13 @@ struct SampleArgs {
 };
 
 // TI = tiles per thread, a compile-time bound with NT <= kBlock * TI, so that every phase issues all of its
-// loads before the first use and keeps its tile values in registers.
-template <bool VEC, int TI>
+// loads before the first use and keeps its tile values in registers.  N = number of drafts when it is known
+// at compile time (0 = run time): then the partials are read ONCE, each thread keeping the n*TI terms
+// ps*exp(pm - m_j) of its own run of tiles in registers for both the log-sum-exp and the tile masses.
+template <bool VEC, int TI, int N>
 __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
     const int b = blockIdx.y, c = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n = a.n, NT = a.NT, V = a.V;
+    const int n = (N > 0) ? N : a.n, NT = a.NT, V = a.V;
     // Workgroup 0 of a sequence always has work, so its temperature load overlaps the loads below; the
     // other workgroups only exist for greedy rows and leave at once otherwise.
     const float T = a.temperature[b];
@@ -168,6 +170,8 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
     __shared__ double s_prefix;
     __shared__ Top2 s_top[kWavesPerBlock];
     __shared__ double s_term[TABED_MAX_N][kTileV];
+    __shared__ float s_wm[kWavesPerBlock][TABED_MAX_N];
+    __shared__ double s_wsum[kWavesPerBlock][TABED_MAX_N];
 
     const float* pmb = a.pm + (size_t)b * n * NT;      // partials of this sequence: [n][NT]
     const float* psb = a.ps + (size_t)b * n * NT;
@@ -175,28 +179,72 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
     const float wj = (tid < n) ? a.weights[(size_t)b * n + tid] : 0.f;
     const float u = a.u_draft ? a.u_draft[out_idx] : tabed_uniform(a.seed, a.round, (uint32_t)b, (uint32_t)a.pos, 0);
 
-    // ---- per-draft log-sum-exp: one wave per draft row, lanes strided over the row's tiles
-    constexpr int TL = TI * kWavesPerBlock;            // tiles per lane when one wave covers a whole row
-    for (int j = wave; j < n; j += kWavesPerBlock) {
-        float pmv[TL], psv[TL];
+    float uu[(N > 0) ? N : 1][TI];                     // single pass: terms of this thread's tiles, all drafts
+    if (N > 0) {
+        // ---- single pass over the partials: thread tid owns tiles [tid*TI, tid*TI + TI) of every draft
+        float pmv[(N > 0) ? N : 1][TI], psv[(N > 0) ? N : 1][TI];
 #pragma unroll
-        for (int i = 0; i < TL; ++i) {
-            const int t = lane + i * kWave;
-            pmv[i] = t < NT ? pmb[(size_t)j * NT + t] : -INFINITY;
-            psv[i] = t < NT ? psb[(size_t)j * NT + t] : 0.f;
+        for (int j = 0; j < N; ++j)
+#pragma unroll
+            for (int i = 0; i < TI; ++i) {
+                const int t = tid * TI + i;
+                pmv[j][i] = t < NT ? pmb[(size_t)j * NT + t] : -INFINITY;
+                psv[j][i] = t < NT ? psb[(size_t)j * NT + t] : 0.f;
+            }
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            float ml = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < TI; ++i) ml = fmaxf(ml, pmv[j][i]);
+            ml = wave_max(ml);
+            if (lane == 0) s_wm[wave][j] = ml;
         }
-        float ml = -INFINITY;
+        __syncthreads();
 #pragma unroll
-        for (int i = 0; i < TL; ++i) ml = fmaxf(ml, pmv[i]);
-        const float M = wave_max(ml);
-        float sl = 0.f;
+        for (int j = 0; j < N; ++j) {
+            const float M = fmaxf(fmaxf(s_wm[0][j], s_wm[1][j]), fmaxf(s_wm[2][j], s_wm[3][j]));
+            float sl = 0.f;
 #pragma unroll
-        for (int i = 0; i < TL; ++i) sl += (psv[i] > 0.f) ? psv[i] * __expf(pmv[i] - M) : 0.f;
-        const double S = wave_sum((double)sl);
-        if (lane == 0) {
+            for (int i = 0; i < TI; ++i) {
+                uu[j][i] = (psv[j][i] > 0.f) ? psv[j][i] * __expf(pmv[j][i] - M) : 0.f;
+                sl += uu[j][i];
+            }
+            const double S = wave_sum((double)sl);
+            if (lane == 0) s_wsum[wave][j] = S;
+        }
+        __syncthreads();
+        if (tid < N) {
+            const int j = tid;
+            const float M = fmaxf(fmaxf(s_wm[0][j], s_wm[1][j]), fmaxf(s_wm[2][j], s_wm[3][j]));
+            const double S = (s_wsum[0][j] + s_wsum[1][j]) + (s_wsum[2][j] + s_wsum[3][j]);
             s_m[j] = M;
             s_S[j] = S;
             if (c == 0) a.draft_lse[((size_t)a.pos * a.B + b) * n + j] = (double)M + log(S);
+        }
+    } else {
+        // ---- per-draft log-sum-exp: one wave per draft row, lanes strided over the row's tiles
+        constexpr int TL = TI * kWavesPerBlock;        // tiles per lane when one wave covers a whole row
+        for (int j = wave; j < n; j += kWavesPerBlock) {
+            float pmv[TL], psv[TL];
+#pragma unroll
+            for (int i = 0; i < TL; ++i) {
+                const int t = lane + i * kWave;
+                pmv[i] = t < NT ? pmb[(size_t)j * NT + t] : -INFINITY;
+                psv[i] = t < NT ? psb[(size_t)j * NT + t] : 0.f;
+            }
+            float ml = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < TL; ++i) ml = fmaxf(ml, pmv[i]);
+            const float M = wave_max(ml);
+            float sl = 0.f;
+#pragma unroll
+            for (int i = 0; i < TL; ++i) sl += (psv[i] > 0.f) ? psv[i] * __expf(pmv[i] - M) : 0.f;
+            const double S = wave_sum((double)sl);
+            if (lane == 0) {
+                s_m[j] = M;
+                s_S[j] = S;
+                if (c == 0) a.draft_lse[((size_t)a.pos * a.B + b) * n + j] = (double)M + log(S);
+            }
         }
     }
     const bool greedy = !(T > 0.f);
@@ -216,21 +264,31 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
 #pragma unroll
         for (int i = 0; i < TI; ++i) mt[i] = 0.0;
         double Z = 0.0;
-#pragma unroll 4
-        for (int j = 0; j < n; ++j) {
-            float pmv[TI], psv[TI];
+        if (N > 0) {
 #pragma unroll
-            for (int i = 0; i < TI; ++i) {
-                const int t = tid * TI + i;
-                pmv[i] = t < NT ? pmb[(size_t)j * NT + t] : -INFINITY;
-                psv[i] = t < NT ? psb[(size_t)j * NT + t] : 0.f;
+            for (int j = 0; j < N; ++j) {
+                const double cj = s_c[j];
+                Z += cj * s_S[j];
+#pragma unroll
+                for (int i = 0; i < TI; ++i) mt[i] += cj * (double)uu[j][i];
             }
-            const double cj = s_c[j];
-            const float mj = s_m[j];
-            Z += cj * s_S[j];
+        } else {
+#pragma unroll 4
+            for (int j = 0; j < n; ++j) {
+                float pmv[TI], psv[TI];
 #pragma unroll
-            for (int i = 0; i < TI; ++i)
-                if (psv[i] > 0.f) mt[i] += cj * (double)(psv[i] * __expf(pmv[i] - mj));
+                for (int i = 0; i < TI; ++i) {
+                    const int t = tid * TI + i;
+                    pmv[i] = t < NT ? pmb[(size_t)j * NT + t] : -INFINITY;
+                    psv[i] = t < NT ? psb[(size_t)j * NT + t] : 0.f;
+                }
+                const double cj = s_c[j];
+                const float mj = s_m[j];
+                Z += cj * s_S[j];
+#pragma unroll
+                for (int i = 0; i < TI; ++i)
+                    if (psv[i] > 0.f) mt[i] += cj * (double)(psv[i] * __expf(pmv[i] - mj));
+            }
         }
         double run = 0.0;
 #pragma unroll
@@ -365,10 +423,16 @@ hipError_t launch_sample(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
     const dim3 grid(L.C2, c.B);
     const bool vec = (c.V % 4 == 0);
     const int ti = (L.NT + kBlock - 1) / kBlock;
+    // single-pass instantiations where n*TI terms fit comfortably in registers
+    const int nc = (vec && ti <= 4 && (c.n == 1 || c.n == 2 || c.n == 4 || c.n == 8)) ? c.n : 0;
 #define TABED_LAUNCH_SAMPLE(TI_)                                                                  \
     do {                                                                                          \
-        if (vec) hipLaunchKernelGGL((k_sample<true, TI_>), grid, dim3(kBlock), 0, s, a);          \
-        else     hipLaunchKernelGGL((k_sample<false, TI_>), grid, dim3(kBlock), 0, s, a);         \
+        if (!vec) hipLaunchKernelGGL((k_sample<false, TI_, 0>), grid, dim3(kBlock), 0, s, a);      \
+        else if (TI_ <= 4 && nc == 1) hipLaunchKernelGGL((k_sample<true, (TI_ <= 4 ? TI_ : 1), 1>), grid, dim3(kBlock), 0, s, a); \
+        else if (TI_ <= 4 && nc == 2) hipLaunchKernelGGL((k_sample<true, (TI_ <= 4 ? TI_ : 1), 2>), grid, dim3(kBlock), 0, s, a); \
+        else if (TI_ <= 4 && nc == 4) hipLaunchKernelGGL((k_sample<true, (TI_ <= 4 ? TI_ : 1), 4>), grid, dim3(kBlock), 0, s, a); \
+        else if (TI_ <= 4 && nc == 8) hipLaunchKernelGGL((k_sample<true, (TI_ <= 4 ? TI_ : 1), 8>), grid, dim3(kBlock), 0, s, a); \
+        else hipLaunchKernelGGL((k_sample<true, TI_, 0>), grid, dim3(kBlock), 0, s, a);           \
     } while (0)
     if (ti <= 1) TABED_LAUNCH_SAMPLE(1);
     else if (ti <= 4) TABED_LAUNCH_SAMPLE(4);
