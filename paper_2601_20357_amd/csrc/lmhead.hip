@@ -256,22 +256,23 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
 #pragma unroll
         for (int i = 0; i < 4; ++i) wreg[kb][i] = *reinterpret_cast<const u32x4*>(W + off[i] + kb * 64);
     };
-    // H lands in LDS and the workgroup meets BEFORE the first W request goes out.  Measured on MI355X: a
-    // compute unit accepts only a bounded number of outstanding requests, so issuing a whole half-tile takes
-    // about as long as streaming it, and with W queued behind it H came back ~5 us late.  So: H alone first
-    // (~1.7 us), then W k-block by k-block, kPF k-blocks ahead of the one being multiplied.
-#pragma unroll
-    for (int q = 0; q < MT * KH; ++q) {
-        const int p = tid + q * kSkinnyThreads, row = p / CH, c = p % CH;
-        *reinterpret_cast<u32x4*>(ldsH + row * HROW + c * 16) = hreg[q];
-    }
-    lds_barrier();                                 // also publishes s_invt
+    // Only the first kPF k-blocks of W are requested before H has landed.  Measured on MI355X: a compute unit
+    // accepts a bounded number of outstanding requests, so issuing a whole half-tile takes about as long as
+    // streaming it, and with all of W queued behind them the H loads came back ~5 us late (nothing can start
+    // without H).  With kPF k-blocks queued H lands at ~1.7 us and the first W data follows at once; the rest
+    // of W is requested k-block by k-block, kPF ahead of the one being multiplied.
     constexpr int kPF = (KH < 3) ? KH : 3;
     size_t src[4];                                 // the tile whose k-blocks are being requested
     aim_tile(src, blockIdx.x * 4 + pair);
 #pragma unroll
     for (int kb = 0; kb < kPF; ++kb) request_kblock(src, kb);
     __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int q = 0; q < MT * KH; ++q) {
+        const int p = tid + q * kSkinnyThreads, row = p / CH, c = p % CH;
+        *reinterpret_cast<u32x4*>(ldsH + row * HROW + c * 16) = hreg[q];
+    }
+    lds_barrier();                                 // also publishes s_invt
 
     for (int g = blockIdx.x;; g += gridDim.x) {    // tile group g = 4 tiles, one per wave pair; trip count is
         const int this_tile = g * 4 + pair;        // uniform over the workgroup (barriers inside)
