@@ -169,11 +169,11 @@ int tabed_update_weights(const tabed_cfg* cfg, void* ws, const float* dev, const
 int tabed_philox_uniforms(const tabed_cfg* cfg, uint64_t round, float* out, void* stream);
 
 /*
- * Per-kernel timing with HIP events on the launch stream.  While enabled every
- * kernel launch is bracketed by two events; tabed_prof_read() waits for them
- * and returns accumulated milliseconds and launch count of kernel `id`
- * (TABED_K_*), then keeps the totals until tabed_prof_reset().  Off by default;
- * these three calls create and destroy events and synchronise, unlike the rest.
+ * Per-kernel timing.  While enabled, every kernel is launched with a start and a stop HIP event attached to
+ * its dispatch (hipExtLaunchKernelGGL), so the pair brackets the kernel's own execution on the launch
+ * stream; tabed_prof_read() waits for them and returns accumulated milliseconds and launch count of kernel
+ * `id` (TABED_K_*), and keeps the totals until tabed_prof_reset().  Off by default; these calls create and
+ * destroy events and synchronise, unlike the rest of the library.
  */
 #define TABED_K_LMHEAD 0  /* LM-head GEMM + softmax partials    */
 #define TABED_K_SAMPLE 1  /* ensemble + draft token             */
@@ -186,9 +186,8 @@ int tabed_prof_enable(int on);
 int tabed_prof_read(int id, double* total_ms, int64_t* launches);
 int tabed_prof_reset(void);
 const char* tabed_kernel_name(int id);
-/* Launches an empty kernel on `stream`, bracketed like the others when timing is enabled: what
- * tabed_prof_read(TABED_K_NULL, ...) then reports is the cost of the event pair plus one dispatch,
- * i.e. how much the per-kernel figures above exceed the kernels' own run time. */
+/* Launches an empty kernel on `stream`, timed like the others when timing is enabled: what
+ * tabed_prof_read(TABED_K_NULL, ...) then reports is the floor of the method. */
 int tabed_prof_null(void* stream);
 
 #ifdef __cplusplus

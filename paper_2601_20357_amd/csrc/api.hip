@@ -59,19 +59,9 @@ static double g_prof_ms[TABED_K_COUNT];
 static int64_t g_prof_n[TABED_K_COUNT];
 
 bool prof_on() { return g_prof_on; }
-void prof_begin(int id, hipStream_t s) {
+void prof_push(int id, hipEvent_t start, hipEvent_t stop) {
     std::lock_guard<std::mutex> lk(g_prof_mu);
-    ProfRec r;
-    r.id = id;
-    if (hipEventCreate(&r.start) != hipSuccess) return;
-    if (hipEventCreate(&r.stop) != hipSuccess) { (void)hipEventDestroy(r.start); return; }
-    (void)hipEventRecord(r.start, s);
-    g_prof_pending.push_back(r);
-}
-void prof_end(int id, hipStream_t s) {
-    std::lock_guard<std::mutex> lk(g_prof_mu);
-    for (size_t i = g_prof_pending.size(); i-- > 0;)
-        if (g_prof_pending[i].id == id) { (void)hipEventRecord(g_prof_pending[i].stop, s); return; }
+    g_prof_pending.push_back(ProfRec{id, start, stop});
 }
 static void prof_drain() {
     for (ProfRec& r : g_prof_pending) {

@@ -64,15 +64,34 @@ hipError_t launch_null(hipStream_t s);
 hipError_t launch_philox(const tabed_cfg& c, uint64_t round, float* out, hipStream_t s);
 
 // ---------------------------------------------------------------- event timing
+// While timing is enabled a launch goes through hipExtLaunchKernelGGL, which attaches a start and a stop
+// event to the dispatch itself: the pair measures the kernel's own begin-to-end time (what a kernel trace
+// reports), not the dispatch gaps around it.
 bool prof_on();
-void prof_begin(int id, hipStream_t s);
-void prof_end(int id, hipStream_t s);
+void prof_push(int id, hipEvent_t start, hipEvent_t stop);
 struct ProfScope {
     int id;
-    hipStream_t s;
     bool on;
-    ProfScope(int id_, hipStream_t s_) : id(id_), s(s_), on(prof_on()) { if (on) prof_begin(id, s); }
-    ~ProfScope() { if (on) prof_end(id, s); }
+    hipEvent_t start = nullptr, stop = nullptr;
+    ProfScope(int id_, hipStream_t) : id(id_), on(prof_on()) {
+        if (on && (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess)) on = false;
+    }
+    ~ProfScope() { if (on) prof_push(id, start, stop); }
+    ProfScope(const ProfScope&) = delete;
+    ProfScope& operator=(const ProfScope&) = delete;
 };
 
 }  // namespace tabed
+
+#if defined(__HIPCC__)
+#include <hip/hip_ext.h>
+namespace tabed {
+template <typename K, typename... Args>
+inline void launch(const ProfScope* prof, K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t s, Args... args) {
+    if (prof != nullptr && prof->on)
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, s, prof->start, prof->stop, 0, args...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, lds, s, args...);
+}
+}  // namespace tabed
+#endif

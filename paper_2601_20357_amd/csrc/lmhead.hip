@@ -375,7 +375,7 @@ static bool skinny_applies(const tabed_cfg& c, int M) {
 }
 
 template <int KH, int MT>
-static void launch_skinny_t(const tabed_cfg& c, const WsLayout& Lay, int M, const void* W, const void* H,
+static void launch_skinny_t(const ProfScope* prof, const tabed_cfg& c, const WsLayout& Lay, int M, const void* W, const void* H,
                             const float* temperature, float* logits, float* pm, float* ps, hipStream_t s) {
     const size_t lds = (size_t)MT * 32 * (KH * 256 + 16) + (size_t)kSkinnyWaves * kPatchBytes;
     static bool attr_set = false;                      // raise the dynamic-LDS limit of this instantiation once
@@ -388,17 +388,17 @@ static void launch_skinny_t(const tabed_cfg& c, const WsLayout& Lay, int M, cons
     int cus = 256;
     const int groups = (num_tiles + 3) / 4;
     const dim3 grid(groups < cus ? groups : cus);
-    hipLaunchKernelGGL((k_lmhead_skinny<KH, MT>), grid, dim3(kSkinnyThreads), lds, s, M, c.V, c.n, Lay.NT, num_tiles,
+    launch(prof, k_lmhead_skinny<KH, MT>, grid, dim3(kSkinnyThreads), lds, s, M, c.V, c.n, Lay.NT, num_tiles,
                        static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), temperature, logits, pm, ps);
 }
 
-static void launch_skinny(const tabed_cfg& c, const WsLayout& Lay, int M, const void* W, const void* H,
+static void launch_skinny(const ProfScope* prof, const tabed_cfg& c, const WsLayout& Lay, int M, const void* W, const void* H,
                           const float* temperature, float* logits, float* pm, float* ps, hipStream_t s) {
     const int KH = c.d / 128, MT = (M + 31) / 32;
 #define TABED_SKINNY(KH_)                                                                              \
     if (KH == KH_) {                                                                                   \
-        if (MT == 1) launch_skinny_t<KH_, 1>(c, Lay, M, W, H, temperature, logits, pm, ps, s);         \
-        else         launch_skinny_t<KH_, 2>(c, Lay, M, W, H, temperature, logits, pm, ps, s);         \
+        if (MT == 1) launch_skinny_t<KH_, 1>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);         \
+        else         launch_skinny_t<KH_, 2>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);         \
     }
     TABED_SKINNY(4) TABED_SKINNY(6) TABED_SKINNY(7) TABED_SKINNY(8)
 #undef TABED_SKINNY
@@ -412,13 +412,13 @@ hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& Lay, char* ws, cons
     const int M = Lay.M;
     if (c.w_dtype == 0) {
         const dim3 grid(Lay.NT, (M + 7) / 8);
-        hipLaunchKernelGGL(k_lmhead_f32, grid, dim3(kBlock), 0, s, M, c.d, c.V, c.n, Lay.NT,
+        launch(&prof, k_lmhead_f32, grid, dim3(kBlock), 0, s, M, c.d, c.V, c.n, Lay.NT,
                            static_cast<const float*>(W), static_cast<const float*>(H), temperature, logits, pm, ps);
     } else if (skinny_applies(c, M)) {
-        launch_skinny(c, Lay, M, W, H, temperature, logits, pm, ps, s);
+        launch_skinny(&prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);
     } else {
         const dim3 grid((c.V + kBN - 1) / kBN, (M + kBM - 1) / kBM);
-        hipLaunchKernelGGL(k_lmhead_bf16, grid, dim3(kBlock), 0, s, M, c.d, c.V, c.n, Lay.NT,
+        launch(&prof, k_lmhead_bf16, grid, dim3(kBlock), 0, s, M, c.d, c.V, c.n, Lay.NT,
                            static_cast<const __hip_bfloat16*>(W), static_cast<const __hip_bfloat16*>(H),
                            temperature, logits, pm, ps);
     }

@@ -17,7 +17,7 @@ __global__ void k_fill_u32(uint32_t* p, int count) {
 
 hipError_t launch_ws_init(const tabed_cfg& c, const WsLayout& L, char* ws, hipStream_t s) {
     const int count = 3 * c.B;
-    hipLaunchKernelGGL(k_fill_u32, dim3((count + 255) / 256), dim3(256), 0, s,
+    launch(nullptr, k_fill_u32, dim3((count + 255) / 256), dim3(256), 0, s,
                        reinterpret_cast<uint32_t*>(ws + L.off_tickets), count);
     return hipGetLastError();
 }
@@ -26,7 +26,7 @@ __global__ void k_null() {}
 
 hipError_t launch_null(hipStream_t s) {
     ProfScope prof(TABED_K_NULL, s);
-    hipLaunchKernelGGL(k_null, dim3(1), dim3(64), 0, s);
+    launch(&prof, k_null, dim3(1), dim3(64), 0, s);
     return hipGetLastError();
 }
 
@@ -42,7 +42,7 @@ __global__ void k_philox(uint64_t seed, uint64_t round, int B, int npos, float* 
 
 hipError_t launch_philox(const tabed_cfg& c, uint64_t round, float* out, hipStream_t s) {
     const int count = c.B * (c.gamma + 1);
-    hipLaunchKernelGGL(k_philox, dim3((count + 255) / 256), dim3(256), 0, s, c.seed, round, c.B, c.gamma + 1, out);
+    launch(nullptr, k_philox, dim3((count + 255) / 256), dim3(256), 0, s, c.seed, round, c.B, c.gamma + 1, out);
     return hipGetLastError();
 }
 
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(64) void k_weights(int n, int B, int gamma, int h, 
 hipError_t launch_weights(const tabed_cfg& c, const float* dev, const int32_t* n_valid, float* ring,
                           int32_t* ring_head, int32_t* ring_count, float* weights, hipStream_t s) {
     ProfScope prof(TABED_K_WEIGHTS, s);
-    hipLaunchKernelGGL(k_weights, dim3(c.B), dim3(64), 0, s, c.n, c.B, c.gamma, c.h, c.policy,
+    launch(&prof, k_weights, dim3(c.B), dim3(64), 0, s, c.n, c.B, c.gamma, c.h, c.policy,
                        (double)c.tau_w, (double)c.eps, dev, n_valid, ring, ring_head, ring_count, weights);
     return hipGetLastError();
 }
@@ -427,12 +427,12 @@ hipError_t launch_sample(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
     const int nc = (vec && ti <= 4 && (c.n == 1 || c.n == 2 || c.n == 4 || c.n == 8)) ? c.n : 0;
 #define TABED_LAUNCH_SAMPLE(TI_)                                                                  \
     do {                                                                                          \
-        if (!vec) hipLaunchKernelGGL((k_sample<false, TI_, 0>), grid, dim3(kBlock), 0, s, a);      \
-        else if (TI_ <= 4 && nc == 1) hipLaunchKernelGGL((k_sample<true, (TI_ <= 4 ? TI_ : 1), 1>), grid, dim3(kBlock), 0, s, a); \
-        else if (TI_ <= 4 && nc == 2) hipLaunchKernelGGL((k_sample<true, (TI_ <= 4 ? TI_ : 1), 2>), grid, dim3(kBlock), 0, s, a); \
-        else if (TI_ <= 4 && nc == 4) hipLaunchKernelGGL((k_sample<true, (TI_ <= 4 ? TI_ : 1), 4>), grid, dim3(kBlock), 0, s, a); \
-        else if (TI_ <= 4 && nc == 8) hipLaunchKernelGGL((k_sample<true, (TI_ <= 4 ? TI_ : 1), 8>), grid, dim3(kBlock), 0, s, a); \
-        else hipLaunchKernelGGL((k_sample<true, TI_, 0>), grid, dim3(kBlock), 0, s, a);           \
+        if (!vec) launch(&prof, k_sample<false, TI_, 0>, grid, dim3(kBlock), 0, s, a);      \
+        else if (TI_ <= 4 && nc == 1) launch(&prof, k_sample<true, (TI_ <= 4 ? TI_ : 1), 1>, grid, dim3(kBlock), 0, s, a); \
+        else if (TI_ <= 4 && nc == 2) launch(&prof, k_sample<true, (TI_ <= 4 ? TI_ : 1), 2>, grid, dim3(kBlock), 0, s, a); \
+        else if (TI_ <= 4 && nc == 4) launch(&prof, k_sample<true, (TI_ <= 4 ? TI_ : 1), 4>, grid, dim3(kBlock), 0, s, a); \
+        else if (TI_ <= 4 && nc == 8) launch(&prof, k_sample<true, (TI_ <= 4 ? TI_ : 1), 8>, grid, dim3(kBlock), 0, s, a); \
+        else launch(&prof, k_sample<true, TI_, 0>, grid, dim3(kBlock), 0, s, a);           \
     } while (0)
     if (ti <= 1) TABED_LAUNCH_SAMPLE(1);
     else if (ti <= 4) TABED_LAUNCH_SAMPLE(4);
@@ -573,13 +573,13 @@ static int pick_stats_unroll(const tabed_cfg& c, int nmax_u) {
 }
 
 template <bool VEC, int N>
-static void launch_stats_n(int U, dim3 grid, hipStream_t s, const StatsArgs& a) {
+static void launch_stats_n(const ProfScope* prof, int U, dim3 grid, hipStream_t s, const StatsArgs& a) {
     if (U == 4) {
-        if constexpr (N <= 4) hipLaunchKernelGGL((k_stats<VEC, 4, N>), grid, dim3(kBlock), 0, s, a);
+        if constexpr (N <= 4) launch(prof, k_stats<VEC, 4, N>, grid, dim3(kBlock), 0, s, a);
     } else if (U == 2) {
-        hipLaunchKernelGGL((k_stats<VEC, 2, N>), grid, dim3(kBlock), 0, s, a);
+        launch(prof, k_stats<VEC, 2, N>, grid, dim3(kBlock), 0, s, a);
     } else {
-        hipLaunchKernelGGL((k_stats<VEC, 1, N>), grid, dim3(kBlock), 0, s, a);
+        launch(prof, k_stats<VEC, 1, N>, grid, dim3(kBlock), 0, s, a);
     }
 }
 
@@ -951,11 +951,11 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
         a.target = target_logits; a.dlogits = draft_logits; a.temperature = temperature;
         a.stats = reinterpret_cast<double*>(ws + L.off_stats);
         const dim3 grid(C3, c.gamma + 1, c.B);
-        if (!vec) launch_stats_n<false, 0>(U, grid, s, a);
-        else if (ncomp == 2) launch_stats_n<true, 2>(U, grid, s, a);
-        else if (ncomp == 4) launch_stats_n<true, 4>(U, grid, s, a);
-        else if (ncomp == 8) launch_stats_n<true, 8>(U, grid, s, a);
-        else launch_stats_n<true, 0>(U, grid, s, a);
+        if (!vec) launch_stats_n<false, 0>(&prof, U, grid, s, a);
+        else if (ncomp == 2) launch_stats_n<true, 2>(&prof, U, grid, s, a);
+        else if (ncomp == 4) launch_stats_n<true, 4>(&prof, U, grid, s, a);
+        else if (ncomp == 8) launch_stats_n<true, 8>(&prof, U, grid, s, a);
+        else launch_stats_n<true, 0>(&prof, U, grid, s, a);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -971,11 +971,11 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
     a.accept_len = accept_len; a.out_tokens = out_tokens; a.dev = dev; a.n_valid = n_valid; a.flags = flags;
     const dim3 grid(L.C5, c.B);
     const size_t lds = sizeof(double) * (size_t)(c.gamma + 1) * C3;
-    if (!vec) hipLaunchKernelGGL((k_finish<false, 0>), grid, dim3(kBlock), lds, s, a);
-    else if (ncomp == 2) hipLaunchKernelGGL((k_finish<true, 2>), grid, dim3(kBlock), lds, s, a);
-    else if (ncomp == 4) hipLaunchKernelGGL((k_finish<true, 4>), grid, dim3(kBlock), lds, s, a);
-    else if (ncomp == 8) hipLaunchKernelGGL((k_finish<true, 8>), grid, dim3(kBlock), lds, s, a);
-    else hipLaunchKernelGGL((k_finish<true, 0>), grid, dim3(kBlock), lds, s, a);
+    if (!vec) launch(&prof, k_finish<false, 0>, grid, dim3(kBlock), lds, s, a);
+    else if (ncomp == 2) launch(&prof, k_finish<true, 2>, grid, dim3(kBlock), lds, s, a);
+    else if (ncomp == 4) launch(&prof, k_finish<true, 4>, grid, dim3(kBlock), lds, s, a);
+    else if (ncomp == 8) launch(&prof, k_finish<true, 8>, grid, dim3(kBlock), lds, s, a);
+    else launch(&prof, k_finish<true, 0>, grid, dim3(kBlock), lds, s, a);
     return hipGetLastError();
 }
 
