@@ -163,9 +163,18 @@ def draft_step(*, V, d, n, B, gamma, w_dtype, seed, rnd, pos, W, H, weights, tem
                             _p(draft_logits), _p(draft_lse), _p(draft_tokens), _p(draft_q), _p(flags))
 
 
+GRID_CANDIDATES = 11
+
+
+def dev_width(n, policy):
+    """Width of one distance vector: n per-draft distances, or the 11 candidate mixtures of the two-draft grid policy."""
+    return GRID_CANDIDATES if policy == 2 else n
+
+
 def verify(*, V, n, B, gamma, distance, seed, rnd, target_logits, draft_logits, draft_tokens,
-           draft_q, weights, temperature, u_acc=None, u_res=None):
+           draft_q, weights, temperature, u_acc=None, u_res=None, n_cand=0):
     """Sec. 3 items 2-3 plus per-position distances; returns a dict of fresh output arrays."""
+    assert n_cand in (0, GRID_CANDIDATES) and (n_cand == 0 or n == 2)
     target_logits = _f32(target_logits)
     draft_logits = _f32(draft_logits)
     assert target_logits.shape == (B, gamma + 1, V) and draft_logits.shape == (gamma, B, n, V)
@@ -178,11 +187,11 @@ def verify(*, V, n, B, gamma, distance, seed, rnd, target_logits, draft_logits, 
     out = dict(
         accept_len=np.zeros(B, dtype=np.int32),
         out_tokens=np.full((B, gamma + 1), -1, dtype=np.int32),
-        dev=np.zeros((B, gamma, n), dtype=np.float32),
+        dev=np.zeros((B, gamma, n_cand if n_cand else n), dtype=np.float32),
         n_valid=np.zeros(B, dtype=np.int32),
         flags=np.zeros((B, gamma + 1), dtype=np.uint8),
     )
-    lib().oracle_verify(V, n, B, gamma, distance, C.c_uint64(seed), C.c_uint64(rnd),
+    lib().oracle_verify(V, n, B, gamma, distance, n_cand, C.c_uint64(seed), C.c_uint64(rnd),
                         _p(target_logits), _p(draft_logits), _p(draft_tokens), _p(draft_q),
                         _p(weights), _p(temperature), _p(ua), _p(ur),
                         _p(out["accept_len"]), _p(out["out_tokens"]), _p(out["dev"]),
@@ -192,7 +201,8 @@ def verify(*, V, n, B, gamma, distance, seed, rnd, target_logits, draft_logits, 
 
 def update_weights(*, n, B, gamma, h, policy, tau_w, eps, dev, n_valid, ring, ring_head, ring_count):
     """Alg. 1 lines 2-3 (App. B.2 policy); ring state is updated in place; returns weights [B,n]."""
-    assert ring.dtype == np.float32 and ring.shape == (B, h, n)
+    assert ring.dtype == np.float32 and ring.shape == (B, h, dev_width(n, policy))
+    assert policy != 2 or n == 2
     assert ring_head.dtype == np.int32 and ring_count.dtype == np.int32
     d_ = None if dev is None else _f32(dev)
     nv = None if n_valid is None else np.ascontiguousarray(n_valid, dtype=np.int32)

@@ -17,7 +17,10 @@
  *     the accumulated distance e_t^j = sum_{t'} D_KL(p_t' || q_t'^j) over the
  *     last h verified positions and held for the whole block.
  *   - App. B.2: the many-draft policy w = softmax([1/e^(1)..1/e^(m)]; tau),
- *     tau = 1; Sec. 4.1 last paragraph: TVD as the alternative distance.
+ *     tau = 1, and the two-draft policy that scores the fixed candidates
+ *     w^c = [1 - c/10, c/10] by the accumulated distance of the MIXTURE
+ *     q(.; w^c) from the target and takes the arg-min (Alg. 1 line 3);
+ *     Sec. 4.1 last paragraph: TVD as the alternative distance.
  *   - Eq. 1: speedup = block_eff / (gamma * Tq/Tp + 1).
  *
  * Notation: n = number of drafting methods (the paper's m), B independent
@@ -277,8 +280,10 @@ void oracle_draft_step(int V, int d, int n, int B, int gamma, int w_dtype,
 /* target_logits [B,gamma+1,V]; u_acc [B,gamma] / u_res [B] or NULL (=> Philox).
  * Outputs: accept_len [B] = k; out_tokens [B,gamma+1] = the k accepted draft
  * tokens, then one corrected (k < gamma) or bonus (k = gamma) token, then -1;
- * dev [B,gamma,n] = D(p_i, q_i^(j)) for every i < gamma (meaningful for
- * i < n_valid); n_valid [B] = min(k+1, gamma); flags [B,gamma+1].
+ * dev [B,gamma,DW] for every i < gamma (meaningful for i < n_valid), where
+ * with n_cand = 0: DW = n and dev[.,i,j] = D(p_i, q_i^(j)); with n_cand = 11
+ * (n = 2): DW = 11 and dev[.,i,c] = D(p_i, (1 - c/10) q_i^(1) + (c/10) q_i^(2));
+ * n_valid [B] = min(k+1, gamma); flags [B,gamma+1].
  * reading: the accept test is u * q(y) < p(y), evaluated in fp32 on the fp32
  * interface values; greedy rows accept iff y equals the arg-max of the target
  * logits, and emit that arg-max as corrected / bonus token.
@@ -287,7 +292,12 @@ void oracle_draft_step(int V, int d, int n, int B, int gamma, int w_dtype,
  * reading: only positions 0..min(k, gamma-1) have both a verified target
  * distribution and draft distributions conditioned on kept tokens, hence
  * n_valid. */
-void oracle_verify(int V, int n, int B, int gamma, int distance,
+#define ORACLE_GRID_CANDIDATES 11 /* c = 0..10, reading: both pure drafts are candidates */
+
+/* Width of one distance vector: n per-draft distances, or 11 candidate mixtures (n_cand = 11, n = 2). */
+int oracle_dev_width(int n, int n_cand) { return n_cand > 0 ? n_cand : n; }
+
+void oracle_verify(int V, int n, int B, int gamma, int distance, int n_cand,
                    uint64_t seed, uint64_t round,
                    const float* target_logits, const float* draft_logits,
                    const int32_t* draft_tokens, const float* draft_q,
@@ -307,18 +317,30 @@ void oracle_verify(int V, int n, int B, int gamma, int distance,
         double* q = (double*)malloc((size_t)n * V * sizeof(double));
         double* logq = (double*)malloc((size_t)n * V * sizeof(double));
         double* f = (double*)malloc((size_t)V * sizeof(double));
+        double* mixlog = (double*)malloc((size_t)V * sizeof(double));
         uint8_t* fl = flags + (size_t)b * (gamma + 1);
         for (int i = 0; i <= gamma; ++i) fl[i] = 0;
 
         int k = 0, rejected = 0;
         for (int i = 0; i < gamma; ++i) {
             oracle_softmax(Lt + (size_t)i * V, V, T_eff, p, logp);
+            const int DW = oracle_dev_width(n, n_cand);
             for (int j = 0; j < n; ++j) {
                 const float* Lq = draft_logits + (((size_t)i * B + b) * n + j) * V;
                 oracle_softmax(Lq, V, T_eff, q + (size_t)j * V, logq + (size_t)j * V);
+                if (n_cand > 0) continue;
                 double D = distance == 0 ? oracle_kl(p, logp, logq + (size_t)j * V, V)
                                          : oracle_tvd(p, q + (size_t)j * V, V);
-                dev[((size_t)b * gamma + i) * n + j] = (float)D;
+                dev[((size_t)b * gamma + i) * DW + j] = (float)D;
+            }
+            for (int c = 0; c < n_cand; ++c) { /* candidate mixtures of the two drafts */
+                const double w1 = (double)c / (double)(n_cand - 1), w0 = 1.0 - w1;
+                for (int v = 0; v < V; ++v) {
+                    f[v] = w0 * q[v] + w1 * q[(size_t)V + v];
+                    mixlog[v] = log(f[v]);
+                }
+                double D = distance == 0 ? oracle_kl(p, logp, mixlog, V) : oracle_tvd(p, f, V);
+                dev[((size_t)b * gamma + i) * DW + c] = (float)D;
             }
             if (rejected || k < i) continue; /* later positions: distances only */
             int y = draft_tokens[(size_t)b * gamma + i];
@@ -375,7 +397,7 @@ void oracle_verify(int V, int n, int B, int gamma, int distance,
         for (int i = k + 1; i <= gamma; ++i) out_tokens[(size_t)b * (gamma + 1) + i] = -1;
         accept_len[b] = k;
         n_valid[b] = k + 1 < gamma ? k + 1 : gamma;
-        free(p); free(logp); free(q); free(logq); free(f);
+        free(p); free(logp); free(q); free(logq); free(f); free(mixlog);
     }
 }
 
@@ -386,7 +408,11 @@ void oracle_verify(int V, int n, int B, int gamma, int distance,
  * sequence; ring_head [B] is the next slot to overwrite, ring_count [B] the
  * number of live slots.  dev / n_valid may be NULL (nothing to push).
  * policy 0: w = softmax((1 / max(e_j, eps)) / tau_w), e_j = sum over the
- * window; policy 1: equal weights.
+ * window; policy 1: equal weights; policy 2 (n = 2, window entries are the 11
+ * candidate distances): w = [1 - c/10, c/10] for the candidate c with the
+ * smallest window sum (reading: lowest c on ties; equal weights while the
+ * window is empty).  The window holds vectors of width DW = n (policies 0, 1)
+ * or 11 (policy 2).
  * reading: an empty window gives equal weights; a window with fewer than h
  * entries sums what exists; 1/e is clamped by eps; softmax(x; tau) divides
  * by tau. */
@@ -396,12 +422,13 @@ void oracle_update_weights(int n, int B, int gamma, int h, int policy,
                            float* ring, int32_t* ring_head, int32_t* ring_count,
                            float* weights)
 {
+    const int DW = policy == 2 ? ORACLE_GRID_CANDIDATES : n;
     for (int b = 0; b < B; ++b) {
         if (dev && n_valid) {
             for (int i = 0; i < n_valid[b]; ++i) {
                 int slot = ring_head[b];
-                for (int j = 0; j < n; ++j)
-                    ring[((size_t)b * h + slot) * n + j] = dev[((size_t)b * gamma + i) * n + j];
+                for (int j = 0; j < DW; ++j)
+                    ring[((size_t)b * h + slot) * DW + j] = dev[((size_t)b * gamma + i) * DW + j];
                 ring_head[b] = (slot + 1) % h;
                 if (ring_count[b] < h) ring_count[b]++;
             }
@@ -414,6 +441,22 @@ void oracle_update_weights(int n, int B, int gamma, int h, int policy,
         }
         double x[64];
         double xmax = -INFINITY;
+        if (policy == 2) { /* arg-min over the candidate mixtures */
+            int best = 0;
+            double ebest = INFINITY;
+            for (int c = 0; c < DW; ++c) {
+                double e = 0.0;
+                for (int t = 0; t < count; ++t) {
+                    int slot = ((ring_head[b] - count + t) % h + h) % h;
+                    e += (double)ring[((size_t)b * h + slot) * DW + c];
+                }
+                if (e < ebest) { ebest = e; best = c; }
+            }
+            const double w1 = (double)best / (double)(DW - 1);
+            w[0] = (float)(1.0 - w1);
+            w[1] = (float)w1;
+            continue;
+        }
         for (int j = 0; j < n; ++j) {
             double e = 0.0;
             for (int t = 0; t < count; ++t) { /* oldest .. newest */

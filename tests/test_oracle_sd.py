@@ -320,3 +320,79 @@ def test_weights_follow_the_draft_that_matches_the_target(oracle):
                             draft_tokens=tok, draft_q=dq, weights=w, temperature=np.ones(B, np.float32))
         dev, nv = out["dev"], out["n_valid"]
         assert np.all(np.abs(w.sum(axis=1) - 1) < 1e-6)
+
+
+# ------------------------------------------------------------------ two-draft grid policy (App. B.2, Alg. 1 line 3)
+def _grid_verify(oracle, logq, logp, distance, T=1.0):
+    gamma, n, V = logq.shape
+    dl = np.ascontiguousarray(logq.astype(np.float32)[:, None])      # [gamma,1,n,V]
+    return oracle.verify(V=V, n=n, B=1, gamma=gamma, distance=distance, seed=0, rnd=0, n_cand=oracle.GRID_CANDIDATES,
+                         target_logits=logp.astype(np.float32)[None], draft_logits=dl,
+                         draft_tokens=np.zeros((1, gamma), np.int32), draft_q=np.ones((1, gamma), np.float32),
+                         weights=np.full((1, n), 0.5, np.float32), temperature=np.full(1, T, np.float32))
+
+
+def test_grid_candidates_are_distances_of_the_mixtures(oracle):
+    rng = np.random.default_rng(31)
+    V, gamma = 120, 2
+    logq, logp, p, _, qj = _dists(rng, gamma, 2, V, (0.5, 0.5))
+    for distance in (0, 1):
+        out = _grid_verify(oracle, logq, logp, distance)
+        assert out["dev"].shape == (1, gamma, 11)
+        for i in range(gamma):
+            ends = []
+            for c in range(11):
+                mix = (1 - c / 10) * qj[i, 0] + (c / 10) * qj[i, 1]
+                ref = sp.rel_entr(p[i], mix).sum() if distance == 0 else 0.5 * np.abs(p[i] - mix).sum()
+                assert abs(out["dev"][0, i, c] - ref) < 1e-6 * max(1.0, ref)
+                ends.append(ref)
+            # the end points are the per-draft distances; both distances are convex in the mixture weight
+            per_draft = oracle.verify(V=V, n=2, B=1, gamma=gamma, distance=distance, seed=0, rnd=0,
+                                      target_logits=logp.astype(np.float32)[None],
+                                      draft_logits=np.ascontiguousarray(logq.astype(np.float32)[:, None]),
+                                      draft_tokens=np.zeros((1, gamma), np.int32), draft_q=np.ones((1, gamma), np.float32),
+                                      weights=np.full((1, 2), 0.5, np.float32), temperature=np.ones(1, np.float32))["dev"]
+            assert abs(out["dev"][0, i, 0] - per_draft[0, i, 0]) < 1e-6 and abs(out["dev"][0, i, 10] - per_draft[0, i, 1]) < 1e-6
+            for c in range(1, 10):
+                assert ends[c] <= (1 - c / 10) * ends[0] + (c / 10) * ends[10] + 1e-12
+
+
+def test_grid_policy_picks_the_mixture_the_target_is_made_of(oracle):
+    rng = np.random.default_rng(32)
+    V, gamma, h = 80, 3, 6
+    for cstar in (0, 3, 7, 10):
+        logq = rng.standard_normal((gamma, 2, V)) * 1.5
+        qj = sp.softmax(logq.astype(np.float32).astype(np.float64), axis=-1)
+        mix = (1 - cstar / 10) * qj[:, 0] + (cstar / 10) * qj[:, 1]
+        logp = np.concatenate([np.log(mix), rng.standard_normal((1, V))])
+        out = _grid_verify(oracle, logq, logp, 0)
+        ring = np.zeros((1, h, 11), np.float32); head = np.zeros(1, np.int32); count = np.zeros(1, np.int32)
+        w = oracle.update_weights(n=2, B=1, gamma=gamma, h=h, policy=2, tau_w=1.0, eps=1e-6, dev=out["dev"],
+                                  n_valid=np.array([gamma], np.int32), ring=ring, ring_head=head, ring_count=count)
+        np.testing.assert_allclose(w[0], [1 - cstar / 10, cstar / 10], atol=1e-7)
+        assert count[0] == gamma and np.array_equal(ring[0, :gamma], out["dev"][0])
+
+
+def test_grid_policy_window_ties_and_empty_window(oracle):
+    ring = np.zeros((2, 4, 11), np.float32); head = np.zeros(2, np.int32); count = np.zeros(2, np.int32)
+    w = oracle.update_weights(n=2, B=2, gamma=1, h=4, policy=2, tau_w=1.0, eps=1e-6, dev=None, n_valid=None,
+                              ring=ring, ring_head=head, ring_count=count)
+    assert np.all(w == np.float32(0.5))                        # empty window: equal weights
+    dev = np.ones((2, 1, 11), np.float32)
+    dev[0, 0, 4] = dev[0, 0, 8] = 0.25                         # tie between candidates 4 and 8 -> lowest index
+    dev[1, 0, 10] = 0.1
+    w = oracle.update_weights(n=2, B=2, gamma=1, h=4, policy=2, tau_w=1.0, eps=1e-6, dev=dev,
+                              n_valid=np.array([1, 1], np.int32), ring=ring, ring_head=head, ring_count=count)
+    np.testing.assert_allclose(w, [[0.6, 0.4], [0.0, 1.0]], atol=1e-7)
+    # brute-force window: only the last h pushed positions count
+    rng = np.random.default_rng(33)
+    log = []
+    ring = np.zeros((1, 3, 11), np.float32); head = np.zeros(1, np.int32); count = np.zeros(1, np.int32)
+    for _ in range(12):
+        dev = rng.random((1, 2, 11)).astype(np.float32)
+        nv = rng.integers(1, 3, 1).astype(np.int32)
+        w = oracle.update_weights(n=2, B=1, gamma=2, h=3, policy=2, tau_w=1.0, eps=1e-6, dev=dev, n_valid=nv,
+                                  ring=ring, ring_head=head, ring_count=count)
+        log += [dev[0, i] for i in range(nv[0])]
+        c = int(np.argmin(np.sum(np.asarray(log[-3:], np.float64), axis=0)))
+        np.testing.assert_allclose(w[0], [1 - c / 10, c / 10], atol=1e-7)
