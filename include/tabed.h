@@ -78,12 +78,20 @@ typedef struct tabed_cfg {
     int32_t gamma;    /* draft block length, 1..TABED_MAX_GAMMA                            */
     int32_t h;        /* observation window length in verified positions, >= 1             */
     int32_t w_dtype;  /* storage type of W and H: 0 = fp32, 1 = bf16                       */
-    int32_t distance; /* D of Alg. 1: 0 = KL(p || q) (Sec. 4.1); 1 = TVD (not built yet)   */
-    int32_t policy;   /* 0 = softmax(1/e; tau_w) (App. B.2); 1 = static equal weights      */
+    int32_t distance; /* D of Alg. 1: 0 = KL(p || q) (Sec. 4.1); 1 = total variation       */
+    int32_t policy;   /* 0 = softmax(1/e; tau_w) (App. B.2); 1 = static equal weights;     */
+                      /* 2 = two-draft grid (App. B.2): arg-min over w^c = [1-c/10, c/10], */
+                      /*     c = 0..10, of the window sum of D(p, mixture); needs n = 2    */
     float tau_w;      /* temperature of the weight softmax, > 0 (paper default 1)          */
     float eps;        /* e is clamped to >= eps before 1/e, > 0                            */
     uint64_t seed;    /* Philox key                                                        */
 } tabed_cfg;
+
+#define TABED_GRID_CANDIDATES 11
+
+/* Width DW of one distance vector (last dimension of `dev` and `ring`): n per-draft distances, or
+ * TABED_GRID_CANDIDATES mixture distances when policy = 2; 0 if cfg is invalid. */
+int32_t tabed_dev_width(const tabed_cfg* cfg);
 
 /* Bytes of scratch the calls below need for this cfg; 0 if cfg is invalid. */
 size_t tabed_workspace_bytes(const tabed_cfg* cfg);
@@ -133,7 +141,8 @@ int tabed_draft_step(const tabed_cfg* cfg, void* ws, uint64_t round, int32_t pos
  *   accept_len    [B]       int32 out  k = number of accepted draft tokens, 0..gamma
  *   out_tokens    [B,gamma+1] int32 out k accepted tokens, then one corrected (k < gamma) or bonus
  *                 (k = gamma) token, then -1
- *   dev           [B,gamma,n] fp32 out D(p_i, q_i^(j)); meaningful for i < n_valid[b]
+ *   dev           [B,gamma,DW] fp32 out D(p_i, q_i^(j)) for every draft j (DW = n), or with policy = 2
+ *                 D(p_i, (1-c/10) q_i^(1) + (c/10) q_i^(2)) for c = 0..10 (DW = 11); meaningful for i < n_valid[b]
  *   n_valid       [B]       int32 out  min(k+1, gamma): positions whose distances enter the window
  *   flags         [B,gamma+1] uint8 out flags of the accept test at i and of the sample emitted at i
  * A drafted token outside [0,V) is rejected and flagged TABED_FLAG_DEGENERATE.
@@ -148,12 +157,13 @@ int tabed_verify(const tabed_cfg* cfg, void* ws, uint64_t round,
 /*
  * Alg. 1 lines 2-3 with the policy of App. B.2: push the distances of the
  * n_valid[b] verified positions of the finished block into the window, then
- * w = softmax((1 / max(e_j, eps)) / tau_w) with e_j the window sum.  An empty
+ * w = softmax((1 / max(e_j, eps)) / tau_w) with e_j the window sum (policy 0), or the candidate
+ * [1-c/10, c/10] with the smallest window sum, lowest c on ties (policy 2).  An empty
  * window, or policy 1, gives equal weights.
  *
- *   dev        [B,gamma,n] fp32  in     may be NULL together with n_valid (nothing to push)
+ *   dev        [B,gamma,DW] fp32 in     may be NULL together with n_valid (nothing to push)
  *   n_valid    [B]         int32 in
- *   ring       [B,h,n]     fp32  in/out caller-owned window state (zero-initialised)
+ *   ring       [B,h,DW]    fp32  in/out caller-owned window state (zero-initialised)
  *   ring_head  [B]         int32 in/out next slot to overwrite
  *   ring_count [B]         int32 in/out live slots, <= h
  *   weights    [B,n]       fp32  out

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtabed.so")
 
 EXPORTS = [
-    "tabed_workspace_bytes", "tabed_workspace_init", "tabed_strerror", "tabed_last_hip_error",
+    "tabed_workspace_bytes", "tabed_workspace_init", "tabed_strerror", "tabed_last_hip_error", "tabed_dev_width",
     "tabed_draft_step", "tabed_verify", "tabed_update_weights", "tabed_philox_uniforms",
     "tabed_prof_enable", "tabed_prof_read", "tabed_prof_reset", "tabed_kernel_name", "tabed_prof_null",
 ]
@@ -49,6 +49,8 @@ def load():
     cfgp = C.POINTER(TabedCfg)
     lib.tabed_workspace_bytes.restype = C.c_size_t
     lib.tabed_workspace_bytes.argtypes = [cfgp]
+    lib.tabed_dev_width.restype = C.c_int32
+    lib.tabed_dev_width.argtypes = [cfgp]
     lib.tabed_workspace_init.restype = C.c_int
     lib.tabed_workspace_init.argtypes = [cfgp, vp, vp]
     lib.tabed_strerror.restype = C.c_char_p
@@ -73,6 +75,9 @@ def load():
     lib.tabed_prof_null.argtypes = [vp]
     _lib = lib
     return lib
+
+
+GRID_CANDIDATES = 11
 
 
 def make_cfg(*, V, d, n, B, gamma, h, w_dtype, distance=0, policy=0, tau_w=1.0, eps=1e-6, seed=0) -> TabedCfg:
@@ -105,6 +110,11 @@ def _stream(stream):
     import torch
     s = torch.cuda.current_stream() if stream is None else stream
     return s.cuda_stream
+
+
+def tabed_dev_width(cfg: TabedCfg) -> int:
+    """Last dimension of `dev` and `ring`: n, or 11 for the two-draft grid policy; 0 for an invalid cfg."""
+    return int(load().tabed_dev_width(C.byref(cfg)))
 
 
 def tabed_workspace_bytes(cfg: TabedCfg) -> int:
@@ -161,7 +171,7 @@ def tabed_verify(cfg, ws, rnd, target_logits, draft_logits, draft_lse, draft_tok
         _ptr(weights, torch.float32, B * n, "weights"), _ptr(temperature, torch.float32, B, "temperature"),
         _ptr(u_acc, torch.float32, B * g, "u_acc"), _ptr(u_res, torch.float32, B, "u_res"),
         _ptr(accept_len, torch.int32, B, "accept_len"), _ptr(out_tokens, torch.int32, B * (g + 1), "out_tokens"),
-        _ptr(dev, torch.float32, B * g * n, "dev"), _ptr(n_valid, torch.int32, B, "n_valid"),
+        _ptr(dev, torch.float32, B * g * tabed_dev_width(cfg), "dev"), _ptr(n_valid, torch.int32, B, "n_valid"),
         _ptr(flags, torch.uint8, B * (g + 1), "flags"), _stream(stream))
     _check(rc, "tabed_verify")
 
@@ -169,10 +179,11 @@ def tabed_verify(cfg, ws, rnd, target_logits, draft_logits, draft_lse, draft_tok
 def tabed_update_weights(cfg, ws, dev, n_valid, ring, ring_head, ring_count, weights, stream=None):
     import torch
     n, B, g, h = cfg.n, cfg.B, cfg.gamma, cfg.h
+    dw = tabed_dev_width(cfg)
     rc = load().tabed_update_weights(
         C.byref(cfg), _ptr(ws, name="ws"),
-        _ptr(dev, torch.float32, B * g * n, "dev"), _ptr(n_valid, torch.int32, B, "n_valid"),
-        _ptr(ring, torch.float32, B * h * n, "ring"), _ptr(ring_head, torch.int32, B, "ring_head"),
+        _ptr(dev, torch.float32, B * g * dw, "dev"), _ptr(n_valid, torch.int32, B, "n_valid"),
+        _ptr(ring, torch.float32, B * h * dw, "ring"), _ptr(ring_head, torch.int32, B, "ring_head"),
         _ptr(ring_count, torch.int32, B, "ring_count"), _ptr(weights, torch.float32, B * n, "weights"),
         _stream(stream))
     _check(rc, "tabed_update_weights")
@@ -236,8 +247,9 @@ class RoundBuffers:
         z = lambda shape, dt: torch.zeros(shape, dtype=dt, device=device)
         self.cfg = cfg
         self.ws = new_workspace(cfg, device)
+        dw = tabed_dev_width(cfg)
         self.weights = z((B, n), torch.float32)
-        self.ring = z((B, h, n), torch.float32)
+        self.ring = z((B, h, dw), torch.float32)
         self.ring_head = z((B,), torch.int32)
         self.ring_count = z((B,), torch.int32)
         self.draft_logits = z((g, B, n, V), torch.float32)
@@ -247,7 +259,7 @@ class RoundBuffers:
         self.draft_flags = z((B, g), torch.uint8)
         self.accept_len = z((B,), torch.int32)
         self.out_tokens = z((B, g + 1), torch.int32)
-        self.dev = z((B, g, n), torch.float32)
+        self.dev = z((B, g, dw), torch.float32)
         self.n_valid = z((B,), torch.int32)
         self.verify_flags = z((B, g + 1), torch.uint8)
 

@@ -19,11 +19,11 @@ int validate_cfg(const tabed_cfg* c) {
     if (c->w_dtype != 0 && c->w_dtype != 1) return TABED_EINVAL;
     if (c->w_dtype == 1 && (c->d % 8) != 0) return TABED_EINVAL;
     if (c->distance != 0 && c->distance != 1) return TABED_EINVAL;
-    if (c->policy != 0 && c->policy != 1) return TABED_EINVAL;
+    if (c->policy < 0 || c->policy > 2) return TABED_EINVAL;
+    if (c->policy == 2 && c->n != 2) return TABED_EINVAL;
     if (!(c->tau_w > 0.f) || !(c->eps > 0.f)) return TABED_EINVAL;
     if ((long long)c->B * c->n > (1ll << 24)) return TABED_ERANGE;
     if (c->V > kTileV * kBlock * 20) return TABED_ERANGE;      // 163840: largest vocabulary the sampler tiles
-    if (c->distance == 1) return TABED_EUNSUPPORTED;
     return TABED_OK;
 }
 
@@ -36,6 +36,8 @@ WsLayout ws_layout(const tabed_cfg& c) {
     L.NSEG = (c.V + kSegV - 1) / kSegV;
     L.C5 = (c.V + kResidChunkV - 1) / kResidChunkV;
     L.RS = kStatHdr + c.n;
+    L.DW = (c.policy == 2) ? TABED_GRID_CANDIDATES : c.n;
+    L.Cd = (c.V + kChunkV - 1) / kChunkV;
     size_t off = 0;
     L.off_tickets = off; off = align_up(off + sizeof(uint32_t) * 3 * (size_t)c.B);
     L.off_pm = off;      off = align_up(off + sizeof(float) * (size_t)L.M * L.NT);
@@ -43,6 +45,7 @@ WsLayout ws_layout(const tabed_cfg& c) {
     L.off_cand = off;    off = align_up(off + sizeof(Top2Rec) * (size_t)c.B * L.C2);
     L.off_stats = off;   off = align_up(off + sizeof(double) * (size_t)c.B * (c.gamma + 1) * L.C3max * L.RS);
     L.off_seg = off;     off = align_up(off + sizeof(double) * 2 * (size_t)c.B * L.NSEG);
+    L.off_dist = off;    off = align_up(off + sizeof(double) * (size_t)c.B * c.gamma * L.DW * L.Cd);
     L.total = off;
     return L;
 }
@@ -87,6 +90,11 @@ static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) &
 using namespace tabed;
 
 extern "C" {
+
+int32_t tabed_dev_width(const tabed_cfg* cfg) {
+    if (validate_cfg(cfg) != TABED_OK) return 0;
+    return ws_layout(*cfg).DW;
+}
 
 size_t tabed_workspace_bytes(const tabed_cfg* cfg) {
     if (validate_cfg(cfg) != TABED_OK) return 0;

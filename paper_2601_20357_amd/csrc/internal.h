@@ -28,12 +28,15 @@ struct Top2Rec {                // chunk candidate of the greedy draft arg-max
 // Where everything lives inside the caller's workspace (byte offsets, 256-byte aligned).
 struct WsLayout {
     int M, NT, C2, C3max, NSEG, C5, RS;
+    int DW;              // width of one distance vector: n, or 11 candidate mixtures (policy 2)
+    int Cd;              // vocabulary chunks of the second-pass distance kernel
     size_t off_tickets;  // uint32 [3][B]: arrival counters (0: greedy draft arg-max, 2: corrected/bonus sampler)
     size_t off_pm;       // float  [M][NT] tile maxima of scaled logits
     size_t off_ps;       // float  [M][NT] tile sums of exp(scaled logit - tile max)
     size_t off_cand;     // Top2Rec [B][C2]
     size_t off_stats;    // double [B][gamma+1][C3max][RS]
     size_t off_seg;      // double [B][2][NSEG] segment masses: residual, target
+    size_t off_dist;     // double [B][gamma][DW][Cd] chunk sums of the second-pass distances (TVD, grid policy)
     size_t total;
 };
 WsLayout ws_layout(const tabed_cfg& c);

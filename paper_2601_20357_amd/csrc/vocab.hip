@@ -48,12 +48,13 @@ hipError_t launch_philox(const tabed_cfg& c, uint64_t round, float* out, hipStre
 
 // One 64-lane workgroup per sequence.  The window after pushing the nv new positions is the newest
 // min(count + nv, h) entries of (old ring entries ++ new entries); every lane loads its share of them in
-// parallel (no load depends on a store), lane j sums draft j's column in fp64, the softmax of 1/e follows,
-// and only then are the new positions stored into the ring.  B*n scalars: latency-bound.
-__global__ __launch_bounds__(64) void k_weights(int n, int B, int gamma, int h, int policy, double tau_w, double eps,
-                                                const float* __restrict__ dev, const int32_t* __restrict__ n_valid,
-                                                float* ring, int32_t* ring_head, int32_t* ring_count,
-                                                float* weights) {
+// parallel (no load depends on a store), lane j sums column j in fp64, the policy follows (softmax of 1/e
+// over the n drafts, or arg-min over the 11 candidate mixtures), and only then are the new positions stored
+// into the ring.  dw = width of one distance vector.  A few hundred scalars: latency-bound.
+__global__ __launch_bounds__(64) void k_weights(int n, int dw, int B, int gamma, int h, int policy, double tau_w,
+                                                double eps, const float* __restrict__ dev,
+                                                const int32_t* __restrict__ n_valid, float* ring,
+                                                int32_t* ring_head, int32_t* ring_count, float* weights) {
     const int b = blockIdx.x, lane = threadIdx.x;
     __shared__ double s_part[64];
     __shared__ double s_x[TABED_MAX_N];
@@ -66,31 +67,36 @@ __global__ __launch_bounds__(64) void k_weights(int n, int B, int gamma, int h, 
         nv = nv < 0 ? 0 : (nv > gamma ? gamma : nv);
     }
     const int new_count = (count + nv < h) ? count + nv : h;
-    float* rb = ring + (size_t)b * h * n;
-    const float* db = dev ? dev + (size_t)b * gamma * n : nullptr;
-    const int per = 64 / n;                       // lanes per draft column (n <= 16 => per >= 4)
-    const int j = lane % n, t0 = lane / n;
+    float* rb = ring + (size_t)b * h * dw;
+    const float* db = dev ? dev + (size_t)b * gamma * dw : nullptr;
+    const int per = 64 / dw;                      // lanes per column (dw <= 16 => per >= 4)
+    const int j = lane % dw, t0 = lane / dw;
     double acc = 0.0;
-    if (lane < per * n) {
+    if (lane < per * dw) {
         for (int r = t0; r < new_count; r += per) {   // r-th newest entry of the new window
             float v;
-            if (r < nv) v = db[(size_t)(nv - 1 - r) * n + j];
-            else        v = rb[(size_t)((((head - 1 - (r - nv)) % h) + h) % h) * n + j];
+            if (r < nv) v = db[(size_t)(nv - 1 - r) * dw + j];
+            else        v = rb[(size_t)((((head - 1 - (r - nv)) % h) + h) % h) * dw + j];
             acc += (double)v;
         }
     }
     s_part[lane] = acc;
     __syncthreads();
-    if (lane < n) {
+    if (lane < dw) {
         double e = 0.0;
-        for (int q = 0; q < per; ++q) e += s_part[q * n + lane];
-        s_x[lane] = (1.0 / fmax(e, eps)) / tau_w;
+        for (int q = 0; q < per; ++q) e += s_part[q * dw + lane];
+        s_x[lane] = (policy == 2) ? e : (1.0 / fmax(e, eps)) / tau_w;
     }
     __syncthreads();
     if (lane < n) {
         float w;
         if (policy == 1 || new_count == 0) {
             w = (float)(1.0 / (double)n);
+        } else if (policy == 2) {
+            int best = 0;                             // arg-min of the window sums, lowest index on ties
+            for (int q = 1; q < dw; ++q) if (s_x[q] < s_x[best]) best = q;
+            const double w1 = (double)best / (double)(dw - 1);
+            w = (float)(lane == 0 ? 1.0 - w1 : w1);
         } else {
             double xmax = -INFINITY;
             for (int q = 0; q < n; ++q) xmax = fmax(xmax, s_x[q]);
@@ -101,9 +107,9 @@ __global__ __launch_bounds__(64) void k_weights(int n, int B, int gamma, int h, 
         weights[(size_t)b * n + lane] = w;
     }
     if (nv > 0) {
-        for (int idx = lane; idx < nv * n; idx += 64) {
-            const int i = idx / n, jj = idx % n;
-            if (i >= nv - h) rb[(size_t)((head + i) % h) * n + jj] = db[(size_t)i * n + jj];
+        for (int idx = lane; idx < nv * dw; idx += 64) {
+            const int i = idx / dw, jj = idx % dw;
+            if (i >= nv - h) rb[(size_t)((head + i) % h) * dw + jj] = db[(size_t)i * dw + jj];
         }
         if (lane == 0) {
             ring_head[b] = (head + nv) % h;
@@ -115,8 +121,9 @@ __global__ __launch_bounds__(64) void k_weights(int n, int B, int gamma, int h, 
 hipError_t launch_weights(const tabed_cfg& c, const float* dev, const int32_t* n_valid, float* ring,
                           int32_t* ring_head, int32_t* ring_count, float* weights, hipStream_t s) {
     ProfScope prof(TABED_K_WEIGHTS, s);
-    launch(&prof, k_weights, dim3(c.B), dim3(64), 0, s, c.n, c.B, c.gamma, c.h, c.policy,
-                       (double)c.tau_w, (double)c.eps, dev, n_valid, ring, ring_head, ring_count, weights);
+    const int dw = (c.policy == 2) ? TABED_GRID_CANDIDATES : c.n;
+    launch(&prof, k_weights, dim3(c.B), dim3(64), 0, s, c.n, dw, c.B, c.gamma, c.h, c.policy,
+           (double)c.tau_w, (double)c.eps, dev, n_valid, ring, ring_head, ring_count, weights);
     return hipGetLastError();
 }
 
@@ -455,6 +462,7 @@ hipError_t launch_sample(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
 // =====================================================================================================
 struct StatsArgs {
     int V, n, B, gamma, C3, RS;
+    int with_drafts;      // 0: only the target-row part of the records (distances come from k_dist)
     const float* target;
     const float* dlogits;
     const float* temperature;
@@ -476,7 +484,7 @@ __global__ __launch_bounds__(kBlock) void k_stats(StatsArgs a) {
     const float* trow = a.target + ((size_t)b * (gamma + 1) + i) * V;
     const float* qbase = a.dlogits + (((size_t)i * a.B + b) * n) * V;   // only dereferenced when i < gamma
     const int cb = c * (kBlock * 4 * U);
-    const bool drafts = (i < gamma);
+    const bool drafts = (i < gamma) && a.with_drafts;
 
     float4 tx[U];
     float4 dx[(N > 0) ? N : 1][U];
@@ -561,6 +569,130 @@ __global__ __launch_bounds__(kBlock) void k_stats(StatsArgs a) {
     if (drafts && tid < n) rec[kStatHdr + tid] = (s_A[0][tid] + s_A[1][tid]) + (s_A[2][tid] + s_A[3][tid]);
 }
 
+// =====================================================================================================
+// Second-pass distances: total variation, and the two-draft grid policy's candidate mixtures.
+// |p - q| (and log of a mixture) cannot be accumulated before the target row's normaliser is known, so
+// these modes take one more pass over the rows: grid (chunk, position i < gamma, sequence b); every
+// workgroup first combines the row's records from k_stats (lse_p), then sums, over its 4096-wide chunk,
+//   MODE 0: |p - q_j|                         per draft j                (TVD, DW = n)
+//   MODE 1: p (log p - log mix_c)             per candidate c = 0..10    (KL of the mixtures, n = 2)
+//   MODE 2: |p - mix_c|                       per candidate c            (TVD of the mixtures, n = 2)
+// with mix_c = (1 - c/10) q_1 + (c/10) q_2.  Chunk sums go to dist[b][i][c][chunk]; k_finish adds them.
+// =====================================================================================================
+struct DistArgs {
+    int V, n, B, gamma, C3, RS, DW, Cd;
+    const float* target;
+    const float* dlogits;
+    const double* dlse;
+    const float* temperature;
+    const double* stats;
+    double* dist;
+};
+
+template <bool VEC, int MODE>
+__global__ __launch_bounds__(kBlock) void k_dist(DistArgs a) {
+    const int c = blockIdx.x, i = blockIdx.y, b = blockIdx.z, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int V = a.V, n = a.n, gamma = a.gamma;
+    constexpr int NC = TABED_GRID_CANDIDATES;
+    __shared__ double s_lse;
+    __shared__ float s_hi[TABED_MAX_N], s_oml[TABED_MAX_N];
+    __shared__ double s_sum[kWavesPerBlock][TABED_MAX_N];
+
+    const float* trow = a.target + ((size_t)b * (gamma + 1) + i) * V;
+    const float* qbase = a.dlogits + (((size_t)i * a.B + b) * n) * V;
+    const int cb = c * kChunkV;
+    float4 tx[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) tx[u] = load4<VEC>(trow, cb + (u * kBlock + tid) * 4, V);
+    const float T = a.temperature[b];
+    const float invT = (T > 0.f) ? 1.f / T : 1.f;
+    if (tid < n) {
+        const double l = a.dlse[((size_t)i * a.B + b) * n + tid];
+        const float hi = (float)l;
+        s_hi[tid] = hi;
+        s_oml[tid] = (float)(1.0 - (l - (double)hi));
+    }
+    if (wave == 0) {                                   // lse of target row (b, i) from its records
+        const double* r0 = a.stats + ((size_t)b * (gamma + 1) + i) * a.C3 * a.RS;
+        double m = -INFINITY;
+        for (int cc = lane; cc < a.C3; cc += kWave) m = fmax(m, r0[(size_t)cc * a.RS]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) m = fmax(m, __shfl_xor(m, o));
+        double Z = 0.0;
+        for (int cc = lane; cc < a.C3; cc += kWave) {
+            const double* r = r0 + (size_t)cc * a.RS;
+            if (r[0] > -INFINITY) Z += r[1] * exp(r[0] - m);
+        }
+        Z = wave_sum(Z);
+        if (lane == 0) s_lse = m + log(Z);
+    }
+    __syncthreads();
+    const double lse = s_lse;
+    const float lhi = (float)lse, loml = (float)(1.0 - (lse - (double)lhi));
+
+    float pv[16], lp[16];                              // p and log p of this thread's 16 elements
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float xe = f4get(tx[u], e);
+            const float st = xe * invT;
+            const bool ok = xe > -INFINITY;
+            pv[u * 4 + e] = ok ? __expf(st - lhi) * loml : 0.f;
+            lp[u * 4 + e] = ok ? (st - lhi) + (loml - 1.f) : 0.f;
+        }
+
+    if (MODE == 0) {
+        for (int j = 0; j < n; ++j) {
+            float acc = 0.f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float4 y = load4<VEC>(qbase + (size_t)j * V, cb + (u * kBlock + tid) * 4, V);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float ye = f4get(y, e);
+                    const float q = (ye > -INFINITY) ? __expf(ye * invT - s_hi[j]) * s_oml[j] : 0.f;
+                    acc += fabsf(pv[u * 4 + e] - q);
+                }
+            }
+            const double t = wave_sum((double)acc);
+            if (lane == 0) s_sum[wave][j] = t;
+        }
+    } else {
+        float acc[NC];
+#pragma unroll
+        for (int k = 0; k < NC; ++k) acc[k] = 0.f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float4 y0 = load4<VEC>(qbase, cb + (u * kBlock + tid) * 4, V);
+            const float4 y1 = load4<VEC>(qbase + (size_t)V, cb + (u * kBlock + tid) * 4, V);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float a0 = f4get(y0, e), a1 = f4get(y1, e);
+                const float q0 = (a0 > -INFINITY) ? __expf(a0 * invT - s_hi[0]) * s_oml[0] : 0.f;
+                const float q1 = (a1 > -INFINITY) ? __expf(a1 * invT - s_hi[1]) * s_oml[1] : 0.f;
+                const float p = pv[u * 4 + e];
+#pragma unroll
+                for (int k = 0; k < NC; ++k) {
+                    const float w1 = (float)((double)k / (double)(NC - 1)), w0 = (float)(1.0 - (double)k / (double)(NC - 1));
+                    const float mix = w0 * q0 + w1 * q1;
+                    if (MODE == 1) { if (p > 0.f) acc[k] += p * (lp[u * 4 + e] - logf(mix)); }
+                    else acc[k] += fabsf(p - mix);
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < NC; ++k) {
+            const double t = wave_sum((double)acc[k]);
+            if (lane == 0) s_sum[wave][k] = t;
+        }
+    }
+    __syncthreads();
+    if (tid < a.DW)
+        a.dist[(((size_t)b * gamma + i) * a.DW + tid) * a.Cd + c] =
+            (s_sum[0][tid] + s_sum[1][tid]) + (s_sum[2][tid] + s_sum[3][tid]);
+}
+
 static int pick_stats_unroll(const tabed_cfg& c, int nmax_u) {
     // Largest chunk that still gives the chip a few workgroups per compute unit.
     const long rows = (long)c.B * (c.gamma + 1);
@@ -607,6 +739,9 @@ struct FinishArgs {
     const float* u_acc;
     const float* u_res;
     const double* stats;
+    const double* dist;   // [B][gamma][DW][Cd] second-pass chunk sums, or nullptr (KL from the records)
+    int DW, Cd;
+    float dist_scale;     // 0.5 for total variation, 1 for KL
     double* seg;          // [B][2][NSEG]
     uint32_t* tickets;
     int32_t* accept_len;
@@ -822,15 +957,25 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
     }
 
     if (c == 0) {
-        // ---- distances: thread per (position, draft), chunks in order with the scales computed above
-        for (int q = tid; q < gamma * n; q += kBlock) {
-            const int ii = q / n, j = q % n;
-            const double* r0 = sb + (size_t)ii * C3 * RS + kStatHdr + j;
-            double A = 0.0;
+        if (a.dist == nullptr) {
+            // ---- distances: thread per (position, draft), chunks in order with the scales computed above
+            for (int q = tid; q < gamma * n; q += kBlock) {
+                const int ii = q / n, j = q % n;
+                const double* r0 = sb + (size_t)ii * C3 * RS + kStatHdr + j;
+                double A = 0.0;
 #pragma unroll 8
-            for (int cc = 0; cc < C3; ++cc) A += r0[(size_t)cc * RS] * s_scale[ii * C3 + cc];
-            const double kl = A / s_rowZ[ii] - s_rowlse[ii] + a.dlse[((size_t)ii * a.B + b) * n + j];
-            a.dev[((size_t)b * gamma + ii) * n + j] = (float)kl;
+                for (int cc = 0; cc < C3; ++cc) A += r0[(size_t)cc * RS] * s_scale[ii * C3 + cc];
+                const double kl = A / s_rowZ[ii] - s_rowlse[ii] + a.dlse[((size_t)ii * a.B + b) * n + j];
+                a.dev[((size_t)b * gamma + ii) * n + j] = (float)kl;
+            }
+        } else {
+            // ---- distances from the second pass: add the chunk sums in chunk order
+            for (int q = tid; q < gamma * a.DW; q += kBlock) {
+                const double* r0 = a.dist + ((size_t)b * gamma * a.DW + q) * a.Cd;
+                double D = 0.0;
+                for (int cc = 0; cc < a.Cd; ++cc) D += r0[cc];
+                a.dev[(size_t)b * gamma * a.DW + q] = (float)((double)a.dist_scale * D);
+            }
         }
         if (tid <= gamma) {
             // accepted prefix, -1 padding, flags of the tests that were evaluated; slot k belongs to the sampler
@@ -941,6 +1086,7 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
                          const float* temperature, const float* u_acc, const float* u_res, int32_t* accept_len,
                          int32_t* out_tokens, float* dev, int32_t* n_valid, uint8_t* flags, hipStream_t s) {
     const bool vec = (c.V % 4 == 0);
+    const bool second_pass = (c.distance == 1 || c.policy == 2);   // distances that need lse_p before the pass
     const int ncomp = (vec && (c.n == 2 || c.n == 4 || c.n == 8)) ? c.n : 0;   // compile-time draft counts
     const int U = pick_stats_unroll(c, ncomp == 8 ? 2 : 4);
     const int C3 = (c.V + kBlock * 4 * U - 1) / (kBlock * 4 * U);
@@ -948,6 +1094,7 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
         ProfScope prof(TABED_K_STATS, s);
         StatsArgs a;
         a.V = c.V; a.n = c.n; a.B = c.B; a.gamma = c.gamma; a.RS = L.RS; a.C3 = C3;
+        a.with_drafts = second_pass ? 0 : 1;
         a.target = target_logits; a.dlogits = draft_logits; a.temperature = temperature;
         a.stats = reinterpret_cast<double*>(ws + L.off_stats);
         const dim3 grid(C3, c.gamma + 1, c.B);
@@ -956,8 +1103,28 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
         else if (ncomp == 4) launch_stats_n<true, 4>(&prof, U, grid, s, a);
         else if (ncomp == 8) launch_stats_n<true, 8>(&prof, U, grid, s, a);
         else launch_stats_n<true, 0>(&prof, U, grid, s, a);
-        const hipError_t e = hipGetLastError();
+        hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
+        if (second_pass) {
+            DistArgs d;
+            d.V = c.V; d.n = c.n; d.B = c.B; d.gamma = c.gamma; d.C3 = C3; d.RS = L.RS; d.DW = L.DW; d.Cd = L.Cd;
+            d.target = target_logits; d.dlogits = draft_logits; d.dlse = draft_lse; d.temperature = temperature;
+            d.stats = a.stats;
+            d.dist = reinterpret_cast<double*>(ws + L.off_dist);
+            const dim3 gd(L.Cd, c.gamma, c.B);
+            const int mode = (c.policy != 2) ? 0 : (c.distance == 0 ? 1 : 2);
+            if (vec) {
+                if (mode == 0) launch(&prof, k_dist<true, 0>, gd, dim3(kBlock), 0, s, d);
+                else if (mode == 1) launch(&prof, k_dist<true, 1>, gd, dim3(kBlock), 0, s, d);
+                else launch(&prof, k_dist<true, 2>, gd, dim3(kBlock), 0, s, d);
+            } else {
+                if (mode == 0) launch(&prof, k_dist<false, 0>, gd, dim3(kBlock), 0, s, d);
+                else if (mode == 1) launch(&prof, k_dist<false, 1>, gd, dim3(kBlock), 0, s, d);
+                else launch(&prof, k_dist<false, 2>, gd, dim3(kBlock), 0, s, d);
+            }
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
     }
     ProfScope prof(TABED_K_RESID, s);
     FinishArgs a;
@@ -966,6 +1133,8 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
     a.target = target_logits; a.dlogits = draft_logits; a.dlse = draft_lse; a.dtok = draft_tokens; a.dq = draft_q;
     a.weights = weights; a.temperature = temperature; a.u_acc = u_acc; a.u_res = u_res;
     a.stats = reinterpret_cast<const double*>(ws + L.off_stats);
+    a.dist = second_pass ? reinterpret_cast<const double*>(ws + L.off_dist) : nullptr;
+    a.DW = L.DW; a.Cd = L.Cd; a.dist_scale = (c.distance == 1) ? 0.5f : 1.f;
     a.seg = reinterpret_cast<double*>(ws + L.off_seg);
     a.tickets = reinterpret_cast<uint32_t*>(ws + L.off_tickets) + 2 * c.B;
     a.accept_len = accept_len; a.out_tokens = out_tokens; a.dev = dev; a.n_valid = n_valid; a.flags = flags;

@@ -26,16 +26,17 @@ def to_dev_store(x: np.ndarray, w_dtype: int) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).to(DEV).view(torch.bfloat16)
 
 
-def cfg_of(wl: synth.Workload, seed=0, policy=0, tau_w=1.0, eps=1e-6):
+def cfg_of(wl: synth.Workload, seed=0, policy=0, tau_w=1.0, eps=1e-6, distance=0):
     return binding.make_cfg(V=wl.V, d=wl.d, n=wl.n, B=wl.B, gamma=wl.gamma, h=wl.h, w_dtype=wl.w_dtype,
-                            policy=policy, tau_w=tau_w, eps=eps, seed=seed)
+                            policy=policy, tau_w=tau_w, eps=eps, seed=seed, distance=distance)
 
 
 class OracleSide:
-    def __init__(self, oracle, wl, seed=0, policy=0, tau_w=1.0, eps=1e-6):
+    def __init__(self, oracle, wl, seed=0, policy=0, tau_w=1.0, eps=1e-6, distance=0):
         self.o, self.wl, self.seed, self.policy, self.tau_w, self.eps = oracle, wl, seed, policy, tau_w, eps
+        self.distance = distance
         B, n, g, h, V = wl.B, wl.n, wl.gamma, wl.h, wl.V
-        self.ring = np.zeros((B, h, n), np.float32)
+        self.ring = np.zeros((B, h, oracle.dev_width(n, policy)), np.float32)
         self.head = np.zeros(B, np.int32)
         self.count = np.zeros(B, np.int32)
         self.dev = None
@@ -56,18 +57,18 @@ class OracleSide:
             o.draft_step(V=V, d=wl.d, n=n, B=B, gamma=g, w_dtype=wl.w_dtype, seed=self.seed, rnd=rnd, pos=pos, W=W,
                          H=H[pos], weights=w, temperature=temp, draft_logits=dl, draft_lse=lse, draft_tokens=tok,
                          draft_q=dq, flags=fl, u_draft=u_draft)
-        out = o.verify(V=V, n=n, B=B, gamma=g, distance=0, seed=self.seed, rnd=rnd, target_logits=target,
+        out = o.verify(V=V, n=n, B=B, gamma=g, distance=self.distance, seed=self.seed, rnd=rnd, target_logits=target,
                        draft_logits=dl, draft_tokens=tok, draft_q=dq, weights=w, temperature=temp, u_acc=u_acc,
-                       u_res=u_res)
+                       u_res=u_res, n_cand=o.GRID_CANDIDATES if self.policy == 2 else 0)
         self.dev, self.n_valid = out["dev"], out["n_valid"]
         out.update(weights=w, draft_logits=dl, draft_lse=lse, draft_tokens=tok, draft_q=dq, draft_flags=fl)
         return out
 
 
 class GpuSide:
-    def __init__(self, wl, seed=0, policy=0, tau_w=1.0, eps=1e-6):
+    def __init__(self, wl, seed=0, policy=0, tau_w=1.0, eps=1e-6, distance=0):
         self.wl = wl
-        self.cfg = cfg_of(wl, seed, policy, tau_w, eps)
+        self.cfg = cfg_of(wl, seed, policy, tau_w, eps, distance)
         self.buf = binding.RoundBuffers(self.cfg, DEV)
         self.first = True
 
@@ -167,11 +168,11 @@ def compare_round(g, o, wl, tally: Tally, check_logits=True):
     return lock
 
 
-def run_rounds(oracle, wl, rounds, temp, seed=0, policy=0, check_logits=True, uniforms=None, W=None):
+def run_rounds(oracle, wl, rounds, temp, seed=0, policy=0, check_logits=True, uniforms=None, W=None, distance=0):
     """Drive both sides for `rounds` rounds with state carried over; returns the tally."""
     W = synth.make_lm_head(wl) if W is None else W
     W_t = to_dev_store(W, wl.w_dtype)
-    orc, gpu = OracleSide(oracle, wl, seed, policy), GpuSide(wl, seed, policy)
+    orc, gpu = OracleSide(oracle, wl, seed, policy, distance=distance), GpuSide(wl, seed, policy, distance=distance)
     tally = Tally()
     for rnd in range(rounds):
         H, target = synth.make_round(wl, W, rnd)

@@ -56,10 +56,13 @@ def test_workspace_bytes_and_cfg_validation(lib):
     assert binding.tabed_workspace_bytes(good_cfg()) > 2 * 64 * 1000 * 4
     assert binding.tabed_workspace_bytes(good_cfg(V=1, d=8, n=1, B=1, gamma=1, h=1)) > 0
     for bad in (dict(V=0), dict(n=0), dict(n=17), dict(gamma=0), dict(gamma=33), dict(h=0), dict(B=0),
-                dict(d=100), dict(w_dtype=2), dict(tau_w=0.0), dict(eps=0.0), dict(policy=5), dict(distance=7)):
+                dict(d=100), dict(w_dtype=2), dict(tau_w=0.0), dict(eps=0.0), dict(policy=5), dict(distance=7),
+                dict(policy=2)):                      # the grid policy is defined for two drafts only
         assert binding.tabed_workspace_bytes(good_cfg(**bad)) == 0, bad
     assert binding.tabed_workspace_bytes(good_cfg(d=100, w_dtype=0)) > 0      # fp32 storage has no d % 8 rule
     assert binding.tabed_workspace_bytes(good_cfg(V=32001)) > 0               # ragged vocabularies are fine
+    assert binding.tabed_dev_width(good_cfg()) == 4 and binding.tabed_dev_width(good_cfg(distance=1)) == 4
+    assert binding.tabed_dev_width(good_cfg(n=2, policy=2)) == 11 and binding.tabed_dev_width(good_cfg(n=3, policy=2)) == 0
 
 
 def test_error_codes_are_returned_before_any_launch(lib):
@@ -83,7 +86,7 @@ def test_error_codes_are_returned_before_any_launch(lib):
     # invalid / unsupported configuration
     assert lib.tabed_draft_step(C.byref(good_cfg(n=99)), fake, 0, 0, *([fake] * 10), None) == -3
     assert lib.tabed_draft_step(C.byref(good_cfg(V=-4)), fake, 0, 0, *([fake] * 10), None) == -2
-    assert lib.tabed_verify(C.byref(good_cfg(distance=1)), fake, 0, *([fake] * 15), None) == -5
+    assert lib.tabed_verify(C.byref(good_cfg(policy=2)), fake, 0, *([fake] * 15), None) == -2   # needs n = 2
     assert lib.tabed_workspace_init(C.byref(cfg), None, None) == -1
     for code in (0, -1, -2, -3, -4, -5, -6):
         assert lib.tabed_strerror(code).decode() not in ("", "unknown error code")

@@ -74,6 +74,18 @@ def test_static_policy_and_other_tau(oracle):
     assert t.max_w_err == 0.0
 
 
+# ------------------------------------------------------------------ total variation distance and the two-draft grid policy
+@pytest.mark.parametrize("policy,distance,n", [(0, 1, 4), (2, 0, 2), (2, 1, 2), (1, 1, 3)],
+                         ids=["tvd", "grid-kl", "grid-tvd", "static-tvd"])
+def test_distance_and_policy_variants(oracle, policy, distance, n):
+    for V, d, B, mode in ((4100, 64, 5, "mixed07"), (4099, 72, 3, "one"), (32000, 768, 4, "one")):
+        wl = synth.scaled(SERVING, V=V, d=d, n=n, B=B, gamma=3, h=5, cfg_id=70 + policy * 2 + distance)
+        _say(f"variant policy={policy} distance={distance} V={V}")
+        tally = harness.run_rounds(oracle, wl, 5, synth.make_temperature(wl, mode), policy=policy, distance=distance)
+        _say(tally)
+        assert tally.flagged_divergences <= max(2, tally.decisions // 50)
+
+
 # ------------------------------------------------------------------ explicit uniforms, including the edges of [0,1)
 def test_explicit_uniform_edges(oracle):
     wl = synth.scaled(SERVING, V=3000, d=64, n=3, B=8, gamma=3, h=4, cfg_id=52)
