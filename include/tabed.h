@@ -76,7 +76,8 @@ typedef struct tabed_cfg {
     int32_t n;        /* drafting methods batched through the draft model, 1..TABED_MAX_N  */
     int32_t B;        /* independent sequences, >= 1                                       */
     int32_t gamma;    /* draft block length, 1..TABED_MAX_GAMMA                            */
-    int32_t h;        /* observation window length in verified positions, >= 1             */
+    int32_t h;        /* observation window length in verified positions, >= 1; 0 = ALL    */
+                      /* positions since the start (the paper's default, App. B.1)         */
     int32_t w_dtype;  /* storage type of W and H: 0 = fp32, 1 = bf16                       */
     int32_t distance; /* D of Alg. 1: 0 = KL(p || q) (Sec. 4.1); 1 = total variation       */
     int32_t policy;   /* 0 = softmax(1/e; tau_w) (App. B.2); 1 = static equal weights;     */
@@ -163,9 +164,10 @@ int tabed_verify(const tabed_cfg* cfg, void* ws, uint64_t round,
  *
  *   dev        [B,gamma,DW] fp32 in     may be NULL together with n_valid (nothing to push)
  *   n_valid    [B]         int32 in
- *   ring       [B,h,DW]    fp32  in/out caller-owned window state (zero-initialised)
+ *   ring       [B,h,DW]    fp32  in/out caller-owned window state (zero-initialised); with h = 0 it is
+ *                                       [B,1,DW]: the running fp32 sum of all verified positions
  *   ring_head  [B]         int32 in/out next slot to overwrite
- *   ring_count [B]         int32 in/out live slots, <= h
+ *   ring_count [B]         int32 in/out live slots, <= h (h = 0: positions summed so far)
  *   weights    [B,n]       fp32  out
  */
 int tabed_update_weights(const tabed_cfg* cfg, void* ws, const float* dev, const int32_t* n_valid,

@@ -201,7 +201,7 @@ def verify(*, V, n, B, gamma, distance, seed, rnd, target_logits, draft_logits, 
 
 def update_weights(*, n, B, gamma, h, policy, tau_w, eps, dev, n_valid, ring, ring_head, ring_count):
     """Alg. 1 lines 2-3 (App. B.2 policy); ring state is updated in place; returns weights [B,n]."""
-    assert ring.dtype == np.float32 and ring.shape == (B, h, dev_width(n, policy))
+    assert ring.dtype == np.float32 and ring.shape == (B, max(h, 1), dev_width(n, policy))   # h = 0: window ALL
     assert policy != 2 or n == 2
     assert ring_head.dtype == np.int32 and ring_count.dtype == np.int32
     d_ = None if dev is None else _f32(dev)

@@ -423,9 +423,17 @@ void oracle_update_weights(int n, int B, int gamma, int h, int policy,
                            float* weights)
 {
     const int DW = policy == 2 ? ORACLE_GRID_CANDIDATES : n;
+    const int all = (h == 0);
+    if (all) h = 1;
     for (int b = 0; b < B; ++b) {
         if (dev && n_valid) {
             for (int i = 0; i < n_valid[b]; ++i) {
+                if (all) { /* running sum, one fp32 addition per verified position, in order */
+                    for (int j = 0; j < DW; ++j)
+                        ring[(size_t)b * DW + j] = ring[(size_t)b * DW + j] + dev[((size_t)b * gamma + i) * DW + j];
+                    if (ring_count[b] < INT32_MAX) ring_count[b]++;
+                    continue;
+                }
                 int slot = ring_head[b];
                 for (int j = 0; j < DW; ++j)
                     ring[((size_t)b * h + slot) * DW + j] = dev[((size_t)b * gamma + i) * DW + j];
@@ -435,6 +443,7 @@ void oracle_update_weights(int n, int B, int gamma, int h, int policy,
         }
         float* w = weights + (size_t)b * n;
         int count = ring_count[b];
+        if (all && count > 1) count = 1; /* the single slot already holds the sum; head stays 0 */
         if (policy == 1 || count == 0) {
             for (int j = 0; j < n; ++j) w[j] = (float)(1.0 / n);
             continue;

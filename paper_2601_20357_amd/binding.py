@@ -183,7 +183,7 @@ def tabed_update_weights(cfg, ws, dev, n_valid, ring, ring_head, ring_count, wei
     rc = load().tabed_update_weights(
         C.byref(cfg), _ptr(ws, name="ws"),
         _ptr(dev, torch.float32, B * g * dw, "dev"), _ptr(n_valid, torch.int32, B, "n_valid"),
-        _ptr(ring, torch.float32, B * h * dw, "ring"), _ptr(ring_head, torch.int32, B, "ring_head"),
+        _ptr(ring, torch.float32, B * max(h, 1) * dw, "ring"), _ptr(ring_head, torch.int32, B, "ring_head"),
         _ptr(ring_count, torch.int32, B, "ring_count"), _ptr(weights, torch.float32, B * n, "weights"),
         _stream(stream))
     _check(rc, "tabed_update_weights")
@@ -249,7 +249,7 @@ class RoundBuffers:
         self.ws = new_workspace(cfg, device)
         dw = tabed_dev_width(cfg)
         self.weights = z((B, n), torch.float32)
-        self.ring = z((B, h, dw), torch.float32)
+        self.ring = z((B, max(h, 1), dw), torch.float32)      # h = 0: window ALL keeps one running sum
         self.ring_head = z((B,), torch.int32)
         self.ring_count = z((B,), torch.int32)
         self.draft_logits = z((g, B, n, V), torch.float32)

@@ -14,7 +14,7 @@ static size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 int validate_cfg(const tabed_cfg* c) {
     if (c == nullptr) return TABED_ENULL;
-    if (c->V < 1 || c->d < 1 || c->B < 1 || c->h < 1 || c->n < 1 || c->gamma < 1) return TABED_EINVAL;
+    if (c->V < 1 || c->d < 1 || c->B < 1 || c->h < 0 || c->n < 1 || c->gamma < 1) return TABED_EINVAL;
     if (c->n > TABED_MAX_N || c->gamma > TABED_MAX_GAMMA) return TABED_ERANGE;
     if (c->w_dtype != 0 && c->w_dtype != 1) return TABED_EINVAL;
     if (c->w_dtype == 1 && (c->d % 8) != 0) return TABED_EINVAL;

@@ -58,6 +58,45 @@ __global__ __launch_bounds__(64) void k_weights(int n, int dw, int B, int gamma,
     const int b = blockIdx.x, lane = threadIdx.x;
     __shared__ double s_part[64];
     __shared__ double s_x[TABED_MAX_N];
+    if (h == 0) {
+        // Window ALL: the single slot holds the running fp32 sum of every verified position; lane j adds the
+        // nv new entries of column j in order (one fp32 addition each), then the same policies apply.
+        int count = ring_count[b];
+        count = count < 0 ? 0 : count;
+        int nv = 0;
+        if (dev != nullptr && n_valid != nullptr) {
+            nv = n_valid[b];
+            nv = nv < 0 ? 0 : (nv > gamma ? gamma : nv);
+        }
+        if (lane < dw) {
+            float sum = ring[(size_t)b * dw + lane];
+            for (int i = 0; i < nv; ++i) sum = sum + dev[((size_t)b * gamma + i) * dw + lane];
+            if (nv > 0) ring[(size_t)b * dw + lane] = sum;
+            s_x[lane] = (policy == 2) ? (double)sum : (1.0 / fmax((double)sum, eps)) / tau_w;
+        }
+        const long long total = (long long)count + nv;
+        if (lane == 0 && nv > 0) ring_count[b] = total > 0x7fffffffLL ? 0x7fffffff : (int)total;
+        __syncthreads();
+        if (lane < n) {
+            float w;
+            if (policy == 1 || total == 0) {
+                w = (float)(1.0 / (double)n);
+            } else if (policy == 2) {
+                int best = 0;
+                for (int q = 1; q < dw; ++q) if (s_x[q] < s_x[best]) best = q;
+                const double w1 = (double)best / (double)(dw - 1);
+                w = (float)(lane == 0 ? 1.0 - w1 : w1);
+            } else {
+                double xmax = -INFINITY;
+                for (int q = 0; q < n; ++q) xmax = fmax(xmax, s_x[q]);
+                double Z = 0.0;
+                for (int q = 0; q < n; ++q) Z += exp(s_x[q] - xmax);
+                w = (float)(exp(s_x[lane] - xmax) / Z);
+            }
+            weights[(size_t)b * n + lane] = w;
+        }
+        return;
+    }
     int head = ring_head[b], count = ring_count[b];
     head = ((head % h) + h) % h;
     count = count < 0 ? 0 : (count > h ? h : count);

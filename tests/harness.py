@@ -36,7 +36,7 @@ class OracleSide:
         self.o, self.wl, self.seed, self.policy, self.tau_w, self.eps = oracle, wl, seed, policy, tau_w, eps
         self.distance = distance
         B, n, g, h, V = wl.B, wl.n, wl.gamma, wl.h, wl.V
-        self.ring = np.zeros((B, h, oracle.dev_width(n, policy)), np.float32)
+        self.ring = np.zeros((B, max(h, 1), oracle.dev_width(n, policy)), np.float32)
         self.head = np.zeros(B, np.int32)
         self.count = np.zeros(B, np.int32)
         self.dev = None

@@ -86,6 +86,15 @@ def test_distance_and_policy_variants(oracle, policy, distance, n):
         assert tally.flagged_divergences <= max(2, tally.decisions // 50)
 
 
+def test_window_all(oracle):
+    """h = 0: the paper's default window (all verified positions since the start)."""
+    for policy, n in ((0, 4), (2, 2)):
+        wl = synth.scaled(SERVING, V=4100, d=64, n=n, B=6, gamma=4, h=0, cfg_id=80 + policy)
+        tally = harness.run_rounds(oracle, wl, 12, synth.make_temperature(wl, "one"), policy=policy)
+        _say(tally)
+        assert tally.flagged_divergences <= 3
+
+
 # ------------------------------------------------------------------ explicit uniforms, including the edges of [0,1)
 def test_explicit_uniform_edges(oracle):
     wl = synth.scaled(SERVING, V=3000, d=64, n=3, B=8, gamma=3, h=4, cfg_id=52)

@@ -396,3 +396,28 @@ def test_grid_policy_window_ties_and_empty_window(oracle):
         log += [dev[0, i] for i in range(nv[0])]
         c = int(np.argmin(np.sum(np.asarray(log[-3:], np.float64), axis=0)))
         np.testing.assert_allclose(w[0], [1 - c / 10, c / 10], atol=1e-7)
+
+
+def test_window_all_is_the_sum_over_every_verified_position(oracle):
+    """h = 0 (ALL, the paper's default window): same weights as a window longer than the run."""
+    rng = np.random.default_rng(41)
+    B, n, gamma = 3, 4, 5
+    ring_all = np.zeros((B, 1, n), np.float32); head_a = np.zeros(B, np.int32); cnt_a = np.zeros(B, np.int32)
+    ring_big = np.zeros((B, 4096, n), np.float32); head_b = np.zeros(B, np.int32); cnt_b = np.zeros(B, np.int32)
+    total = np.zeros((B, n))
+    for step in range(40):
+        dev = (rng.random((B, gamma, n)) * 0.5 + 0.01).astype(np.float32)
+        nv = rng.integers(1, gamma + 1, B).astype(np.int32)
+        wa = oracle.update_weights(n=n, B=B, gamma=gamma, h=0, policy=0, tau_w=1.0, eps=1e-6, dev=dev, n_valid=nv,
+                                   ring=ring_all, ring_head=head_a, ring_count=cnt_a)
+        wb = oracle.update_weights(n=n, B=B, gamma=gamma, h=4096, policy=0, tau_w=1.0, eps=1e-6, dev=dev, n_valid=nv,
+                                   ring=ring_big, ring_head=head_b, ring_count=cnt_b)
+        for b in range(B):
+            total[b] += dev[b, :nv[b]].astype(np.float64).sum(axis=0)
+        np.testing.assert_allclose(wa, wb, rtol=2e-5)
+        np.testing.assert_allclose(ring_all[:, 0], total, rtol=1e-5)
+        assert np.array_equal(cnt_a, cnt_b)
+    ring = np.zeros((1, 1, n), np.float32)
+    w = oracle.update_weights(n=n, B=1, gamma=gamma, h=0, policy=0, tau_w=1.0, eps=1e-6, dev=None, n_valid=None,
+                              ring=ring, ring_head=np.zeros(1, np.int32), ring_count=np.zeros(1, np.int32))
+    assert np.all(w == np.float32(0.25))
