@@ -469,22 +469,25 @@ hipError_t launch_sample(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
     const dim3 grid(L.C2, c.B);
     const bool vec = (c.V % 4 == 0);
     const int ti = (L.NT + kBlock - 1) / kBlock;
-    // single-pass instantiations where n*TI terms fit comfortably in registers
-    const int nc = (vec && ti <= 4 && (c.n == 1 || c.n == 2 || c.n == 4 || c.n == 8)) ? c.n : 0;
-#define TABED_LAUNCH_SAMPLE(TI_)                                                                  \
+    // single-pass instantiations: compile-time draft counts whose n*TI terms (x3 registers) fit a 512-register wave
+    const bool ncomp_ok = vec && (c.n == 1 || c.n == 2 || c.n == 4 || (c.n == 8 && ti <= 8));
+    const int nc = ncomp_ok ? c.n : 0;
+#define TABED_LAUNCH_SAMPLE_N(TI_, N_) launch(&prof, k_sample<true, TI_, N_>, grid, dim3(kBlock), 0, s, a)
+#define TABED_LAUNCH_SAMPLE(TI_, ALLOW8_)                                                         \
     do {                                                                                          \
-        if (!vec) launch(&prof, k_sample<false, TI_, 0>, grid, dim3(kBlock), 0, s, a);      \
-        else if (TI_ <= 4 && nc == 1) launch(&prof, k_sample<true, (TI_ <= 4 ? TI_ : 1), 1>, grid, dim3(kBlock), 0, s, a); \
-        else if (TI_ <= 4 && nc == 2) launch(&prof, k_sample<true, (TI_ <= 4 ? TI_ : 1), 2>, grid, dim3(kBlock), 0, s, a); \
-        else if (TI_ <= 4 && nc == 4) launch(&prof, k_sample<true, (TI_ <= 4 ? TI_ : 1), 4>, grid, dim3(kBlock), 0, s, a); \
-        else if (TI_ <= 4 && nc == 8) launch(&prof, k_sample<true, (TI_ <= 4 ? TI_ : 1), 8>, grid, dim3(kBlock), 0, s, a); \
-        else launch(&prof, k_sample<true, TI_, 0>, grid, dim3(kBlock), 0, s, a);           \
+        if (!vec) launch(&prof, k_sample<false, TI_, 0>, grid, dim3(kBlock), 0, s, a);            \
+        else if (nc == 1) TABED_LAUNCH_SAMPLE_N(TI_, 1);                                          \
+        else if (nc == 2) TABED_LAUNCH_SAMPLE_N(TI_, 2);                                          \
+        else if (nc == 4) TABED_LAUNCH_SAMPLE_N(TI_, 4);                                          \
+        else if (nc == 8 && ALLOW8_) TABED_LAUNCH_SAMPLE_N(TI_, (ALLOW8_ ? 8 : 1));               \
+        else TABED_LAUNCH_SAMPLE_N(TI_, 0);                                                       \
     } while (0)
-    if (ti <= 1) TABED_LAUNCH_SAMPLE(1);
-    else if (ti <= 4) TABED_LAUNCH_SAMPLE(4);
-    else if (ti <= 8) TABED_LAUNCH_SAMPLE(8);
-    else if (ti <= 20) TABED_LAUNCH_SAMPLE(20);
+    if (ti <= 1) TABED_LAUNCH_SAMPLE(1, true);
+    else if (ti <= 4) TABED_LAUNCH_SAMPLE(4, true);
+    else if (ti <= 8) TABED_LAUNCH_SAMPLE(8, true);
+    else if (ti <= 20) TABED_LAUNCH_SAMPLE(20, false);
     else return hipErrorInvalidValue;              // V > 163840: validate_cfg rejects it before this point
+#undef TABED_LAUNCH_SAMPLE_N
 #undef TABED_LAUNCH_SAMPLE
     return hipGetLastError();
 }

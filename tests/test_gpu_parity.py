@@ -55,6 +55,7 @@ SHAPES = [
     (4099,  1024, 4, 16, 2,    3, 1, "one"),        # n*B = 64, V % 4 != 0
     (40000,  768, 4, 16, 1,    3, 1, "one"),        # more tile groups than workgroups: persistent loop runs twice
     (33000,  768, 3, 11, 2,    3, 1, "greedy"),     # n*B = 33: second row block almost empty
+    (70004,  64,  4, 3, 2,     3, 1, "mixed07"),    # more than 2048 softmax tiles: 20 tiles per sampler thread
 ]
 
 
