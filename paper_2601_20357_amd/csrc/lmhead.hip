@@ -335,6 +335,115 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
     }
 }
 
+// ---------------------------------------------------------------- bf16, many rows (M > 64): MFMA-bound tiled GEMM
+// With hundreds of rows (stress shape: n*B = 512) the LM head is a real GEMM: 2*M*d*V flops against one
+// pass over W.  Workgroup tile 256 (rows) x 128 (vocabulary) x 64 (k), 8 waves, each wave a 64 x 64 block
+// (2 x 2 MFMA 32x32x16 tiles, W as the row operand so the accumulator is [vocabulary][row] and the cheap
+// transposed epilogue applies).  Both operands are staged through LDS in two buffers: while the MFMAs of
+// k-block i run out of one buffer, the 16-byte loads of k-block i+1 are in flight into registers and are
+// then written to the other buffer -- one barrier per k-block.  Rows padded by 16 bytes against bank
+// conflicts.  Workgroups are numbered so that the row blocks that share a vocabulary block run back to back
+// on the same XCD (workgroup w goes to XCD w % 8): W is then read from HBM once and from L2 afterwards.
+constexpr int kLBM = 256, kLBN = 128, kLBK = 64, kLRow = (kLBK + 8) * 2;   // LDS row stride in bytes (144)
+constexpr int kLargeThreads = 512;
+constexpr int kLargeStage = (kLBM + kLBN) * kLRow;                          // bytes per buffer (55296)
+
+__global__ __launch_bounds__(kLargeThreads) void k_lmhead_large(int M, int d, int V, int n, int NT, int mblocks,
+                                                                const uint16_t* __restrict__ W,
+                                                                const uint16_t* __restrict__ H,
+                                                                const float* __restrict__ temperature,
+                                                                float* __restrict__ L, float* __restrict__ pm,
+                                                                float* __restrict__ ps) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    __shared__ float s_invt[kLBM];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nn = lane & 31, half = lane >> 5;
+    // XCD-aware numbering: workgroup w runs on XCD w % 8; consecutive slots of one XCD walk the row blocks
+    // of one vocabulary block before moving to the next vocabulary block.
+    const int w = blockIdx.x, xcd = w & 7, slot = w >> 3;
+    const int mb = slot % mblocks, nb = (slot / mblocks) * 8 + xcd;
+    const int m0 = mb * kLBM, v0 = nb * kLBN;
+    if (v0 >= V) return;                                  // uniform: padding workgroups of the last XCD round
+    const int wm = wave >> 1, wn = wave & 1;              // wave block: rows m0 + 64*wm.., vocabulary v0 + 64*wn..
+    if (tid < kLBM && m0 + tid < M) s_invt[tid] = row_inv_temperature(temperature, m0 + tid, n);
+
+    // ---- global -> register staging of one k-block: 2 pieces of W and 4 of H per thread (16 bytes each)
+    u32x4 rw[2], rh[4];
+    auto fetch = [&](int kb) {
+        const int k = kb * kLBK;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int q = tid + t * kLargeThreads, row = q >> 3, c = q & 7;
+            const int v = min(v0 + row, V - 1);           // clamped rows are masked in the epilogue
+            rw[t] = *reinterpret_cast<const u32x4*>(W + (size_t)v * d + k + c * 8);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int q = tid + t * kLargeThreads, row = q >> 3, c = q & 7;
+            const int m = min(m0 + row, M - 1);
+            rh[t] = *reinterpret_cast<const u32x4*>(H + (size_t)m * d + k + c * 8);
+        }
+    };
+    auto stash = [&](int buf) {
+        unsigned char* sW = lds + buf * kLargeStage;
+        unsigned char* sH = sW + kLBN * kLRow;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int q = tid + t * kLargeThreads, row = q >> 3, c = q & 7;
+            *reinterpret_cast<u32x4*>(sW + row * kLRow + c * 16) = rw[t];
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int q = tid + t * kLargeThreads, row = q >> 3, c = q & 7;
+            *reinterpret_cast<u32x4*>(sH + row * kLRow + c * 16) = rh[t];
+        }
+    };
+
+    f32x16 acc[2][2];                                     // [vocabulary tile][row tile]
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    const int KB = d / kLBK;
+    fetch(0);
+    stash(0);
+    lds_barrier();
+    for (int kb = 0; kb < KB; ++kb) {
+        const int buf = kb & 1;
+        if (kb + 1 < KB) fetch(kb + 1);                   // in flight while this k-block is multiplied
+        const unsigned char* sW = lds + buf * kLargeStage;
+        const unsigned char* sH = sW + kLBN * kLRow;
+#pragma unroll
+        for (int ks = 0; ks < kLBK / 16; ++ks) {
+            bf16x8 wf[2], hf[2];
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+                wf[a] = *reinterpret_cast<const bf16x8*>(sW + (wn * 64 + a * 32 + nn) * kLRow + (2 * ks + half) * 16);
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+                hf[b] = *reinterpret_cast<const bf16x8*>(sH + (wm * 64 + b * 32 + nn) * kLRow + (2 * ks + half) * 16);
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[a], hf[b], acc[a][b], 0, 0, 0);
+        }
+        if (kb + 1 < KB) stash(buf ^ 1);                  // the other buffer was last read one barrier ago
+        lds_barrier();
+    }
+    // ---- epilogue: every wave turns its four 32x32 blocks through a private patch carved from buffer 0
+    unsigned char* tpatch = lds + wave * kPatchBytes;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+            store_tile_32x32_t(acc[a][b], m0 + wm * 64 + b * 32, v0 + wn * 64 + a * 32, M, V, NT, s_invt - m0, L, pm, ps,
+                               tpatch);
+}
+
 // ---------------------------------------------------------------- fp32 operands: one output per thread
 // Workgroup = 8 rows x 32 vocabulary entries; a half-wave shares one row, so the tile partials are a
 // half-wave reduction.  Only the tiny correctness configuration stores fp32 weights.
@@ -416,6 +525,19 @@ hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& Lay, char* ws, cons
                            static_cast<const float*>(W), static_cast<const float*>(H), temperature, logits, pm, ps);
     } else if (skinny_applies(c, M)) {
         launch_skinny(&prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);
+    } else if (M > 64 && c.d % kLBK == 0) {
+        static bool attr_set = false;                      // raise the dynamic-LDS limit once
+        const size_t lds = 2 * (size_t)kLargeStage;
+        if (!attr_set) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_lmhead_large),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            attr_set = true;
+        }
+        const int mblocks = (M + kLBM - 1) / kLBM, nblocks = (c.V + kLBN - 1) / kLBN;
+        const int nrounds = (nblocks + 7) / 8;             // vocabulary blocks are dealt to the 8 XCDs in rounds
+        const dim3 grid(nrounds * mblocks * 8);
+        launch(&prof, k_lmhead_large, grid, dim3(kLargeThreads), lds, s, M, c.d, c.V, c.n, Lay.NT, mblocks,
+               static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), temperature, logits, pm, ps);
     } else {
         const dim3 grid((c.V + kBN - 1) / kBN, (M + kBM - 1) / kBM);
         launch(&prof, k_lmhead_bf16, grid, dim3(kBlock), 0, s, M, c.d, c.V, c.n, Lay.NT,
