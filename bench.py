@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rounds", type=int, default=60)
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--separate-update", action="store_true",
+                    help="call tabed_update_weights at the start of every round instead of letting tabed_verify "
+                         "open the next round (window push + next weights) in its last workgroup")
     ap.add_argument("--launch", default="graph", choices=["graph", "eager"],
                     help="graph: the pool's rounds are captured once into a HIP graph (stream capture of the same "
                          "C-ABI calls) and replayed; eager: every call is issued from Python each round")
@@ -142,14 +145,17 @@ def main():
     for r in range(args.pool):
         W = Ws[r % len(Ws)]
         drafts = [buf.prepare_draft_step(0, pos, W, Hs[r][pos], temp) for pos in range(wl.gamma)]
-        slots.append((drafts, buf.prepare_verify(0, Ts[r], temp)))
+        slots.append((drafts, buf.prepare_verify(0, Ts[r], temp, fused_update=not args.separate_update)))
 
     state = {"step": 0}
 
     def step():
         s = state["step"]
         drafts, ver = slots[s % args.pool]
-        (upd_first if s == 0 else upd)()
+        if s == 0:
+            upd_first()                       # opens the first round: empty window, equal weights
+        elif args.separate_update:
+            upd()
         for c in drafts:
             c.set_round(s)
             c()
@@ -179,7 +185,7 @@ def main():
         # uniforms repeat with the pool, like the inputs do; the window state still evolves across replays.
         import ctypes as C
         side = torch.cuda.Stream()
-        every = [upd] + [c for drafts, ver in slots for c in drafts + [ver]]
+        every = [upd, upd_first] + [c for drafts, ver in slots for c in drafts + [ver]]
         for c in every:
             c.args[-1] = C.c_void_p(side.cuda_stream)
         graph = torch.cuda.CUDAGraph()
@@ -243,7 +249,8 @@ def main():
         "dtype": "bf16" if wl.w_dtype == 1 else "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: V={wl.V} d={wl.d} n={wl.n} B={wl.B} gamma={wl.gamma} h={wl.h} "
                                f"temperature={wl.temperature}", "pool_rounds": args.pool, "w_copies": args.w_copies,
-                   "calls_per_step": 2 + wl.gamma, "launch": launch},
+                   "calls_per_step": (2 if args.separate_update else 1) + wl.gamma, "launch": launch,
+                   "window_update": "separate call" if args.separate_update else "fused into tabed_verify"},
         "roofline": roofline,
         "cpu_baseline": None,
         "detail": {"kernels": kernels, "mean_tokens_per_round": emitted,

@@ -146,6 +146,10 @@ int tabed_draft_step(const tabed_cfg* cfg, void* ws, uint64_t round, int32_t pos
  *                 D(p_i, (1-c/10) q_i^(1) + (c/10) q_i^(2)) for c = 0..10 (DW = 11); meaningful for i < n_valid[b]
  *   n_valid       [B]       int32 out  min(k+1, gamma): positions whose distances enter the window
  *   flags         [B,gamma+1] uint8 out flags of the accept test at i and of the sample emitted at i
+ *   ring, ring_head, ring_count, next_weights: optional, all four or all NULL.  When given, the call also
+ *                 performs the tabed_update_weights() that would open the next round (same arguments, same
+ *                 result: the window takes the n_valid verified positions and next_weights [B,n] receives the
+ *                 weights of the next block), saving that call's launch.  next_weights may alias weights.
  * A drafted token outside [0,V) is rejected and flagged TABED_FLAG_DEGENERATE.
  */
 int tabed_verify(const tabed_cfg* cfg, void* ws, uint64_t round,
@@ -153,7 +157,8 @@ int tabed_verify(const tabed_cfg* cfg, void* ws, uint64_t round,
                  const int32_t* draft_tokens, const float* draft_q, const float* weights,
                  const float* temperature, const float* u_acc, const float* u_res,
                  int32_t* accept_len, int32_t* out_tokens, float* dev, int32_t* n_valid,
-                 uint8_t* flags, void* stream);
+                 uint8_t* flags, float* ring, int32_t* ring_head, int32_t* ring_count, float* next_weights,
+                 void* stream);
 
 /*
  * Alg. 1 lines 2-3 with the policy of App. B.2: push the distances of the

@@ -59,7 +59,7 @@ def load():
     lib.tabed_draft_step.restype = C.c_int
     lib.tabed_draft_step.argtypes = [cfgp, vp, u64, i32] + [vp] * 11
     lib.tabed_verify.restype = C.c_int
-    lib.tabed_verify.argtypes = [cfgp, vp, u64] + [vp] * 15
+    lib.tabed_verify.argtypes = [cfgp, vp, u64] + [vp] * 19
     lib.tabed_update_weights.restype = C.c_int
     lib.tabed_update_weights.argtypes = [cfgp, vp] + [vp] * 7
     lib.tabed_philox_uniforms.restype = C.c_int
@@ -159,7 +159,8 @@ def tabed_draft_step(cfg, ws, rnd, pos, W, H, weights, temperature, draft_logits
 
 
 def tabed_verify(cfg, ws, rnd, target_logits, draft_logits, draft_lse, draft_tokens, draft_q, weights, temperature,
-                 accept_len, out_tokens, dev, n_valid, flags, u_acc=None, u_res=None, stream=None):
+                 accept_len, out_tokens, dev, n_valid, flags, u_acc=None, u_res=None, ring=None, ring_head=None,
+                 ring_count=None, next_weights=None, stream=None):
     import torch
     V, n, B, g = cfg.V, cfg.n, cfg.B, cfg.gamma
     rc = load().tabed_verify(
@@ -172,7 +173,10 @@ def tabed_verify(cfg, ws, rnd, target_logits, draft_logits, draft_lse, draft_tok
         _ptr(u_acc, torch.float32, B * g, "u_acc"), _ptr(u_res, torch.float32, B, "u_res"),
         _ptr(accept_len, torch.int32, B, "accept_len"), _ptr(out_tokens, torch.int32, B * (g + 1), "out_tokens"),
         _ptr(dev, torch.float32, B * g * tabed_dev_width(cfg), "dev"), _ptr(n_valid, torch.int32, B, "n_valid"),
-        _ptr(flags, torch.uint8, B * (g + 1), "flags"), _stream(stream))
+        _ptr(flags, torch.uint8, B * (g + 1), "flags"),
+        _ptr(ring, torch.float32, B * max(cfg.h, 1) * tabed_dev_width(cfg), "ring"),
+        _ptr(ring_head, torch.int32, B, "ring_head"), _ptr(ring_count, torch.int32, B, "ring_count"),
+        _ptr(next_weights, torch.float32, B * n, "next_weights"), _stream(stream))
     _check(rc, "tabed_verify")
 
 
@@ -287,7 +291,8 @@ class RoundBuffers:
                 vp(self.draft_q.data_ptr()), vp(self.draft_flags.data_ptr()), vp(_stream(stream))]
         return PreparedCall(load().tabed_draft_step, args, "tabed_draft_step", args[2])
 
-    def prepare_verify(self, rnd, target_logits, temperature, u_acc=None, u_res=None, stream=None) -> PreparedCall:
+    def prepare_verify(self, rnd, target_logits, temperature, u_acc=None, u_res=None, stream=None,
+                       fused_update=False) -> PreparedCall:
         import torch
         c = self.cfg
         vp = C.c_void_p
@@ -298,7 +303,10 @@ class RoundBuffers:
                 vp(_ptr(temperature, torch.float32, c.B, "temperature")),
                 vp(_ptr(u_acc, torch.float32, c.B * c.gamma, "u_acc")), vp(_ptr(u_res, torch.float32, c.B, "u_res")),
                 vp(self.accept_len.data_ptr()), vp(self.out_tokens.data_ptr()), vp(self.dev.data_ptr()),
-                vp(self.n_valid.data_ptr()), vp(self.verify_flags.data_ptr()), vp(_stream(stream))]
+                vp(self.n_valid.data_ptr()), vp(self.verify_flags.data_ptr()),
+                vp(self.ring.data_ptr() if fused_update else None), vp(self.ring_head.data_ptr() if fused_update else None),
+                vp(self.ring_count.data_ptr() if fused_update else None),
+                vp(self.weights.data_ptr() if fused_update else None), vp(_stream(stream))]
         return PreparedCall(load().tabed_verify, args, "tabed_verify", args[2])
 
     def update_weights(self, first: bool, stream=None):
@@ -309,7 +317,10 @@ class RoundBuffers:
         tabed_draft_step(self.cfg, self.ws, rnd, pos, W, H, self.weights, temperature, self.draft_logits,
                          self.draft_lse, self.draft_tokens, self.draft_q, self.draft_flags, u_draft, stream)
 
-    def verify(self, rnd, target_logits, temperature, u_acc=None, u_res=None, stream=None):
+    def verify(self, rnd, target_logits, temperature, u_acc=None, u_res=None, stream=None, fused_update=False):
+        """fused_update: the call also opens the next round (window push + next weights, in place)."""
+        w = dict(ring=self.ring, ring_head=self.ring_head, ring_count=self.ring_count,
+                 next_weights=self.weights) if fused_update else {}
         tabed_verify(self.cfg, self.ws, rnd, target_logits, self.draft_logits, self.draft_lse, self.draft_tokens,
                      self.draft_q, self.weights, temperature, self.accept_len, self.out_tokens, self.dev,
-                     self.n_valid, self.verify_flags, u_acc, u_res, stream)
+                     self.n_valid, self.verify_flags, u_acc, u_res, stream=stream, **w)

@@ -149,7 +149,8 @@ int tabed_verify(const tabed_cfg* cfg, void* ws, uint64_t round, const float* ta
                  const float* draft_logits, const double* draft_lse, const int32_t* draft_tokens,
                  const float* draft_q, const float* weights, const float* temperature, const float* u_acc,
                  const float* u_res, int32_t* accept_len, int32_t* out_tokens, float* dev, int32_t* n_valid,
-                 uint8_t* flags, void* stream) {
+                 uint8_t* flags, float* ring, int32_t* ring_head, int32_t* ring_count, float* next_weights,
+                 void* stream) {
     const int rc = validate_cfg(cfg);
     if (rc != TABED_OK) return rc;
     if (!ws || !target_logits || !draft_logits || !draft_lse || !draft_tokens || !draft_q || !weights ||
@@ -157,11 +158,13 @@ int tabed_verify(const tabed_cfg* cfg, void* ws, uint64_t round, const float* ta
         return TABED_ENULL;
     if (misaligned(ws) || misaligned(target_logits) || misaligned(draft_logits) || misaligned(draft_lse))
         return TABED_EALIGN;
+    const int nwin = (ring != nullptr) + (ring_head != nullptr) + (ring_count != nullptr) + (next_weights != nullptr);
+    if (nwin != 0 && nwin != 4) return TABED_ENULL;        // the fused window update takes all four or none
     const WsLayout L = ws_layout(*cfg);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const hipError_t e = launch_verify(*cfg, L, static_cast<char*>(ws), round, target_logits, draft_logits, draft_lse,
                                        draft_tokens, draft_q, weights, temperature, u_acc, u_res, accept_len,
-                                       out_tokens, dev, n_valid, flags, s);
+                                       out_tokens, dev, n_valid, flags, ring, ring_head, ring_count, next_weights, s);
     return e == hipSuccess ? TABED_OK : fail_hip(e);
 }
 

@@ -57,7 +57,8 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
                          const float* target_logits, const float* draft_logits, const double* draft_lse,
                          const int32_t* draft_tokens, const float* draft_q, const float* weights,
                          const float* temperature, const float* u_acc, const float* u_res, int32_t* accept_len,
-                         int32_t* out_tokens, float* dev, int32_t* n_valid, uint8_t* flags, hipStream_t s);
+                         int32_t* out_tokens, float* dev, int32_t* n_valid, uint8_t* flags, float* ring,
+                         int32_t* ring_head, int32_t* ring_count, float* next_weights, hipStream_t s);
 
 hipError_t launch_weights(const tabed_cfg& c, const float* dev, const int32_t* n_valid, float* ring,
                           int32_t* ring_head, int32_t* ring_count, float* weights, hipStream_t s);

@@ -46,90 +46,85 @@ hipError_t launch_philox(const tabed_cfg& c, uint64_t round, float* out, hipStre
     return hipGetLastError();
 }
 
-// One 64-lane workgroup per sequence.  The window after pushing the nv new positions is the newest
-// min(count + nv, h) entries of (old ring entries ++ new entries); every lane loads its share of them in
-// parallel (no load depends on a store), lane j sums column j in fp64, the policy follows (softmax of 1/e
-// over the n drafts, or arg-min over the 11 candidate mixtures), and only then are the new positions stored
-// into the ring.  dw = width of one distance vector.  A few hundred scalars: latency-bound.
-__global__ __launch_bounds__(64) void k_weights(int n, int dw, int B, int gamma, int h, int policy, double tau_w,
-                                                double eps, const float* __restrict__ dev,
-                                                const int32_t* __restrict__ n_valid, float* ring,
-                                                int32_t* ring_head, int32_t* ring_count, float* weights) {
-    const int b = blockIdx.x, lane = threadIdx.x;
-    __shared__ double s_part[64];
-    __shared__ double s_x[TABED_MAX_N];
+// Window + weights for one sequence, executed by ONE wave (64 lanes).  The window after pushing the nv new
+// positions is the newest min(count + nv, h) entries of (old ring entries ++ new entries); every lane loads
+// its share of them in parallel (no load depends on a store), lane j sums column j in fp64, the policy
+// follows (softmax of 1/e over the n drafts, or arg-min over the 11 candidate mixtures), and only then are the
+// new positions stored into the ring.  h = 0 (window ALL): one running fp32 sum per column.  dw = width of
+// one distance vector.  PUB: the distances were just published by another workgroup of the same kernel and
+// must be read at device scope.  Lanes exchange through two small LDS arrays; LDS operations of one wave
+// execute in order, so no barrier is involved.  A few hundred scalars: latency-bound.
+struct WindowArgs {
+    int n, dw, gamma, h, policy;
+    double tau_w, eps;
+    float* ring;
+    int32_t* ring_head;
+    int32_t* ring_count;
+    float* weights;
+};
+
+template <bool PUB>
+__device__ __forceinline__ float dev_load(const float* p) { return PUB ? published_load(p) : *p; }
+
+template <bool PUB>
+__device__ __forceinline__ void window_update(const WindowArgs& a, int b, int lane, const float* dev, int nv,
+                                              double* s_part /* [64] */, double* s_x /* [TABED_MAX_N] */) {
+    const int n = a.n, dw = a.dw, gamma = a.gamma, h = a.h, policy = a.policy;
+    nv = (dev == nullptr) ? 0 : (nv < 0 ? 0 : (nv > gamma ? gamma : nv));
+    const float* db = dev ? dev + (size_t)b * gamma * dw : nullptr;
+    bool empty;
     if (h == 0) {
-        // Window ALL: the single slot holds the running fp32 sum of every verified position; lane j adds the
-        // nv new entries of column j in order (one fp32 addition each), then the same policies apply.
-        int count = ring_count[b];
+        int count = a.ring_count[b];
         count = count < 0 ? 0 : count;
-        int nv = 0;
-        if (dev != nullptr && n_valid != nullptr) {
-            nv = n_valid[b];
-            nv = nv < 0 ? 0 : (nv > gamma ? gamma : nv);
-        }
         if (lane < dw) {
-            float sum = ring[(size_t)b * dw + lane];
-            for (int i = 0; i < nv; ++i) sum = sum + dev[((size_t)b * gamma + i) * dw + lane];
-            if (nv > 0) ring[(size_t)b * dw + lane] = sum;
-            s_x[lane] = (policy == 2) ? (double)sum : (1.0 / fmax((double)sum, eps)) / tau_w;
+            float sum = a.ring[(size_t)b * dw + lane];
+            for (int i = 0; i < nv; ++i) sum = sum + dev_load<PUB>(db + (size_t)i * dw + lane);   // fp32, in order
+            if (nv > 0) a.ring[(size_t)b * dw + lane] = sum;
+            s_x[lane] = (policy == 2) ? (double)sum : (1.0 / fmax((double)sum, a.eps)) / a.tau_w;
         }
         const long long total = (long long)count + nv;
-        if (lane == 0 && nv > 0) ring_count[b] = total > 0x7fffffffLL ? 0x7fffffff : (int)total;
-        __syncthreads();
-        if (lane < n) {
-            float w;
-            if (policy == 1 || total == 0) {
-                w = (float)(1.0 / (double)n);
-            } else if (policy == 2) {
-                int best = 0;
-                for (int q = 1; q < dw; ++q) if (s_x[q] < s_x[best]) best = q;
-                const double w1 = (double)best / (double)(dw - 1);
-                w = (float)(lane == 0 ? 1.0 - w1 : w1);
-            } else {
-                double xmax = -INFINITY;
-                for (int q = 0; q < n; ++q) xmax = fmax(xmax, s_x[q]);
-                double Z = 0.0;
-                for (int q = 0; q < n; ++q) Z += exp(s_x[q] - xmax);
-                w = (float)(exp(s_x[lane] - xmax) / Z);
+        if (lane == 0 && nv > 0) a.ring_count[b] = total > 0x7fffffffLL ? 0x7fffffff : (int)total;
+        empty = (total == 0);
+    } else {
+        int head = a.ring_head[b], count = a.ring_count[b];
+        head = ((head % h) + h) % h;
+        count = count < 0 ? 0 : (count > h ? h : count);
+        const int new_count = (count + nv < h) ? count + nv : h;
+        float* rb = a.ring + (size_t)b * h * dw;
+        const int per = 64 / dw;                      // lanes per column (dw <= 16 => per >= 4)
+        const int j = lane % dw, t0 = lane / dw;
+        double acc = 0.0;
+        if (lane < per * dw) {
+            for (int r = t0; r < new_count; r += per) {   // r-th newest entry of the new window
+                float v;
+                if (r < nv) v = dev_load<PUB>(db + (size_t)(nv - 1 - r) * dw + j);
+                else        v = rb[(size_t)((((head - 1 - (r - nv)) % h) + h) % h) * dw + j];
+                acc += (double)v;
             }
-            weights[(size_t)b * n + lane] = w;
         }
-        return;
-    }
-    int head = ring_head[b], count = ring_count[b];
-    head = ((head % h) + h) % h;
-    count = count < 0 ? 0 : (count > h ? h : count);
-    int nv = 0;
-    if (dev != nullptr && n_valid != nullptr) {
-        nv = n_valid[b];
-        nv = nv < 0 ? 0 : (nv > gamma ? gamma : nv);
-    }
-    const int new_count = (count + nv < h) ? count + nv : h;
-    float* rb = ring + (size_t)b * h * dw;
-    const float* db = dev ? dev + (size_t)b * gamma * dw : nullptr;
-    const int per = 64 / dw;                      // lanes per column (dw <= 16 => per >= 4)
-    const int j = lane % dw, t0 = lane / dw;
-    double acc = 0.0;
-    if (lane < per * dw) {
-        for (int r = t0; r < new_count; r += per) {   // r-th newest entry of the new window
-            float v;
-            if (r < nv) v = db[(size_t)(nv - 1 - r) * dw + j];
-            else        v = rb[(size_t)((((head - 1 - (r - nv)) % h) + h) % h) * dw + j];
-            acc += (double)v;
+        s_part[lane] = acc;
+        __builtin_amdgcn_wave_barrier();
+        if (lane < dw) {
+            double e = 0.0;
+            for (int q = 0; q < per; ++q) e += s_part[q * dw + lane];
+            s_x[lane] = (policy == 2) ? e : (1.0 / fmax(e, a.eps)) / a.tau_w;
         }
+        if (nv > 0) {                                 // all window loads above are complete: store the new entries
+            for (int idx = lane; idx < nv * dw; idx += 64) {
+                const int i = idx / dw, jj = idx % dw;
+                if (i >= nv - h) rb[(size_t)((head + i) % h) * dw + jj] = dev_load<PUB>(db + (size_t)i * dw + jj);
+            }
+            if (lane == 0) {
+                a.ring_head[b] = (head + nv) % h;
+                a.ring_count[b] = new_count;
+            }
+        }
+        empty = (new_count == 0);
     }
-    s_part[lane] = acc;
-    __syncthreads();
-    if (lane < dw) {
-        double e = 0.0;
-        for (int q = 0; q < per; ++q) e += s_part[q * dw + lane];
-        s_x[lane] = (policy == 2) ? e : (1.0 / fmax(e, eps)) / tau_w;
-    }
-    __syncthreads();
+    __builtin_amdgcn_wave_barrier();
     if (lane < n) {
         float w;
-        if (policy == 1 || new_count == 0) {
+        if (policy == 1 || empty) {
             w = (float)(1.0 / (double)n);
         } else if (policy == 2) {
             int best = 0;                             // arg-min of the window sums, lowest index on ties
@@ -143,26 +138,31 @@ __global__ __launch_bounds__(64) void k_weights(int n, int dw, int B, int gamma,
             for (int q = 0; q < n; ++q) Z += exp(s_x[q] - xmax);
             w = (float)(exp(s_x[lane] - xmax) / Z);
         }
-        weights[(size_t)b * n + lane] = w;
+        a.weights[(size_t)b * n + lane] = w;
     }
-    if (nv > 0) {
-        for (int idx = lane; idx < nv * dw; idx += 64) {
-            const int i = idx / dw, jj = idx % dw;
-            if (i >= nv - h) rb[(size_t)((head + i) % h) * dw + jj] = db[(size_t)i * dw + jj];
-        }
-        if (lane == 0) {
-            ring_head[b] = (head + nv) % h;
-            ring_count[b] = new_count;
-        }
-    }
+}
+
+__global__ __launch_bounds__(64) void k_weights(WindowArgs a, const float* __restrict__ dev,
+                                                const int32_t* __restrict__ n_valid) {
+    __shared__ double s_part[64];
+    __shared__ double s_x[TABED_MAX_N];
+    const int b = blockIdx.x;
+    const int nv = (dev != nullptr && n_valid != nullptr) ? n_valid[b] : 0;
+    window_update<false>(a, b, threadIdx.x, (dev != nullptr && n_valid != nullptr) ? dev : nullptr, nv, s_part, s_x);
+}
+
+static WindowArgs window_args(const tabed_cfg& c, float* ring, int32_t* ring_head, int32_t* ring_count, float* weights) {
+    WindowArgs a;
+    a.n = c.n; a.dw = (c.policy == 2) ? TABED_GRID_CANDIDATES : c.n; a.gamma = c.gamma; a.h = c.h; a.policy = c.policy;
+    a.tau_w = (double)c.tau_w; a.eps = (double)c.eps;
+    a.ring = ring; a.ring_head = ring_head; a.ring_count = ring_count; a.weights = weights;
+    return a;
 }
 
 hipError_t launch_weights(const tabed_cfg& c, const float* dev, const int32_t* n_valid, float* ring,
                           int32_t* ring_head, int32_t* ring_count, float* weights, hipStream_t s) {
     ProfScope prof(TABED_K_WEIGHTS, s);
-    const int dw = (c.policy == 2) ? TABED_GRID_CANDIDATES : c.n;
-    launch(&prof, k_weights, dim3(c.B), dim3(64), 0, s, c.n, dw, c.B, c.gamma, c.h, c.policy,
-           (double)c.tau_w, (double)c.eps, dev, n_valid, ring, ring_head, ring_count, weights);
+    launch(&prof, k_weights, dim3(c.B), dim3(64), 0, s, window_args(c, ring, ring_head, ring_count, weights), dev, n_valid);
     return hipGetLastError();
 }
 
@@ -402,22 +402,27 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
     // ---- greedy row: arg-max (with runner-up) of the mixture over this workgroup's chunk
     Top2 best = top2_empty();
     const int cb = c * kChunkV;
+    float q[4][4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) q[u][e] = 0.f;
+    for (int j = 0; j < n; ++j) {                          // the four loads of a draft row go out together
+        float4 x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) x[u] = load4<VEC>(rows + (size_t)j * V, cb + (u * kBlock + tid) * 4, V);
+        const float cj = s_cf[j], mj = s_m[j];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) q[u][e] += cj * __expf(f4get(x[u], e) * invT - mj);
+    }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int v = cb + (u * kBlock + tid) * 4;
-        if (v >= V) continue;
-        float q[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int j = 0; j < n; ++j) {
-            const float4 x = load4<VEC>(rows + (size_t)j * V, v, V);
-            const float cj = s_cf[j], mj = s_m[j];
-            q[0] += cj * __expf(x.x * invT - mj);
-            q[1] += cj * __expf(x.y * invT - mj);
-            q[2] += cj * __expf(x.z * invT - mj);
-            q[3] += cj * __expf(x.w * invT - mj);
-        }
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            if (v + e < V) best = top2_push(best, q[e], v + e);
+            if (v + e < V) best = top2_push(best, q[u][e], v + e);
     }
     best = wave_top2(best);
     if (lane == 0) s_top[wave] = best;
@@ -784,6 +789,8 @@ struct FinishArgs {
     const double* dist;   // [B][gamma][DW][Cd] second-pass chunk sums, or nullptr (KL from the records)
     int DW, Cd;
     float dist_scale;     // 0.5 for total variation, 1 for KL
+    int fuse;             // 1: the workgroup that finishes a sequence also advances its window and weights
+    WindowArgs win;
     double* seg;          // [B][2][NSEG]
     uint32_t* tickets;
     int32_t* accept_len;
@@ -879,6 +886,7 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
     __shared__ double s_redd[kWavesPerBlock];
     __shared__ int s_last, s_first[kWavesPerBlock], s_lastw[kWavesPerBlock], s_seg;
     __shared__ double s_prefix;
+    __shared__ double s_wpart[64], s_wx[TABED_MAX_N];    // fused window update (one wave)
 
     // ---- everything that does not depend on another load is requested first
     int y = -1;
@@ -1008,7 +1016,7 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
 #pragma unroll 8
                 for (int cc = 0; cc < C3; ++cc) A += r0[(size_t)cc * RS] * s_scale[ii * C3 + cc];
                 const double kl = A / s_rowZ[ii] - s_rowlse[ii] + a.dlse[((size_t)ii * a.B + b) * n + j];
-                a.dev[((size_t)b * gamma + ii) * n + j] = (float)kl;
+                publish_store(&a.dev[((size_t)b * gamma + ii) * n + j], (float)kl);
             }
         } else {
             // ---- distances from the second pass: add the chunk sums in chunk order
@@ -1016,7 +1024,7 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
                 const double* r0 = a.dist + ((size_t)b * gamma * a.DW + q) * a.Cd;
                 double D = 0.0;
                 for (int cc = 0; cc < a.Cd; ++cc) D += r0[cc];
-                a.dev[(size_t)b * gamma * a.DW + q] = (float)((double)a.dist_scale * D);
+                publish_store(&a.dev[(size_t)b * gamma * a.DW + q], (float)((double)a.dist_scale * D));
             }
         }
         if (tid <= gamma) {
@@ -1034,7 +1042,15 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
             a.n_valid[b] = k + 1 < gamma ? k + 1 : gamma;
         }
     }
-    if (greedy) return;
+    const int nv_k = k + 1 < gamma ? k + 1 : gamma;
+    if (greedy) {
+        // a greedy row is complete here: its single workgroup also advances the window when asked to
+        if (a.fuse) {
+            __syncthreads();                               // the distances above are acknowledged
+            if (tid < kWave) window_update<true>(a.win, b, lane, a.dev, nv_k, s_wpart, s_wx);
+        }
+        return;
+    }
 
     double* segR = a.seg + ((size_t)b * 2 + 0) * NSEG;
     double* segP = a.seg + ((size_t)b * 2 + 1) * NSEG;
@@ -1073,6 +1089,7 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
             a.out_tokens[out_idx] = 0;
             a.flags[out_idx] = (uint8_t)(flag | TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE);
         }
+        if (a.fuse && tid < kWave) window_update<true>(a.win, b, lane, a.dev, nv_k, s_wpart, s_wx);
         return;
     }
     if (tid == owner) {
@@ -1120,13 +1137,16 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
         a.out_tokens[out_idx] = tok < V ? tok : V - 1;
         a.flags[out_idx] = (uint8_t)flag;
     }
+    // every workgroup of the sequence has arrived, so its distances are published: advance the window
+    if (a.fuse) window_update<true>(a.win, b, lane, a.dev, nv_k, s_wpart, s_wx);
 }
 
 hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round,
                          const float* target_logits, const float* draft_logits, const double* draft_lse,
                          const int32_t* draft_tokens, const float* draft_q, const float* weights,
                          const float* temperature, const float* u_acc, const float* u_res, int32_t* accept_len,
-                         int32_t* out_tokens, float* dev, int32_t* n_valid, uint8_t* flags, hipStream_t s) {
+                         int32_t* out_tokens, float* dev, int32_t* n_valid, uint8_t* flags, float* ring,
+                         int32_t* ring_head, int32_t* ring_count, float* next_weights, hipStream_t s) {
     const bool vec = (c.V % 4 == 0);
     const bool second_pass = (c.distance == 1 || c.policy == 2);   // distances that need lse_p before the pass
     const int ncomp = (vec && (c.n == 2 || c.n == 4 || c.n == 8)) ? c.n : 0;   // compile-time draft counts
@@ -1177,6 +1197,8 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
     a.stats = reinterpret_cast<const double*>(ws + L.off_stats);
     a.dist = second_pass ? reinterpret_cast<const double*>(ws + L.off_dist) : nullptr;
     a.DW = L.DW; a.Cd = L.Cd; a.dist_scale = (c.distance == 1) ? 0.5f : 1.f;
+    a.fuse = (ring != nullptr) ? 1 : 0;
+    a.win = window_args(c, ring, ring_head, ring_count, next_weights);
     a.seg = reinterpret_cast<double*>(ws + L.off_seg);
     a.tickets = reinterpret_cast<uint32_t*>(ws + L.off_tickets) + 2 * c.B;
     a.accept_len = accept_len; a.out_tokens = out_tokens; a.dev = dev; a.n_valid = n_valid; a.flags = flags;

@@ -66,25 +66,30 @@ class OracleSide:
 
 
 class GpuSide:
-    def __init__(self, wl, seed=0, policy=0, tau_w=1.0, eps=1e-6, distance=0):
+    def __init__(self, wl, seed=0, policy=0, tau_w=1.0, eps=1e-6, distance=0, fused=False):
         self.wl = wl
         self.cfg = cfg_of(wl, seed, policy, tau_w, eps, distance)
         self.buf = binding.RoundBuffers(self.cfg, DEV)
         self.first = True
+        self.fused = fused          # tabed_verify also opens the next round (window push + next weights)
+        self.need_update = True
 
     def round(self, rnd, W_t, H, target, temp, u_draft=None, u_acc=None, u_res=None):
         wl, buf = self.wl, self.buf
         t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV)
         temp_t, tgt_t = t(temp), t(target)
         ud, ua, ur = t(u_draft), t(u_acc), t(u_res)
-        buf.update_weights(self.first)
+        if self.need_update:
+            buf.update_weights(self.first)
         self.first = False
+        self.need_update = not self.fused
+        w_used = buf.weights.clone()
         for pos in range(wl.gamma):
             buf.draft_step(rnd, pos, W_t, to_dev_store(H[pos], wl.w_dtype), temp_t, ud)
-        buf.verify(rnd, tgt_t, temp_t, ua, ur)
+        buf.verify(rnd, tgt_t, temp_t, ua, ur, fused_update=self.fused)
         torch.cuda.synchronize()
         c = lambda x: x.cpu().numpy()
-        return dict(weights=c(buf.weights), draft_logits=c(buf.draft_logits), draft_lse=c(buf.draft_lse),
+        return dict(weights=c(w_used), draft_logits=c(buf.draft_logits), draft_lse=c(buf.draft_lse),
                     draft_tokens=c(buf.draft_tokens), draft_q=c(buf.draft_q), draft_flags=c(buf.draft_flags),
                     accept_len=c(buf.accept_len), out_tokens=c(buf.out_tokens), dev=c(buf.dev),
                     n_valid=c(buf.n_valid), flags=c(buf.verify_flags))
@@ -96,6 +101,7 @@ class GpuSide:
         self.buf.ring_count.copy_(torch.from_numpy(orc.count).to(DEV))
         self.buf.dev.copy_(torch.from_numpy(orc.dev).to(DEV))
         self.buf.n_valid.copy_(torch.from_numpy(orc.n_valid).to(DEV))
+        self.need_update = True     # fused mode: redo the push from the oracle's distances with the plain call
 
 
 class Tally:
@@ -168,11 +174,12 @@ def compare_round(g, o, wl, tally: Tally, check_logits=True):
     return lock
 
 
-def run_rounds(oracle, wl, rounds, temp, seed=0, policy=0, check_logits=True, uniforms=None, W=None, distance=0):
+def run_rounds(oracle, wl, rounds, temp, seed=0, policy=0, check_logits=True, uniforms=None, W=None, distance=0,
+               fused=False):
     """Drive both sides for `rounds` rounds with state carried over; returns the tally."""
     W = synth.make_lm_head(wl) if W is None else W
     W_t = to_dev_store(W, wl.w_dtype)
-    orc, gpu = OracleSide(oracle, wl, seed, policy, distance=distance), GpuSide(wl, seed, policy, distance=distance)
+    orc, gpu = OracleSide(oracle, wl, seed, policy, distance=distance), GpuSide(wl, seed, policy, distance=distance, fused=fused)
     tally = Tally()
     for rnd in range(rounds):
         H, target = synth.make_round(wl, W, rnd)

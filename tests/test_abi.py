@@ -72,8 +72,11 @@ def test_error_codes_are_returned_before_any_launch(lib):
     # NULL pointers
     rc = lib.tabed_draft_step(C.byref(cfg), None, 0, 0, *([fake] * 10), None)
     assert rc == -1
-    rc = lib.tabed_verify(C.byref(cfg), fake, 0, None, *([fake] * 14), None)
+    rc = lib.tabed_verify(C.byref(cfg), fake, 0, None, *([fake] * 14), None, None, None, None, None)
     assert rc == -1
+    ok15 = [fake] * 7 + [None, None] + [fake] * 5           # u_acc / u_res may be NULL
+    rc = lib.tabed_verify(C.byref(cfg), fake, 0, fake, *ok15[1:], fake, None, None, None, None)
+    assert rc == -1                     # fused window update: all four pointers or none
     rc = lib.tabed_update_weights(C.byref(cfg), fake, fake, None, fake, fake, fake, fake, None)
     assert rc == -1                     # dev without n_valid
     # position outside the block
@@ -86,7 +89,7 @@ def test_error_codes_are_returned_before_any_launch(lib):
     # invalid / unsupported configuration
     assert lib.tabed_draft_step(C.byref(good_cfg(n=99)), fake, 0, 0, *([fake] * 10), None) == -3
     assert lib.tabed_draft_step(C.byref(good_cfg(V=-4)), fake, 0, 0, *([fake] * 10), None) == -2
-    assert lib.tabed_verify(C.byref(good_cfg(policy=2)), fake, 0, *([fake] * 15), None) == -2   # needs n = 2
+    assert lib.tabed_verify(C.byref(good_cfg(policy=2)), fake, 0, *([fake] * 15), None, None, None, None, None) == -2   # needs n = 2
     assert lib.tabed_workspace_init(C.byref(cfg), None, None) == -1
     for code in (0, -1, -2, -3, -4, -5, -6):
         assert lib.tabed_strerror(code).decode() not in ("", "unknown error code")

@@ -90,6 +90,20 @@ def test_distance_and_policy_variants(oracle, policy, distance, n):
         assert tally.flagged_divergences <= max(2, tally.decisions // 50)
 
 
+@pytest.mark.parametrize("policy,distance,n,h,mode", [(0, 0, 4, 8, "one"), (0, 0, 3, 5, "mixed07"), (2, 1, 2, 0, "one"),
+                                                        (0, 0, 4, 0, "greedy")],
+                         ids=["softmax", "mixed-rows", "grid-tvd-all", "greedy-all"])
+def test_verify_with_fused_window_update(oracle, policy, distance, n, h, mode):
+    """tabed_verify given the window pointers must leave the same window and next weights as the separate
+    tabed_update_weights call the oracle models."""
+    for V, d, B in ((4100, 64, 5), (32000, 768, 16)):
+        wl = synth.scaled(SERVING, V=V, d=d, n=n, B=B, gamma=4, h=h, cfg_id=90 + policy + distance)
+        tally = harness.run_rounds(oracle, wl, 8, synth.make_temperature(wl, mode), policy=policy, distance=distance,
+                                   fused=True)
+        _say(tally)
+        assert tally.flagged_divergences <= max(2, tally.decisions // 50)
+
+
 def test_window_all(oracle):
     """h = 0: the paper's default window (all verified positions since the start)."""
     for policy, n in ((0, 4), (2, 2)):
