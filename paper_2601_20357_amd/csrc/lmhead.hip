@@ -6,6 +6,8 @@
 // correctness configuration) use plain FMAs.
 #include <hip/hip_bf16.h>
 
+#include <type_traits>
+
 #include "device_utils.h"
 #include "internal.h"
 
@@ -344,9 +346,12 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
 // then written to the other buffer -- one barrier per k-block.  Rows padded by 16 bytes against bank
 // conflicts.  Workgroups are numbered so that the row blocks that share a vocabulary block run back to back
 // on the same XCD (workgroup w goes to XCD w % 8): W is then read from HBM once and from L2 afterwards.
-constexpr int kLBM = 256, kLBN = 128, kLBK = 64, kLRow = (kLBK + 8) * 2;   // LDS row stride in bytes (144)
+constexpr int kLBM = 256, kLBN = 256, kLBK = 32, kLRow = (kLBK + 8) * 2;   // LDS row stride in bytes (80)
+constexpr int kLCh = kLBK / 8;                                              // 16-byte chunks per row of a k-block
 constexpr int kLargeThreads = 512;
-constexpr int kLargeStage = (kLBM + kLBN) * kLRow;                          // bytes per buffer (55296)
+constexpr int kLargeStage = (kLBM + kLBN) * kLRow;                          // bytes per buffer (40960)
+static_assert(kLBN * kLCh % kLargeThreads == 0 && kLBM * kLCh % kLargeThreads == 0, "staging split");
+constexpr int kLWPieces = kLBN * kLCh / kLargeThreads, kLHPieces = kLBM * kLCh / kLargeThreads;
 
 __global__ __launch_bounds__(kLargeThreads) void k_lmhead_large(int M, int d, int V, int n, int NT, int mblocks,
                                                                 const uint16_t* __restrict__ W,
@@ -364,74 +369,97 @@ __global__ __launch_bounds__(kLargeThreads) void k_lmhead_large(int M, int d, in
     const int mb = slot % mblocks, nb = (slot / mblocks) * 8 + xcd;
     const int m0 = mb * kLBM, v0 = nb * kLBN;
     if (v0 >= V) return;                                  // uniform: padding workgroups of the last XCD round
-    const int wm = wave >> 1, wn = wave & 1;              // wave block: rows m0 + 64*wm.., vocabulary v0 + 64*wn..
+    const int wm = wave >> 2, wn = wave & 3;              // wave block: rows m0 + 128*wm.., vocabulary v0 + 64*wn..
     if (tid < kLBM && m0 + tid < M) s_invt[tid] = row_inv_temperature(temperature, m0 + tid, n);
 
-    // ---- global -> register staging of one k-block: 2 pieces of W and 4 of H per thread (16 bytes each)
-    u32x4 rw[2], rh[4];
-    auto fetch = [&](int kb) {
+    // ---- global -> register staging: two register sets, so that the loads of k-block kb+2 and kb+3 are in
+    //      flight while k-block kb is multiplied (one k-block is only ~1000 cycles of MFMA work per SIMD,
+    //      less than an L2 round trip).  kLWPieces of W and kLHPieces of H per thread and set (16 bytes each).
+    u32x4 rw[2][kLWPieces], rh[2][kLHPieces];
+    auto fetch = [&](int kb, auto set_c) {
+        constexpr int S = decltype(set_c)::value;
         const int k = kb * kLBK;
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int q = tid + t * kLargeThreads, row = q >> 3, c = q & 7;
+        for (int t = 0; t < kLWPieces; ++t) {
+            const int q = tid + t * kLargeThreads, row = q / kLCh, c = q % kLCh;
             const int v = min(v0 + row, V - 1);           // clamped rows are masked in the epilogue
-            rw[t] = *reinterpret_cast<const u32x4*>(W + (size_t)v * d + k + c * 8);
+            rw[S][t] = *reinterpret_cast<const u32x4*>(W + (size_t)v * d + k + c * 8);
         }
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int q = tid + t * kLargeThreads, row = q >> 3, c = q & 7;
+        for (int t = 0; t < kLHPieces; ++t) {
+            const int q = tid + t * kLargeThreads, row = q / kLCh, c = q % kLCh;
             const int m = min(m0 + row, M - 1);
-            rh[t] = *reinterpret_cast<const u32x4*>(H + (size_t)m * d + k + c * 8);
+            rh[S][t] = *reinterpret_cast<const u32x4*>(H + (size_t)m * d + k + c * 8);
         }
     };
-    auto stash = [&](int buf) {
+    auto stash = [&](int buf, auto set_c) {
+        constexpr int S = decltype(set_c)::value;
         unsigned char* sW = lds + buf * kLargeStage;
         unsigned char* sH = sW + kLBN * kLRow;
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int q = tid + t * kLargeThreads, row = q >> 3, c = q & 7;
-            *reinterpret_cast<u32x4*>(sW + row * kLRow + c * 16) = rw[t];
+        for (int t = 0; t < kLWPieces; ++t) {
+            const int q = tid + t * kLargeThreads, row = q / kLCh, c = q % kLCh;
+            *reinterpret_cast<u32x4*>(sW + row * kLRow + c * 16) = rw[S][t];
         }
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int q = tid + t * kLargeThreads, row = q >> 3, c = q & 7;
-            *reinterpret_cast<u32x4*>(sH + row * kLRow + c * 16) = rh[t];
+        for (int t = 0; t < kLHPieces; ++t) {
+            const int q = tid + t * kLargeThreads, row = q / kLCh, c = q % kLCh;
+            *reinterpret_cast<u32x4*>(sH + row * kLRow + c * 16) = rh[S][t];
         }
     };
+    using Set0 = std::integral_constant<int, 0>;
+    using Set1 = std::integral_constant<int, 1>;
 
-    f32x16 acc[2][2];                                     // [vocabulary tile][row tile]
+    f32x16 acc[2][4];                                     // [vocabulary tile][row tile]
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    const int KB = d / kLBK;
-    fetch(0);
-    stash(0);
-    lds_barrier();
-    for (int kb = 0; kb < KB; ++kb) {
-        const int buf = kb & 1;
-        if (kb + 1 < KB) fetch(kb + 1);                   // in flight while this k-block is multiplied
+    auto multiply = [&](int buf) {
         const unsigned char* sW = lds + buf * kLargeStage;
         const unsigned char* sH = sW + kLBN * kLRow;
+        // operand fragments of k-step ks+1 are read from LDS while the MFMAs of k-step ks run
+        bf16x8 wf[2][2], hf[2][4];
+        auto read_frags = [&](int ks, int set) {
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+                wf[set][a] = *reinterpret_cast<const bf16x8*>(sW + (wn * 64 + a * 32 + nn) * kLRow + (2 * ks + half) * 16);
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                hf[set][b] = *reinterpret_cast<const bf16x8*>(sH + (wm * 128 + b * 32 + nn) * kLRow + (2 * ks + half) * 16);
+        };
+        read_frags(0, 0);
 #pragma unroll
         for (int ks = 0; ks < kLBK / 16; ++ks) {
-            bf16x8 wf[2], hf[2];
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-                wf[a] = *reinterpret_cast<const bf16x8*>(sW + (wn * 64 + a * 32 + nn) * kLRow + (2 * ks + half) * 16);
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-                hf[b] = *reinterpret_cast<const bf16x8*>(sH + (wm * 64 + b * 32 + nn) * kLRow + (2 * ks + half) * 16);
+            if (ks + 1 < kLBK / 16) read_frags(ks + 1, (ks + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);            // keep the reads ahead of the MFMAs they overlap with
 #pragma unroll
             for (int a = 0; a < 2; ++a)
 #pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[a], hf[b], acc[a][b], 0, 0, 0);
+                for (int b = 0; b < 4; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks & 1][a], hf[ks & 1][b], acc[a][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (kb + 1 < KB) stash(buf ^ 1);                  // the other buffer was last read one barrier ago
+    };
+
+    // k-block j lives in register set j & 1 until it is written to LDS buffer j & 1.  KB is even (d % 64 == 0).
+    const int KB = d / kLBK;
+    fetch(0, Set0{});
+    stash(0, Set0{});
+    fetch(1, Set1{});
+    if (2 < KB) fetch(2, Set0{});
+    lds_barrier();
+    for (int kb = 0; kb < KB; kb += 2) {
+        multiply(0);                                      // k-block kb
+        if (kb + 1 < KB) stash(1, Set1{});                // k-block kb+1 (requested two iterations ago)
+        if (kb + 3 < KB) fetch(kb + 3, Set1{});
+        lds_barrier();
+        if (kb + 1 < KB) multiply(1);                     // k-block kb+1
+        if (kb + 2 < KB) stash(0, Set0{});                // k-block kb+2
+        if (kb + 4 < KB) fetch(kb + 4, Set0{});
         lds_barrier();
     }
     // ---- epilogue: every wave turns its four 32x32 blocks through a private patch carved from buffer 0
@@ -439,8 +467,8 @@ __global__ __launch_bounds__(kLargeThreads) void k_lmhead_large(int M, int d, in
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
-            store_tile_32x32_t(acc[a][b], m0 + wm * 64 + b * 32, v0 + wn * 64 + a * 32, M, V, NT, s_invt - m0, L, pm, ps,
+        for (int b = 0; b < 4; ++b)
+            store_tile_32x32_t(acc[a][b], m0 + wm * 128 + b * 32, v0 + wn * 64 + a * 32, M, V, NT, s_invt - m0, L, pm, ps,
                                tpatch);
 }
 
@@ -525,7 +553,7 @@ hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& Lay, char* ws, cons
                            static_cast<const float*>(W), static_cast<const float*>(H), temperature, logits, pm, ps);
     } else if (skinny_applies(c, M)) {
         launch_skinny(&prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);
-    } else if (M > 64 && c.d % kLBK == 0) {
+    } else if (M > 64 && c.d % 64 == 0) {
         static bool attr_set = false;                      // raise the dynamic-LDS limit once
         const size_t lds = 2 * (size_t)kLargeStage;
         if (!attr_set) {
