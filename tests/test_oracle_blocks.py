@@ -211,7 +211,10 @@ def test_uniforms_are_uniform_exact_and_keyed_by_seed_round_b_pos(oracle):
     us = np.array([[oracle.uniform(0, r, b, p, w) for w in (0, 1)]
                    for r in range(40) for b in range(16) for p in range(6)])
     assert us.min() >= 0.0 and us.max() < 1.0
-    assert np.all(us * 2 ** 24 == np.round(us * 2 ** 24))        # multiples of 2^-24
+    assert np.all(us * 2 ** 24 == np.round(us * 2 ** 24))        # multiples of 2^-24 ...
+    odd = np.mean((us * 2 ** 24).astype(np.int64) % 2 == 1)
+    assert 0.45 < odd < 0.55                                     # ... and all 24 bits are used
+    assert us.max() > 1 - 2.0 ** -9 or len(us) < 1000            # the top of [0,1) is reachable
     assert st.kstest(us[:, 0], "uniform").pvalue > 1e-3
     assert st.kstest(us[:, 1], "uniform").pvalue > 1e-3
     assert abs(np.corrcoef(us[:, 0], us[:, 1])[0, 1]) < 0.05
