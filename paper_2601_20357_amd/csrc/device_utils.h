@@ -84,14 +84,23 @@ __device__ __forceinline__ double block_sum(double v, double* lds4) {
     return r;
 }
 
-// Inclusive prefix sum across the 64 lanes of a wave (Hillis-Steele, fixed order).
+// Inclusive prefix sum across the 64 lanes of a wave, fixed order, no LDS traffic: Hillis-Steele inside each
+// 16-lane row with row_shr (lanes shifted in from outside the row read 0), then the total of row 0 goes to
+// row 1 and that of row 2 to row 3 (row_bcast:15), then the total of rows 0-1 goes to rows 2-3 (row_bcast:31).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_f64_zero(double v) {
+    const long long b = __builtin_bit_cast(long long, v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)b, CTRL, ROW_MASK, 0xF, true);
+    const unsigned hi = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)(b >> 32), CTRL, ROW_MASK, 0xF, true);
+    return __builtin_bit_cast(double, (long long)(((unsigned long long)hi << 32) | lo));
+}
 __device__ __forceinline__ double wave_inclusive_scan(double v) {
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        double up = __shfl_up(v, o);
-        if (lane >= o) v += up;
-    }
+    v += dpp_f64_zero<0x111, 0xF>(v);    // row_shr:1
+    v += dpp_f64_zero<0x112, 0xF>(v);    // row_shr:2
+    v += dpp_f64_zero<0x114, 0xF>(v);    // row_shr:4
+    v += dpp_f64_zero<0x118, 0xF>(v);    // row_shr:8
+    v += dpp_f64_zero<0x142, 0xA>(v);    // row_bcast:15 into rows 1 and 3
+    v += dpp_f64_zero<0x143, 0xC>(v);    // row_bcast:31 into rows 2 and 3
     return v;
 }
 

@@ -255,7 +255,7 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
                 uu[j][i] = (psv[j][i] > 0.f) ? psv[j][i] * __expf(pmv[j][i] - M) : 0.f;
                 sl += uu[j][i];
             }
-            const double S = wave_sum((double)sl);
+            const double S = (double)wave_sum(sl);         // 64 x TI terms in fp32, fp64 across the four waves
             if (lane == 0) s_wsum[wave][j] = S;
         }
         __syncthreads();
