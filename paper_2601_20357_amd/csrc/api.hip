@@ -32,6 +32,7 @@ WsLayout ws_layout(const tabed_cfg& c) {
     L.M = c.n * c.B;
     L.NT = (c.V + kTileV - 1) / kTileV;
     L.C2 = (c.V + kChunkV - 1) / kChunkV;
+    if (L.C2 > kMaxGreedyChunks) L.C2 = kMaxGreedyChunks;
     L.C3max = (c.V + kBlock * 4 - 1) / (kBlock * 4);
     L.NSEG = (c.V + kSegV - 1) / kSegV;
     L.C5 = (c.V + kResidChunkV - 1) / kResidChunkV;

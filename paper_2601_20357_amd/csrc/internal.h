@@ -15,6 +15,7 @@ constexpr int kWavesPerBlock = kBlock / kWave;
 constexpr int kTileV = 32;      // width of one softmax-partial tile written by the LM-head epilogue
 constexpr int kSegV = 256;      // width of one CDF segment of the corrected/bonus sampler (one wave x float4)
 constexpr int kChunkV = 4096;   // vocabulary span of one workgroup in the greedy arg-max pass (256 threads x 4 float4)
+constexpr int kMaxGreedyChunks = 8;  // workgroups per greedy row in the draft arg-max pass
 constexpr int kResidChunkV = 2048;  // vocabulary span of one workgroup in the corrected/bonus sampler (2 segments per wave)
 constexpr int kStatHdr = 4;     // doubles before the per-draft sums in a chunk record: max, Z, argmax value, argmax index
 

@@ -400,29 +400,32 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
     }
 
     // ---- greedy row: arg-max (with runner-up) of the mixture over this workgroup's chunk
+    // (at most kMaxGreedyChunks workgroups per row: every one of them repeats the log-sum-exp pass over the
+    // row's partials, so a large vocabulary is walked in several 4096-wide strides per workgroup instead)
     Top2 best = top2_empty();
-    const int cb = c * kChunkV;
-    float q[4][4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) q[u][e] = 0.f;
-    for (int j = 0; j < n; ++j) {                          // the four loads of a draft row go out together
-        float4 x[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) x[u] = load4<VEC>(rows + (size_t)j * V, cb + (u * kBlock + tid) * 4, V);
-        const float cj = s_cf[j], mj = s_m[j];
+    for (int cb = c * kChunkV; cb < V; cb += a.C2 * kChunkV) {
+        float q[4][4];
 #pragma unroll
         for (int u = 0; u < 4; ++u)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) q[u][e] += cj * __expf(f4get(x[u], e) * invT - mj);
-    }
+            for (int e = 0; e < 4; ++e) q[u][e] = 0.f;
+        for (int j = 0; j < n; ++j) {                      // the four loads of a draft row go out together
+            float4 x[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int v = cb + (u * kBlock + tid) * 4;
+            for (int u = 0; u < 4; ++u) x[u] = load4<VEC>(rows + (size_t)j * V, cb + (u * kBlock + tid) * 4, V);
+            const float cj = s_cf[j], mj = s_m[j];
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (v + e < V) best = top2_push(best, q[u][e], v + e);
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) q[u][e] += cj * __expf(f4get(x[u], e) * invT - mj);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int v = cb + (u * kBlock + tid) * 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (v + e < V) best = top2_push(best, q[u][e], v + e);
+        }
     }
     best = wave_top2(best);
     if (lane == 0) s_top[wave] = best;
