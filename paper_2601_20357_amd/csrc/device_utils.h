@@ -117,6 +117,35 @@ __device__ __forceinline__ double block_exclusive_scan(double v, double* lds4, d
     return base + inc - v;
 }
 
+__device__ __forceinline__ int wave_min_i32(int v) {
+    v = min(v, dpp_i32<kDppXor1>(v));
+    v = min(v, dpp_i32<kDppXor2>(v));
+    v = min(v, dpp_i32<kDppHalfMirror>(v));
+    v = min(v, dpp_i32<kDppMirror>(v));
+    return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+}
+__device__ __forceinline__ int wave_max_i32(int v) {
+    v = max(v, dpp_i32<kDppXor1>(v));
+    v = max(v, dpp_i32<kDppXor2>(v));
+    v = max(v, dpp_i32<kDppHalfMirror>(v));
+    v = max(v, dpp_i32<kDppMirror>(v));
+    return max(max(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               max(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+}
+// Smallest `first_key` over the workgroup (keys order the candidates along the prefix); if no thread offers
+// one (first_key = INT_MAX everywhere), the largest `last_key`; -1 if there is none either.
+__device__ __forceinline__ int block_pick_key(int first_key, int last_key, int* lds_first4, int* lds_last4) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int f = wave_min_i32(first_key), l = wave_max_i32(last_key);
+    if (lane == 0) { lds_first4[w] = f; lds_last4[w] = l; }
+    __syncthreads();
+    const int first = min(min(lds_first4[0], lds_first4[1]), min(lds_first4[2], lds_first4[3]));
+    const int last = max(max(lds_last4[0], lds_last4[1]), max(lds_last4[2], lds_last4[3]));
+    __syncthreads();
+    return first != 0x7fffffff ? first : last;
+}
+
 // Which thread's run of the prefix contains `target`?  Every thread passes the exclusive prefix and the
 // sum of its run (block_exclusive_scan order).  Returns the lowest thread whose inclusive prefix exceeds
 // target; if rounding lets none exceed it, the highest thread with a non-empty run; -1 if all runs are

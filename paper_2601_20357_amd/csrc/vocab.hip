@@ -218,6 +218,7 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
     __shared__ double s_term[TABED_MAX_N][kTileV];
     __shared__ float s_wm[kWavesPerBlock][TABED_MAX_N];
     __shared__ double s_wsum[kWavesPerBlock][TABED_MAX_N];
+    __shared__ double s_wtot[kWavesPerBlock][5];        // wave totals of the tile-mass scan, per chunk row
 
     const float* pmb = a.pm + (size_t)b * n * NT;      // partials of this sequence: [n][NT]
     const float* psb = a.ps + (size_t)b * n * NT;
@@ -225,18 +226,41 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
     const float wj = (tid < n) ? a.weights[(size_t)b * n + tid] : 0.f;
     const float u = a.u_draft ? a.u_draft[out_idx] : tabed_uniform(a.seed, a.round, (uint32_t)b, (uint32_t)a.pos, 0);
 
+    // Which tiles a thread owns.  Few tiles per thread: the contiguous run [tid*TI, tid*TI + TI).  Many
+    // (single-pass kernels of large vocabularies): TI/4 chunks of 4 consecutive tiles, chunk q*256 + tid for
+    // q < TI/4 -- then every 16-byte load of a wave is one contiguous kilobyte.
+    constexpr bool CHUNKED = (N > 0 && TI > 4);
+    constexpr int TPC = CHUNKED ? 4 : TI;              // tiles per chunk
+    constexpr int Q = TI / TPC;                        // chunks per thread
+    auto tile_of = [&](int i) { return CHUNKED ? ((i / 4) * kBlock + tid) * 4 + (i & 3) : tid * TI + i; };
+
     float uu[(N > 0) ? N : 1][TI];                     // single pass: terms of this thread's tiles, all drafts
     if (N > 0) {
-        // ---- single pass over the partials: thread tid owns tiles [tid*TI, tid*TI + TI) of every draft
+        // ---- single pass over the partials of every draft
         float pmv[(N > 0) ? N : 1][TI], psv[(N > 0) ? N : 1][TI];
 #pragma unroll
-        for (int j = 0; j < N; ++j)
+        for (int j = 0; j < N; ++j) {
+            if (CHUNKED && (NT & 3) == 0) {
 #pragma unroll
-            for (int i = 0; i < TI; ++i) {
-                const int t = tid * TI + i;
-                pmv[j][i] = t < NT ? pmb[(size_t)j * NT + t] : -INFINITY;
-                psv[j][i] = t < NT ? psb[(size_t)j * NT + t] : 0.f;
+                for (int q = 0; q < Q; ++q) {
+                    const int t = tile_of(4 * q);
+                    float4 m4 = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY), s4 = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (t < NT) {
+                        m4 = *reinterpret_cast<const float4*>(pmb + (size_t)j * NT + t);
+                        s4 = *reinterpret_cast<const float4*>(psb + (size_t)j * NT + t);
+                    }
+                    pmv[j][4 * q] = m4.x; pmv[j][4 * q + 1] = m4.y; pmv[j][4 * q + 2] = m4.z; pmv[j][4 * q + 3] = m4.w;
+                    psv[j][4 * q] = s4.x; psv[j][4 * q + 1] = s4.y; psv[j][4 * q + 2] = s4.z; psv[j][4 * q + 3] = s4.w;
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < TI; ++i) {
+                    const int t = tile_of(i);
+                    pmv[j][i] = t < NT ? pmb[(size_t)j * NT + t] : -INFINITY;
+                    psv[j][i] = t < NT ? psb[(size_t)j * NT + t] : 0.f;
+                }
             }
+        }
 #pragma unroll
         for (int j = 0; j < N; ++j) {
             float ml = -INFINITY;
@@ -324,7 +348,7 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
                 float pmv[TI], psv[TI];
 #pragma unroll
                 for (int i = 0; i < TI; ++i) {
-                    const int t = tid * TI + i;
+                    const int t = tile_of(i);
                     pmv[i] = t < NT ? pmb[(size_t)j * NT + t] : -INFINITY;
                     psv[i] = t < NT ? psb[(size_t)j * NT + t] : 0.f;
                 }
@@ -336,14 +360,37 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
                     if (psv[i] > 0.f) mt[i] += cj * (double)(psv[i] * __expf(pmv[i] - mj));
             }
         }
-        double run = 0.0;
+        // ---- prefix over the tile masses in tile order.  Chunk q of thread tid has key q*256 + tid; keys
+        //      order the chunks along the vocabulary.  One wave scan per chunk row, one barrier.
+        double cs[Q], cinc[Q];
 #pragma unroll
-        for (int i = 0; i < TI; ++i) run += mt[i];
-        double Zscan;
-        const double excl = block_exclusive_scan(run, s_redd, &Zscan);
+        for (int q = 0; q < Q; ++q) {
+            cs[q] = 0.0;
+#pragma unroll
+            for (int e = 0; e < TPC; ++e) cs[q] += mt[q * TPC + e];
+            cinc[q] = wave_inclusive_scan(cs[q]);
+            if (lane == 63) s_wtot[wave][q] = cinc[q];
+        }
+        __syncthreads();
         const double target = (double)u * Z;
-        const int owner = block_find_owner(excl, run, target, s_first, s_lastw);   // -1 only if every mass is zero
-        if (owner < 0) {
+        double excl[Q];
+        int first_key = 0x7fffffff, last_key = -1;
+        {
+            double rowbase = 0.0;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                double before = rowbase;
+                for (int w = 0; w < wave; ++w) before += s_wtot[w][q];
+                excl[q] = before + (cinc[q] - cs[q]);
+                if (cs[q] > 0.0) {
+                    if (first_key == 0x7fffffff && excl[q] + cs[q] > target) first_key = q * kBlock + tid;
+                    last_key = q * kBlock + tid;
+                }
+                rowbase += ((s_wtot[0][q] + s_wtot[1][q]) + s_wtot[2][q]) + s_wtot[3][q];
+            }
+        }
+        const int key = block_pick_key(first_key, last_key, s_first, s_lastw);   // -1 only if every mass is zero
+        if (key < 0) {
             if (tid == 0) {
                 a.draft_tokens[out_idx] = 0;
                 a.draft_q[out_idx] = 0.f;
@@ -351,19 +398,27 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
             }
             return;
         }
-        if (tid == owner) {
-            double P = excl, Plast = excl;
+        if (tid == (key & (kBlock - 1))) {
+            const int qs = key / kBlock;
+            double P = 0.0, Plast = 0.0;
             int istar = -1, ilast = 0;
 #pragma unroll
-            for (int i = 0; i < TI; ++i) {
-                if (istar < 0) {
-                    if (mt[i] > 0.0) { ilast = i; Plast = P; }
-                    if (P + mt[i] > target) istar = i;
-                    else P += mt[i];
+            for (int q = 0; q < Q; ++q) {
+                if (q == qs) {
+                    P = excl[q]; Plast = P; ilast = q * TPC;
+#pragma unroll
+                    for (int e = 0; e < TPC; ++e) {
+                        const int i = q * TPC + e;
+                        if (istar < 0) {
+                            if (mt[i] > 0.0) { ilast = i; Plast = P; }
+                            if (P + mt[i] > target) istar = i;
+                            else P += mt[i];
+                        }
+                    }
                 }
             }
             if (istar < 0) { istar = ilast; P = Plast; }
-            s_tile = tid * TI + istar;
+            s_tile = tile_of(istar);
             s_prefix = P;
         }
         __syncthreads();
