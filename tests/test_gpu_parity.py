@@ -213,3 +213,23 @@ def test_llava_full_size_greedy_and_sampling(oracle):
         tally = harness.run_rounds(oracle, wl, 4, synth.make_temperature(wl, mode))
         _say(tally)
         assert tally.flagged_divergences <= 2
+
+
+def test_lvlm_full_size(oracle):
+    """V=152064, d=896, n=4, B=8, gamma=7, h=16 with the matching draft switching (BASELINE workload 4)."""
+    wl = synth.WORKLOADS["lvlm"]
+    _say("lvlm full size")
+    tally = harness.run_rounds(oracle, wl, 2, synth.make_temperature(wl))
+    _say(tally)
+    assert tally.flagged_divergences <= 3
+
+
+def test_stress_shape_fewer_sequences(oracle):
+    """The stress vocabulary, hidden size, draft count and temperature mix (V=128256, d=2048, n=8, greedy and
+    T=0.7 rows, heavy-tailed target noise) on 12 sequences and 2 positions: 96 rows through the many-rows LM head.
+    The full 64-sequence shape differs only in the number of row blocks and is too slow for the oracle here."""
+    wl = synth.scaled(synth.WORKLOADS["stress"], B=12, gamma=2, cfg_id=95)
+    _say("stress shape, 12 sequences")
+    tally = harness.run_rounds(oracle, wl, 2, synth.make_temperature(wl))
+    _say(tally)
+    assert tally.flagged_divergences <= 3
