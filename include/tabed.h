@@ -71,7 +71,7 @@ extern "C" {
 #define TABED_FLAG_DEGENERATE 4u    /* empty residual, CDF never crossed, or token out of range */
 
 typedef struct tabed_cfg {
-    int32_t V;        /* vocabulary size, >= 1                                             */
+    int32_t V;        /* vocabulary size, 1..262144                                        */
     int32_t d;        /* draft hidden size, >= 1 (multiple of 8 when w_dtype = 1)          */
     int32_t n;        /* drafting methods batched through the draft model, 1..TABED_MAX_N  */
     int32_t B;        /* independent sequences, >= 1                                       */

@@ -23,7 +23,7 @@ int validate_cfg(const tabed_cfg* c) {
     if (c->policy == 2 && c->n != 2) return TABED_EINVAL;
     if (!(c->tau_w > 0.f) || !(c->eps > 0.f)) return TABED_EINVAL;
     if ((long long)c->B * c->n > (1ll << 24)) return TABED_ERANGE;
-    if (c->V > kTileV * kBlock * 20) return TABED_ERANGE;      // 163840: largest vocabulary the sampler tiles
+    if (c->V > kTileV * kBlock * 32) return TABED_ERANGE;      // 262144: largest vocabulary the sampler tiles
     return TABED_OK;
 }
 

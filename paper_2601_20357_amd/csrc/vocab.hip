@@ -533,7 +533,7 @@ hipError_t launch_sample(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
     const bool vec = (c.V % 4 == 0);
     const int ti = (L.NT + kBlock - 1) / kBlock;
     // single-pass instantiations: compile-time draft counts whose n*TI terms (x3 registers) fit a 512-register wave
-    const bool ncomp_ok = vec && (c.n == 1 || c.n == 2 || c.n == 4 || (c.n == 8 && ti <= 8));
+    const bool ncomp_ok = vec && ti <= 20 && (c.n == 1 || c.n == 2 || c.n == 4 || (c.n == 8 && ti <= 8));
     const int nc = ncomp_ok ? c.n : 0;
 #define TABED_LAUNCH_SAMPLE_N(TI_, N_) launch(&prof, k_sample<true, TI_, N_>, grid, dim3(kBlock), 0, s, a)
 #define TABED_LAUNCH_SAMPLE(TI_, ALLOW8_)                                                         \
@@ -549,7 +549,8 @@ hipError_t launch_sample(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
     else if (ti <= 4) TABED_LAUNCH_SAMPLE(4, true);
     else if (ti <= 8) TABED_LAUNCH_SAMPLE(8, true);
     else if (ti <= 20) TABED_LAUNCH_SAMPLE(20, false);
-    else return hipErrorInvalidValue;              // V > 163840: validate_cfg rejects it before this point
+    else if (ti <= 32) { if (vec) TABED_LAUNCH_SAMPLE_N(32, 0); else launch(&prof, k_sample<false, 32, 0>, grid, dim3(kBlock), 0, s, a); }
+    else return hipErrorInvalidValue;              // V > 262144: validate_cfg rejects it before this point
 #undef TABED_LAUNCH_SAMPLE_N
 #undef TABED_LAUNCH_SAMPLE
     return hipGetLastError();

@@ -61,6 +61,7 @@ def test_workspace_bytes_and_cfg_validation(lib):
         assert binding.tabed_workspace_bytes(good_cfg(**bad)) == 0, bad
     assert binding.tabed_workspace_bytes(good_cfg(d=100, w_dtype=0)) > 0      # fp32 storage has no d % 8 rule
     assert binding.tabed_workspace_bytes(good_cfg(V=32001)) > 0               # ragged vocabularies are fine
+    assert binding.tabed_workspace_bytes(good_cfg(V=262144)) > 0 and binding.tabed_workspace_bytes(good_cfg(V=262145)) == 0
     assert binding.tabed_dev_width(good_cfg()) == 4 and binding.tabed_dev_width(good_cfg(distance=1)) == 4
     assert binding.tabed_dev_width(good_cfg(n=2, policy=2)) == 11 and binding.tabed_dev_width(good_cfg(n=3, policy=2)) == 0
 
