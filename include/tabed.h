@@ -74,7 +74,7 @@ typedef struct tabed_cfg {
     int32_t V;        /* vocabulary size, 1..262144                                        */
     int32_t d;        /* draft hidden size, >= 1 (multiple of 8 when w_dtype = 1)          */
     int32_t n;        /* drafting methods batched through the draft model, 1..TABED_MAX_N  */
-    int32_t B;        /* independent sequences, >= 1                                       */
+    int32_t B;        /* independent sequences, 1..65535                                   */
     int32_t gamma;    /* draft block length, 1..TABED_MAX_GAMMA                            */
     int32_t h;        /* observation window length in verified positions, >= 1; 0 = ALL    */
                       /* positions since the start (the paper's default, App. B.1)         */

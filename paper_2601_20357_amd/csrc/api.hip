@@ -1,6 +1,7 @@
 // C ABI of the TABED hot path (see include/tabed.h): argument validation on the host, workspace
 // layout, launch sequencing, optional per-kernel event timing.  No allocation, no synchronisation,
 // except inside the tabed_prof_* calls.
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -22,7 +23,7 @@ int validate_cfg(const tabed_cfg* c) {
     if (c->policy < 0 || c->policy > 2) return TABED_EINVAL;
     if (c->policy == 2 && c->n != 2) return TABED_EINVAL;
     if (!(c->tau_w > 0.f) || !(c->eps > 0.f)) return TABED_EINVAL;
-    if ((long long)c->B * c->n > (1ll << 24)) return TABED_ERANGE;
+    if (c->B > 65535 || (long long)c->B * c->n > (1ll << 24)) return TABED_ERANGE;   // B is a grid dimension
     if (c->V > kTileV * kBlock * 32) return TABED_ERANGE;      // 262144: largest vocabulary the sampler tiles
     return TABED_OK;
 }
@@ -57,12 +58,12 @@ struct ProfRec {
     hipEvent_t start, stop;
 };
 static std::mutex g_prof_mu;
-static bool g_prof_on = false;
+static std::atomic<bool> g_prof_on{false};
 static std::vector<ProfRec> g_prof_pending;
 static double g_prof_ms[TABED_K_COUNT];
 static int64_t g_prof_n[TABED_K_COUNT];
 
-bool prof_on() { return g_prof_on; }
+bool prof_on() { return g_prof_on.load(std::memory_order_relaxed); }
 void prof_push(int id, hipEvent_t start, hipEvent_t stop) {
     std::lock_guard<std::mutex> lk(g_prof_mu);
     g_prof_pending.push_back(ProfRec{id, start, stop});
@@ -191,7 +192,7 @@ int tabed_philox_uniforms(const tabed_cfg* cfg, uint64_t round, float* out, void
 
 int tabed_prof_enable(int on) {
     std::lock_guard<std::mutex> lk(g_prof_mu);
-    g_prof_on = (on != 0);
+    g_prof_on.store(on != 0, std::memory_order_relaxed);
     return TABED_OK;
 }
 

@@ -6,6 +6,7 @@
 // correctness configuration) use plain FMAs.
 #include <hip/hip_bf16.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "device_utils.h"
@@ -515,12 +516,11 @@ template <int KH, int MT>
 static void launch_skinny_t(const ProfScope* prof, const tabed_cfg& c, const WsLayout& Lay, int M, const void* W, const void* H,
                             const float* temperature, float* logits, float* pm, float* ps, hipStream_t s) {
     const size_t lds = (size_t)MT * 32 * (KH * 256 + 16) + (size_t)kSkinnyWaves * kPatchBytes;
-    static bool attr_set = false;                      // raise the dynamic-LDS limit of this instantiation once
-    if (!attr_set) {
+    static std::once_flag attr_once;                   // raise the dynamic-LDS limit of this instantiation once
+    std::call_once(attr_once, [&] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_lmhead_skinny<KH, MT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        attr_set = true;
-    }
+    });
     const int num_tiles = Lay.NT;
     int cus = 256;
     const int groups = (num_tiles + 3) / 4;
@@ -554,13 +554,12 @@ hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& Lay, char* ws, cons
     } else if (skinny_applies(c, M)) {
         launch_skinny(&prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);
     } else if (M > 64 && c.d % 64 == 0) {
-        static bool attr_set = false;                      // raise the dynamic-LDS limit once
+        static std::once_flag attr_once;                   // raise the dynamic-LDS limit once
         const size_t lds = 2 * (size_t)kLargeStage;
-        if (!attr_set) {
+        std::call_once(attr_once, [&] {
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_lmhead_large),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            attr_set = true;
-        }
+        });
         const int mblocks = (M + kLBM - 1) / kLBM, nblocks = (c.V + kLBN - 1) / kLBN;
         const int nrounds = (nblocks + 7) / 8;             // vocabulary blocks are dealt to the 8 XCDs in rounds
         const dim3 grid(nrounds * mblocks * 8);

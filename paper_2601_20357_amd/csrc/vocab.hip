@@ -211,7 +211,6 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
     __shared__ double s_S[TABED_MAX_N];   // sum_v exp(scaled - max)
     __shared__ double s_c[TABED_MAX_N];   // w_j / S_j
     __shared__ float s_cf[TABED_MAX_N];
-    __shared__ double s_redd[kWavesPerBlock];
     __shared__ int s_first[kWavesPerBlock], s_lastw[kWavesPerBlock], s_tile, s_last;
     __shared__ double s_prefix;
     __shared__ Top2 s_top[kWavesPerBlock];
