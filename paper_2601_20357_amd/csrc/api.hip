@@ -47,6 +47,7 @@ WsLayout ws_layout(const tabed_cfg& c) {
     L.off_cand = off;    off = align_up(off + sizeof(Top2Rec) * (size_t)c.B * L.C2);
     L.off_stats = off;   off = align_up(off + sizeof(double) * (size_t)c.B * (c.gamma + 1) * L.C3max * L.RS);
     L.off_seg = off;     off = align_up(off + sizeof(double) * 2 * (size_t)c.B * L.NSEG);
+    L.off_wstage = off;  off = align_up(off + sizeof(float) * (size_t)c.B * c.n);
     L.off_dist = off;    off = align_up(off + sizeof(double) * (size_t)c.B * c.gamma * L.DW * L.Cd);
     L.total = off;
     return L;

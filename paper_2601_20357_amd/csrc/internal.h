@@ -37,6 +37,7 @@ struct WsLayout {
     size_t off_cand;     // Top2Rec [B][C2]
     size_t off_stats;    // double [B][gamma+1][C3max][RS]
     size_t off_seg;      // double [B][2][NSEG] segment masses: residual, target
+    size_t off_wstage;   // float [B][n] next weights staged by the fused window update
     size_t off_dist;     // double [B][gamma][DW][Cd] chunk sums of the second-pass distances (TVD, grid policy)
     size_t total;
 };

@@ -138,7 +138,8 @@ __device__ __forceinline__ void window_update(const WindowArgs& a, int b, int la
             for (int q = 0; q < n; ++q) Z += exp(s_x[q] - xmax);
             w = (float)(exp(s_x[lane] - xmax) / Z);
         }
-        a.weights[(size_t)b * n + lane] = w;
+        if (PUB) publish_store(&a.weights[(size_t)b * n + lane], w);
+        else a.weights[(size_t)b * n + lane] = w;
     }
 }
 
@@ -822,10 +823,11 @@ static void launch_stats_n(const ProfScope* prof, int U, dim3 grid, hipStream_t 
 
 // =====================================================================================================
 // Accept chain, distances, corrected / bonus token.
-// Grid (chunk, sequence b).  Every workgroup of a sequence first combines the chunk records of all
+// Grid (chunk + 1, sequence b).  Every workgroup of a sequence first combines the chunk records of all
 // gamma+1 target rows (fp64, chunk order), evaluates the gamma accept tests of Sec. 3 item 3 in parallel
-// and takes k = the first failing position.  Workgroup 0 also writes KL(p_i || q_i^(j)) and the
-// bookkeeping outputs.  For a sampling row the emitted token comes from f = max(0, p_k - q_k) (k < gamma)
+// and takes k = the first failing position.  The last workgroup of the row (the "book-keeping" one) has
+// no vocabulary chunk: it writes KL(p_i || q_i^(j)) and the bookkeeping outputs and, when asked to,
+// advances the window and computes the next weights while its siblings work on the residual row.  For a sampling row the emitted token comes from f = max(0, p_k - q_k) (k < gamma)
 // or f = p_gamma (k = gamma): every wave writes the mass of f over its 256-wide segments; the last
 // workgroup of the sequence to arrive prefixes the segment masses in order, finds the segment the uniform
 // falls into, and one wave re-evaluates that segment element by element.  A greedy row emits the arg-max of
@@ -847,8 +849,9 @@ struct FinishArgs {
     const double* dist;   // [B][gamma][DW][Cd] second-pass chunk sums, or nullptr (KL from the records)
     int DW, Cd;
     float dist_scale;     // 0.5 for total variation, 1 for KL
-    int fuse;             // 1: the workgroup that finishes a sequence also advances its window and weights
+    int fuse;             // 1: the call also advances every sequence's window and writes the next weights
     WindowArgs win;
+    float* wstage;        // [B][n] next weights, staged until every workgroup of the sequence has arrived
     double* seg;          // [B][2][NSEG]
     uint32_t* tickets;
     int32_t* accept_len;
@@ -1016,7 +1019,8 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
         }
     }
     const bool greedy = !(T > 0.f);
-    if (greedy && c != 0) return;
+    const bool book = (c == a.C5);                        // the book-keeping workgroup of this sequence
+    if (greedy && !book) return;
     const float invT = greedy ? 1.f : 1.f / T;
     const bool y_ok = (y >= 0 && y < V);
     if (tid < gamma && y_ok && !greedy) rawy = a.target[((size_t)b * (gamma + 1) + tid) * V + y];
@@ -1058,13 +1062,13 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
     constexpr int kSegPerWave = kSegPerChunk / kWavesPerBlock;    // 2
     float f[kSegPerWave][4], p[kSegPerWave][4];
     int vs[kSegPerWave];
-    if (!greedy) {
+    if (!greedy && !book) {
 #pragma unroll
         for (int s = 0; s < kSegPerWave; ++s) vs[s] = (c * kSegPerChunk + wave + s * kWavesPerBlock) * kSegV + lane * 4;
         resid_eval<VEC, N, kSegPerWave>(r, n, V, vs, hi_k, lo_k, s_w, f, p);
     }
 
-    if (c == 0) {
+    if (book) {
         if (a.dist == nullptr) {
             // ---- distances: thread per (position, draft), chunks in order with the scales computed above
             for (int q = tid; q < gamma * n; q += kBlock) {
@@ -1112,17 +1116,31 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
 
     double* segR = a.seg + ((size_t)b * 2 + 0) * NSEG;
     double* segP = a.seg + ((size_t)b * 2 + 1) * NSEG;
+    if (book) {
+        // window + next weights, off the critical path of the sampler.  The weights are staged: the buffer
+        // they go to may be the one the siblings are still reading this block's weights from.
+        if (a.fuse) {
+            __syncthreads();                               // the distances above are acknowledged
+            if (tid < kWave) {
+                WindowArgs wa = a.win;
+                wa.weights = a.wstage;
+                window_update<true>(wa, b, lane, a.dev, nv_k, s_wpart, s_wx);
+            }
+        }
+    } else {
 #pragma unroll
-    for (int s = 0; s < kSegPerWave; ++s) {
-        const int seg = c * kSegPerChunk + wave + s * kWavesPerBlock;
-        const double mf = (double)wave_sum((f[s][0] + f[s][1]) + (f[s][2] + f[s][3]));
-        const double mp = (double)wave_sum((p[s][0] + p[s][1]) + (p[s][2] + p[s][3]));
-        if (lane == 0 && seg < NSEG) { publish_store(&segR[seg], mf); publish_store(&segP[seg], mp); }
+        for (int s = 0; s < kSegPerWave; ++s) {
+            const int seg = c * kSegPerChunk + wave + s * kWavesPerBlock;
+            const double mf = (double)wave_sum((f[s][0] + f[s][1]) + (f[s][2] + f[s][3]));
+            const double mp = (double)wave_sum((p[s][0] + p[s][1]) + (p[s][2] + p[s][3]));
+            if (lane == 0 && seg < NSEG) { publish_store(&segR[seg], mf); publish_store(&segP[seg], mp); }
+        }
     }
-    __syncthreads();                                       // every wave's mass stores are acknowledged
-    if (tid == 0) s_last = arrive(&a.tickets[b], (uint32_t)a.C5) ? 1 : 0;
+    __syncthreads();                                       // every wave's published stores are acknowledged
+    if (tid == 0) s_last = arrive(&a.tickets[b], (uint32_t)(a.C5 + 1)) ? 1 : 0;
     __syncthreads();
     if (!s_last) return;
+    if (a.fuse && tid < n) a.win.weights[(size_t)b * n + tid] = published_load(&a.wstage[(size_t)b * n + tid]);
 
     // ---- last workgroup of sequence b: locate the segment, then the token
     const int S = (NSEG + kBlock - 1) / kBlock;
@@ -1147,7 +1165,6 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
             a.out_tokens[out_idx] = 0;
             a.flags[out_idx] = (uint8_t)(flag | TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE);
         }
-        if (a.fuse && tid < kWave) window_update<true>(a.win, b, lane, a.dev, nv_k, s_wpart, s_wx);
         return;
     }
     if (tid == owner) {
@@ -1195,8 +1212,6 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
         a.out_tokens[out_idx] = tok < V ? tok : V - 1;
         a.flags[out_idx] = (uint8_t)flag;
     }
-    // every workgroup of the sequence has arrived, so its distances are published: advance the window
-    if (a.fuse) window_update<true>(a.win, b, lane, a.dev, nv_k, s_wpart, s_wx);
 }
 
 hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round,
@@ -1257,10 +1272,11 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
     a.DW = L.DW; a.Cd = L.Cd; a.dist_scale = (c.distance == 1) ? 0.5f : 1.f;
     a.fuse = (ring != nullptr) ? 1 : 0;
     a.win = window_args(c, ring, ring_head, ring_count, next_weights);
+    a.wstage = reinterpret_cast<float*>(ws + L.off_wstage);
     a.seg = reinterpret_cast<double*>(ws + L.off_seg);
     a.tickets = reinterpret_cast<uint32_t*>(ws + L.off_tickets) + 2 * c.B;
     a.accept_len = accept_len; a.out_tokens = out_tokens; a.dev = dev; a.n_valid = n_valid; a.flags = flags;
-    const dim3 grid(L.C5, c.B);
+    const dim3 grid(L.C5 + 1, c.B);                      // + the book-keeping workgroup of every sequence
     const size_t lds = sizeof(double) * (size_t)(c.gamma + 1) * C3;
     if (!vec) launch(&prof, k_finish<false, 0>, grid, dim3(kBlock), lds, s, a);
     else if (ncomp == 2) launch(&prof, k_finish<true, 2>, grid, dim3(kBlock), lds, s, a);
