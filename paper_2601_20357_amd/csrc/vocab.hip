@@ -985,12 +985,22 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
                 r0v = r[0]; r1v = r[1];
                 am = ArgMax{(float)r[2], (int)r[3]};
             }
+            // all-reduce inside aligned groups of C3p lanes: DPP for the first four doublings (no LDS traffic),
+            // ds_bpermute only beyond a 16-lane row
             double m = r0v;
-            for (int o = C3p >> 1; o > 0; o >>= 1) m = fmax(m, __shfl_xor(m, o));
+            if (C3p > 1) m = fmax(m, dpp_f64<kDppXor1>(m));
+            if (C3p > 2) m = fmax(m, dpp_f64<kDppXor2>(m));
+            if (C3p > 4) m = fmax(m, dpp_f64<kDppHalfMirror>(m));
+            if (C3p > 8) m = fmax(m, dpp_f64<kDppMirror>(m));
+            for (int o = 16; o < C3p; o <<= 1) m = fmax(m, __shfl_xor(m, o));
             const double sc = (r0v > -INFINITY) ? exp(r0v - m) : 0.0;
             if (live) s_scale[row * C3 + cc] = sc;
             double Z = r1v * sc;
-            for (int o = C3p >> 1; o > 0; o >>= 1) {
+            if (C3p > 1) { Z += dpp_f64<kDppXor1>(Z); am = argmax_dpp_step<kDppXor1>(am); }
+            if (C3p > 2) { Z += dpp_f64<kDppXor2>(Z); am = argmax_dpp_step<kDppXor2>(am); }
+            if (C3p > 4) { Z += dpp_f64<kDppHalfMirror>(Z); am = argmax_dpp_step<kDppHalfMirror>(am); }
+            if (C3p > 8) { Z += dpp_f64<kDppMirror>(Z); am = argmax_dpp_step<kDppMirror>(am); }
+            for (int o = 16; o < C3p; o <<= 1) {
                 Z += __shfl_xor(Z, o);
                 const ArgMax other{__shfl_xor(am.v, o), __shfl_xor(am.i, o)};
                 am = argmax_merge(am, other);
