@@ -234,3 +234,58 @@ def test_stress_shape_fewer_sequences(oracle):
     tally = harness.run_rounds(oracle, wl, 2, synth.make_temperature(wl))
     _say(tally)
     assert tally.flagged_divergences <= 3
+
+
+def test_hip_graph_replay_matches_eager_bitwise(oracle):
+    """bench.py replays captured rounds: a captured sequence of the C-ABI calls must give, on every replay,
+    exactly what the same calls give when issued eagerly from the same state."""
+    import ctypes as C
+    wl = synth.scaled(SERVING, V=32000, B=8, gamma=3, cfg_id=97)
+    W = synth.make_lm_head(wl)
+    W_t = harness.to_dev_store(W, wl.w_dtype)
+    temp_t = torch.from_numpy(synth.make_temperature(wl, "mixed07")).to(DEV)
+    rounds = [synth.make_round(wl, W, r) for r in range(2)]
+    H_t = [[harness.to_dev_store(H[pos], wl.w_dtype) for pos in range(wl.gamma)] for H, _ in rounds]
+    T_t = [torch.from_numpy(t).to(DEV) for _, t in rounds]
+    cfg = harness.cfg_of(wl)
+    buf = binding.RoundBuffers(cfg, DEV)
+    keys = ("weights", "ring", "ring_head", "ring_count", "draft_tokens", "draft_q", "draft_lse", "accept_len",
+            "out_tokens", "dev", "n_valid", "verify_flags", "draft_flags")
+
+    def reset():
+        for k in ("weights", "ring", "ring_head", "ring_count", "dev", "n_valid"):
+            getattr(buf, k).zero_()
+
+    def two_rounds(stream=None):
+        buf.update_weights(True, stream=stream)
+        for r in range(2):
+            for pos in range(wl.gamma):
+                buf.draft_step(r, pos, W_t, H_t[r][pos], temp_t, stream=stream)
+            buf.verify(r, T_t[r], temp_t, stream=stream, fused_update=True)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return {k: getattr(buf, k).clone() for k in keys}
+
+    reset()
+    two_rounds()
+    eager = snapshot()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        reset()
+        two_rounds(side)                      # once on the side stream before capture
+        side.synchronize()
+        reset()
+        with torch.cuda.graph(graph, stream=side):
+            two_rounds(side)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        reset()
+        scratch = torch.randn(1 << 20, device=DEV).sum()       # unrelated eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for k in keys:
+            assert torch.equal(got[k], eager[k]), (replay, k)
+        del scratch
