@@ -1,7 +1,8 @@
 // Vocabulary-wide passes of a TABED round on gfx950: ensemble + draft token (Alg. 1 lines 6-7),
 // target statistics + per-draft KL + accept chain (Sec. 3 items 2-3, Sec. 4.1), corrected / bonus token
 // (Sec. 3 item 3), window + weights (Alg. 1 lines 2-3, App. B.2).  All of them are HBM- or latency-bound:
-// wave64 shuffles and a few LDS words do the reductions, fp64 carries every cross-lane sum.
+// DPP lane exchanges and a few LDS words do the reductions, fp64 carries the cross-wave and cross-workgroup
+// sums, and partial results cross workgroups through device-scope atomics (no fences).
 #include "device_utils.h"
 #include "internal.h"
 
@@ -172,9 +173,9 @@ hipError_t launch_weights(const tabed_cfg& c, const float* dev, const int32_t* n
 // The LM-head epilogue left, per draft row and per 32-wide vocabulary tile, the tile maximum of the scaled
 // logits and the tile sum of exp(scaled logit - tile maximum).  From those alone this kernel gets every
 // draft's log-sum-exp and the mass of the mixture q = sum_j w_j q^(j) inside every tile; a sampling row
-// therefore reads logits only inside the one tile its uniform falls into.  The partials of a sequence
-// (n*NT pairs) are staged into LDS in one burst of independent loads when they fit, so the kernel pays two
-// memory round trips (partials, then the chosen tile) instead of one per reduction.  A greedy row needs
+// therefore reads logits only inside the one tile its uniform falls into.  Every thread loads the partials
+// of its own tiles (all drafts) in one burst of independent loads and keeps them in registers, so the kernel
+// pays two memory round trips (partials, then the chosen tile) instead of one per reduction.  A greedy row needs
 // the arg-max of q over the whole vocabulary: its row is split over gridDim.x workgroups and the last one
 // to arrive merges the candidates (lowest index wins ties, so arrival order does not matter).
 // =====================================================================================================
