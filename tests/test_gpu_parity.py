@@ -217,7 +217,7 @@ def test_llava_full_size_greedy_and_sampling(oracle):
 
 
 def test_lvlm_full_size(oracle):
-    """V=152064, d=896, n=4, B=8, gamma=7, h=16 with the matching draft switching (BASELINE workload 4)."""
+    """V=152064, d=896, n=4, B=8, gamma=7, h=16 with the matching draft switching: the large-vocabulary LVLM workload."""
     wl = synth.WORKLOADS["lvlm"]
     _say("lvlm full size")
     tally = harness.run_rounds(oracle, wl, 2, synth.make_temperature(wl))
