@@ -26,8 +26,8 @@
  * Notation: n = number of drafting methods (the paper's m), B independent
  * sequences, V vocabulary, d draft hidden size, gamma block length, h window.
  *
- * Readings where the paper is silent are listed in the repository's design
- * notes; each is marked "reading:" below.
+ * Where the paper is silent or ambiguous the reading taken is stated at the
+ * function that takes it, marked "reading:".
  *
  * Pin status: every function below is pinned by tests that do not reuse its
  * formula (library cross-checks, closed forms, exact enumeration on tiny

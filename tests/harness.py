@@ -1,12 +1,14 @@
 """Shared machinery of the GPU parity tests: run SD rounds through the C ABI (via the binding) and through
 the CPU oracle on the same seeded inputs, and compare element by element.
 
-Tolerances (derived in the repository's design notes):
-  logits        |dL| <= 1e-5 * max|L|   (exact bf16 products, fp32 MFMA accumulation vs fp64)  and <= 2e-2 (budget)
-  lse           |d| <= 2e-6
-  q(y), p       relative 1e-5
-  dev (KL)      |d| <= 1e-5 * |dev| + 1e-6
-  weights       |d| <= 1e-5 * w + 1e-6   (end to end; the isolated kernel is tested to 1e-6 relative)
+Tolerances, and where they come from (the oracle computes in fp64 from the same stored inputs):
+  logits        |dL| <= 1e-5 * max|L| and <= 2e-2: bf16 x bf16 products are exact in fp32, the MFMA adds d of them in
+                fp32, so the error is ~d * eps * |terms| ~ 1e-6 at |L| ~ 1
+  lse           |d| <= 2e-6 absolute (a logit error moves a log-sum-exp by at most that error)
+  q(y), p       relative 1e-5 (a logit error delta moves a log-probability by at most 2 * delta)
+  dev           |d| <= 1e-5 * |dev| + 1e-6: KL is a difference of O(1)..O(10) quantities, so its error is absolute
+  weights       |d| <= 1e-5 * w + 1e-6 end to end (x = 1/e amplifies an absolute error of e by 1/e^2); the weights
+                kernel alone, fed identical windows, is tested to 1e-6 relative
   integers      bit-exact unless the decision that produced them is flagged (margin < 1e-6) on either side
 """
 from __future__ import annotations
