@@ -199,7 +199,7 @@ def verify(*, V, n, B, gamma, distance, seed, rnd, target_logits, draft_logits, 
     return out
 
 
-def update_weights(*, n, B, gamma, h, policy, tau_w, eps, dev, n_valid, ring, ring_head, ring_count):
+def update_weights(*, n, B, gamma, h, policy, tau_w, eps, dev, n_valid, ring, ring_head, ring_count, seed=0, rnd=0):
     """Alg. 1 lines 2-3 (App. B.2 policy); ring state is updated in place; returns weights [B,n]."""
     assert ring.dtype == np.float32 and ring.shape == (B, max(h, 1), dev_width(n, policy))   # h = 0: window ALL
     assert policy != 2 or n == 2
@@ -208,5 +208,6 @@ def update_weights(*, n, B, gamma, h, policy, tau_w, eps, dev, n_valid, ring, ri
     nv = None if n_valid is None else np.ascontiguousarray(n_valid, dtype=np.int32)
     w = np.empty((B, n), dtype=np.float32)
     lib().oracle_update_weights(n, B, gamma, h, policy, C.c_double(tau_w), C.c_double(eps),
+                                C.c_uint64(seed), C.c_uint64(rnd),
                                 _p(d_), _p(nv), _p(ring), _p(ring_head), _p(ring_count), _p(w))
     return w

@@ -411,13 +411,17 @@ void oracle_verify(int V, int n, int B, int gamma, int distance, int n_cand,
  * window; policy 1: equal weights; policy 2 (n = 2, window entries are the 11
  * candidate distances): w = [1 - c/10, c/10] for the candidate c with the
  * smallest window sum (reading: lowest c on ties; equal weights while the
- * window is empty).  The window holds vectors of width DW = n (policies 0, 1)
+ * window is empty); policy 3: the random-weights ablation of Sec. 5 (reading:
+ * uniform on the simplex, drawn afresh for every block: w_j = E_j / sum E,
+ * E_j = -ln U_j, U_j = (x + 0.5) 2^-24 from word j % 4 of the Philox block
+ * (seed; round, b, gamma + 1 + j / 4), `round` being the block the weights are
+ * for); the window is still maintained.  The window holds vectors of width DW = n (policies 0, 1)
  * or 11 (policy 2).
  * reading: an empty window gives equal weights; a window with fewer than h
  * entries sums what exists; 1/e is clamped by eps; softmax(x; tau) divides
  * by tau. */
 void oracle_update_weights(int n, int B, int gamma, int h, int policy,
-                           double tau_w, double eps,
+                           double tau_w, double eps, uint64_t seed, uint64_t round,
                            const float* dev, const int32_t* n_valid,
                            float* ring, int32_t* ring_head, int32_t* ring_count,
                            float* weights)
@@ -444,6 +448,19 @@ void oracle_update_weights(int n, int B, int gamma, int h, int policy,
         float* w = weights + (size_t)b * n;
         int count = ring_count[b];
         if (all && count > 1) count = 1; /* the single slot already holds the sum; head stays 0 */
+        if (policy == 3) {
+            double E[64], tot = 0.0;
+            for (int j = 0; j < n; ++j) {
+                uint32_t ctr[4] = { (uint32_t)round, (uint32_t)(round >> 32), (uint32_t)b, (uint32_t)(gamma + 1 + j / 4) };
+                uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+                uint32_t out[4];
+                oracle_philox4x32_10(ctr, key, out);
+                E[j] = -log(((double)(out[j % 4] >> 8) + 0.5) * (1.0 / 16777216.0));
+                tot += E[j];
+            }
+            for (int j = 0; j < n; ++j) w[j] = (float)(E[j] / tot);
+            continue;
+        }
         if (policy == 1 || count == 0) {
             for (int j = 0; j < n; ++j) w[j] = (float)(1.0 / n);
             continue;

@@ -421,3 +421,34 @@ def test_window_all_is_the_sum_over_every_verified_position(oracle):
     w = oracle.update_weights(n=n, B=1, gamma=gamma, h=0, policy=0, tau_w=1.0, eps=1e-6, dev=None, n_valid=None,
                               ring=ring, ring_head=np.zeros(1, np.int32), ring_count=np.zeros(1, np.int32))
     assert np.all(w == np.float32(0.25))
+
+
+def test_random_weights_are_uniform_on_the_simplex(oracle):
+    """Policy 3 (the paper's random-weights ablation): Dirichlet(1,..,1), i.e. each weight ~ Beta(1, n-1),
+    fresh for every block and sequence; the window is maintained all the same."""
+    n, B, gamma, h = 4, 64, 3, 5
+    ring = np.zeros((B, h, n), np.float32); head = np.zeros(B, np.int32); count = np.zeros(B, np.int32)
+    ws = []
+    for rnd in range(60):
+        dev = np.full((B, gamma, n), 0.5, np.float32)
+        w = oracle.update_weights(n=n, B=B, gamma=gamma, h=h, policy=3, tau_w=1.0, eps=1e-6, dev=dev if rnd else None,
+                                  n_valid=np.full(B, 2, np.int32) if rnd else None, ring=ring, ring_head=head,
+                                  ring_count=count, seed=9, rnd=rnd)
+        assert np.all(w >= 0) and np.all(np.abs(w.sum(axis=1) - 1) < 1e-6)
+        ws.append(w)
+    ws = np.concatenate(ws)                                     # 3840 draws
+    for j in range(n):
+        assert st.kstest(ws[:, j], st.beta(1, n - 1).cdf).pvalue > 1e-3
+    assert abs(ws.mean() - 1 / n) < 1e-6
+    assert np.abs(np.corrcoef(ws[:-B, 0], ws[B:, 0])[0, 1]) < 0.06      # fresh per block
+    assert len({tuple(r) for r in np.round(ws, 6)}) == len(ws)          # and per sequence
+    assert np.all(count == h) and np.all(ring == 0.5)                   # the window was pushed all along
+    # same (seed, round, b) => same weights; another seed => others
+    a = oracle.update_weights(n=n, B=2, gamma=gamma, h=h, policy=3, tau_w=1.0, eps=1e-6, dev=None, n_valid=None,
+                              ring=np.zeros((2, h, n), np.float32), ring_head=np.zeros(2, np.int32),
+                              ring_count=np.zeros(2, np.int32), seed=9, rnd=7)
+    assert np.array_equal(a, ws[7 * B: 7 * B + 2])
+    b = oracle.update_weights(n=n, B=2, gamma=gamma, h=h, policy=3, tau_w=1.0, eps=1e-6, dev=None, n_valid=None,
+                              ring=np.zeros((2, h, n), np.float32), ring_head=np.zeros(2, np.int32),
+                              ring_count=np.zeros(2, np.int32), seed=10, rnd=7)
+    assert not np.array_equal(a, b)
