@@ -163,6 +163,7 @@ def main():
         if s == 0:
             upd_first()                       # opens the first round: empty window, equal weights
         elif args.separate_update:
+            upd.set_round(s)
             upd()
         for c in drafts:
             c.set_round(s)

@@ -82,7 +82,9 @@ typedef struct tabed_cfg {
     int32_t distance; /* D of Alg. 1: 0 = KL(p || q) (Sec. 4.1); 1 = total variation       */
     int32_t policy;   /* 0 = softmax(1/e; tau_w) (App. B.2); 1 = static equal weights;     */
                       /* 2 = two-draft grid (App. B.2): arg-min over w^c = [1-c/10, c/10], */
-                      /*     c = 0..10, of the window sum of D(p, mixture); needs n = 2    */
+                      /*     c = 0..10, of the window sum of D(p, mixture); needs n = 2;   */
+                      /* 3 = random weights, uniform on the simplex, fresh for every block */
+                      /*     (the random-weights ablation of Sec. 5)                       */
     float tau_w;      /* temperature of the weight softmax, > 0 (paper default 1)          */
     float eps;        /* e is clamped to >= eps before 1/e, > 0                            */
     uint64_t seed;    /* Philox key                                                        */
@@ -147,7 +149,7 @@ int tabed_draft_step(const tabed_cfg* cfg, void* ws, uint64_t round, int32_t pos
  *   n_valid       [B]       int32 out  min(k+1, gamma): positions whose distances enter the window
  *   flags         [B,gamma+1] uint8 out flags of the accept test at i and of the sample emitted at i
  *   ring, ring_head, ring_count, next_weights: optional, all four or all NULL.  When given, the call also
- *                 performs the tabed_update_weights() that would open the next round (same arguments, same
+ *                 performs the tabed_update_weights() that would open round + 1 (same arguments, same
  *                 result: the window takes the n_valid verified positions and next_weights [B,n] receives the
  *                 weights of the next block), saving that call's launch.  next_weights may alias weights.
  * A drafted token outside [0,V) is rejected and flagged TABED_FLAG_DEGENERATE.
@@ -165,8 +167,11 @@ int tabed_verify(const tabed_cfg* cfg, void* ws, uint64_t round,
  * n_valid[b] verified positions of the finished block into the window, then
  * w = softmax((1 / max(e_j, eps)) / tau_w) with e_j the window sum (policy 0), or the candidate
  * [1-c/10, c/10] with the smallest window sum, lowest c on ties (policy 2).  An empty
- * window, or policy 1, gives equal weights.
+ * window, or policy 1, gives equal weights.  Policy 3 ignores the window (but maintains it):
+ * w_j = E_j / sum E with E_j = -ln U_j, U_j = (x + 0.5) 2^-24 from word j % 4 of the Philox block
+ * (cfg->seed; round, b, gamma + 1 + j / 4).
  *
+ *   round      the round (block) the weights are for: only policy 3 reads it
  *   dev        [B,gamma,DW] fp32 in     may be NULL together with n_valid (nothing to push)
  *   n_valid    [B]         int32 in
  *   ring       [B,h,DW]    fp32  in/out caller-owned window state (zero-initialised); with h = 0 it is
@@ -175,7 +180,7 @@ int tabed_verify(const tabed_cfg* cfg, void* ws, uint64_t round,
  *   ring_count [B]         int32 in/out live slots, <= h (h = 0: positions summed so far)
  *   weights    [B,n]       fp32  out
  */
-int tabed_update_weights(const tabed_cfg* cfg, void* ws, const float* dev, const int32_t* n_valid,
+int tabed_update_weights(const tabed_cfg* cfg, void* ws, uint64_t round, const float* dev, const int32_t* n_valid,
                          float* ring, int32_t* ring_head, int32_t* ring_count, float* weights,
                          void* stream);
 

@@ -61,7 +61,7 @@ def load():
     lib.tabed_verify.restype = C.c_int
     lib.tabed_verify.argtypes = [cfgp, vp, u64] + [vp] * 19
     lib.tabed_update_weights.restype = C.c_int
-    lib.tabed_update_weights.argtypes = [cfgp, vp] + [vp] * 7
+    lib.tabed_update_weights.argtypes = [cfgp, vp, u64] + [vp] * 7
     lib.tabed_philox_uniforms.restype = C.c_int
     lib.tabed_philox_uniforms.argtypes = [cfgp, u64, vp, vp]
     lib.tabed_prof_enable.restype = C.c_int
@@ -180,12 +180,12 @@ def tabed_verify(cfg, ws, rnd, target_logits, draft_logits, draft_lse, draft_tok
     _check(rc, "tabed_verify")
 
 
-def tabed_update_weights(cfg, ws, dev, n_valid, ring, ring_head, ring_count, weights, stream=None):
+def tabed_update_weights(cfg, ws, rnd, dev, n_valid, ring, ring_head, ring_count, weights, stream=None):
     import torch
     n, B, g, h = cfg.n, cfg.B, cfg.gamma, cfg.h
     dw = tabed_dev_width(cfg)
     rc = load().tabed_update_weights(
-        C.byref(cfg), _ptr(ws, name="ws"),
+        C.byref(cfg), _ptr(ws, name="ws"), rnd,
         _ptr(dev, torch.float32, B * g * dw, "dev"), _ptr(n_valid, torch.int32, B, "n_valid"),
         _ptr(ring, torch.float32, B * max(h, 1) * dw, "ring"), _ptr(ring_head, torch.int32, B, "ring_head"),
         _ptr(ring_count, torch.int32, B, "ring_count"), _ptr(weights, torch.float32, B * n, "weights"),
@@ -268,15 +268,15 @@ class RoundBuffers:
         self.verify_flags = z((B, g + 1), torch.uint8)
 
     # ---- the same three calls with arguments converted once (hot loops)
-    def prepare_update_weights(self, first: bool, stream=None) -> PreparedCall:
+    def prepare_update_weights(self, first: bool, rnd=0, stream=None) -> PreparedCall:
         import torch
         c = self.cfg
         vp = C.c_void_p
-        args = [C.byref(c), vp(self.ws.data_ptr()),
+        args = [C.byref(c), vp(self.ws.data_ptr()), C.c_uint64(rnd),
                 vp(None if first else self.dev.data_ptr()), vp(None if first else self.n_valid.data_ptr()),
                 vp(self.ring.data_ptr()), vp(self.ring_head.data_ptr()), vp(self.ring_count.data_ptr()),
                 vp(self.weights.data_ptr()), vp(_stream(stream))]
-        return PreparedCall(load().tabed_update_weights, args, "tabed_update_weights")
+        return PreparedCall(load().tabed_update_weights, args, "tabed_update_weights", args[2])
 
     def prepare_draft_step(self, rnd, pos, W, H, temperature, u_draft=None, stream=None) -> PreparedCall:
         import torch
@@ -309,8 +309,8 @@ class RoundBuffers:
                 vp(self.weights.data_ptr() if fused_update else None), vp(_stream(stream))]
         return PreparedCall(load().tabed_verify, args, "tabed_verify", args[2])
 
-    def update_weights(self, first: bool, stream=None):
-        tabed_update_weights(self.cfg, self.ws, None if first else self.dev, None if first else self.n_valid,
+    def update_weights(self, first: bool, rnd=0, stream=None):
+        tabed_update_weights(self.cfg, self.ws, rnd, None if first else self.dev, None if first else self.n_valid,
                              self.ring, self.ring_head, self.ring_count, self.weights, stream)
 
     def draft_step(self, rnd, pos, W, H, temperature, u_draft=None, stream=None):

@@ -20,7 +20,7 @@ int validate_cfg(const tabed_cfg* c) {
     if (c->w_dtype != 0 && c->w_dtype != 1) return TABED_EINVAL;
     if (c->w_dtype == 1 && (c->d % 8) != 0) return TABED_EINVAL;
     if (c->distance != 0 && c->distance != 1) return TABED_EINVAL;
-    if (c->policy < 0 || c->policy > 2) return TABED_EINVAL;
+    if (c->policy < 0 || c->policy > 3) return TABED_EINVAL;
     if (c->policy == 2 && c->n != 2) return TABED_EINVAL;
     if (!(c->tau_w > 0.f) || !(c->eps > 0.f)) return TABED_EINVAL;
     if (c->B > 65535 || (long long)c->B * c->n > (1ll << 24)) return TABED_ERANGE;   // B is a grid dimension
@@ -171,14 +171,14 @@ int tabed_verify(const tabed_cfg* cfg, void* ws, uint64_t round, const float* ta
     return e == hipSuccess ? TABED_OK : fail_hip(e);
 }
 
-int tabed_update_weights(const tabed_cfg* cfg, void* ws, const float* dev, const int32_t* n_valid, float* ring,
+int tabed_update_weights(const tabed_cfg* cfg, void* ws, uint64_t round, const float* dev, const int32_t* n_valid, float* ring,
                          int32_t* ring_head, int32_t* ring_count, float* weights, void* stream) {
     (void)ws;
     const int rc = validate_cfg(cfg);
     if (rc != TABED_OK) return rc;
     if (!ring || !ring_head || !ring_count || !weights) return TABED_ENULL;
     if ((dev == nullptr) != (n_valid == nullptr)) return TABED_ENULL;
-    const hipError_t e = launch_weights(*cfg, dev, n_valid, ring, ring_head, ring_count, weights,
+    const hipError_t e = launch_weights(*cfg, round, dev, n_valid, ring, ring_head, ring_count, weights,
                                         static_cast<hipStream_t>(stream));
     return e == hipSuccess ? TABED_OK : fail_hip(e);
 }

@@ -62,7 +62,7 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
                          int32_t* out_tokens, float* dev, int32_t* n_valid, uint8_t* flags, float* ring,
                          int32_t* ring_head, int32_t* ring_count, float* next_weights, hipStream_t s);
 
-hipError_t launch_weights(const tabed_cfg& c, const float* dev, const int32_t* n_valid, float* ring,
+hipError_t launch_weights(const tabed_cfg& c, uint64_t round, const float* dev, const int32_t* n_valid, float* ring,
                           int32_t* ring_head, int32_t* ring_count, float* weights, hipStream_t s);
 
 hipError_t launch_null(hipStream_t s);

@@ -58,6 +58,7 @@ hipError_t launch_philox(const tabed_cfg& c, uint64_t round, float* out, hipStre
 struct WindowArgs {
     int n, dw, gamma, h, policy;
     double tau_w, eps;
+    uint64_t seed, round;   // policy 3: Philox key and the round the weights are for
     float* ring;
     int32_t* ring_head;
     int32_t* ring_count;
@@ -122,10 +123,20 @@ __device__ __forceinline__ void window_update(const WindowArgs& a, int b, int la
         }
         empty = (new_count == 0);
     }
+    if (policy == 3 && lane < n) {                     // random weights: E_j = -ln U_j, normalised below
+        const U4 r = philox4x32_10((uint32_t)a.round, (uint32_t)(a.round >> 32), (uint32_t)b,
+                                   (uint32_t)(gamma + 1 + lane / 4), (uint32_t)a.seed, (uint32_t)(a.seed >> 32));
+        const uint32_t x = (lane & 3) == 0 ? r.x : (lane & 3) == 1 ? r.y : (lane & 3) == 2 ? r.z : r.w;
+        s_x[lane] = -log(((double)(x >> 8) + 0.5) * (1.0 / 16777216.0));
+    }
     __builtin_amdgcn_wave_barrier();
     if (lane < n) {
         float w;
-        if (policy == 1 || empty) {
+        if (policy == 3) {
+            double tot = 0.0;
+            for (int q = 0; q < n; ++q) tot += s_x[q];
+            w = (float)(s_x[lane] / tot);
+        } else if (policy == 1 || empty) {
             w = (float)(1.0 / (double)n);
         } else if (policy == 2) {
             int best = 0;                             // arg-min of the window sums, lowest index on ties
@@ -153,18 +164,21 @@ __global__ __launch_bounds__(64) void k_weights(WindowArgs a, const float* __res
     window_update<false>(a, b, threadIdx.x, (dev != nullptr && n_valid != nullptr) ? dev : nullptr, nv, s_part, s_x);
 }
 
-static WindowArgs window_args(const tabed_cfg& c, float* ring, int32_t* ring_head, int32_t* ring_count, float* weights) {
+static WindowArgs window_args(const tabed_cfg& c, uint64_t round, float* ring, int32_t* ring_head, int32_t* ring_count,
+                              float* weights) {
     WindowArgs a;
+    a.seed = c.seed; a.round = round;
     a.n = c.n; a.dw = (c.policy == 2) ? TABED_GRID_CANDIDATES : c.n; a.gamma = c.gamma; a.h = c.h; a.policy = c.policy;
     a.tau_w = (double)c.tau_w; a.eps = (double)c.eps;
     a.ring = ring; a.ring_head = ring_head; a.ring_count = ring_count; a.weights = weights;
     return a;
 }
 
-hipError_t launch_weights(const tabed_cfg& c, const float* dev, const int32_t* n_valid, float* ring,
+hipError_t launch_weights(const tabed_cfg& c, uint64_t round, const float* dev, const int32_t* n_valid, float* ring,
                           int32_t* ring_head, int32_t* ring_count, float* weights, hipStream_t s) {
     ProfScope prof(TABED_K_WEIGHTS, s);
-    launch(&prof, k_weights, dim3(c.B), dim3(64), 0, s, window_args(c, ring, ring_head, ring_count, weights), dev, n_valid);
+    launch(&prof, k_weights, dim3(c.B), dim3(64), 0, s, window_args(c, round, ring, ring_head, ring_count, weights), dev,
+           n_valid);
     return hipGetLastError();
 }
 
@@ -1282,7 +1296,7 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
     a.dist = second_pass ? reinterpret_cast<const double*>(ws + L.off_dist) : nullptr;
     a.DW = L.DW; a.Cd = L.Cd; a.dist_scale = (c.distance == 1) ? 0.5f : 1.f;
     a.fuse = (ring != nullptr) ? 1 : 0;
-    a.win = window_args(c, ring, ring_head, ring_count, next_weights);
+    a.win = window_args(c, round + 1, ring, ring_head, ring_count, next_weights);   // the weights of the NEXT round
     a.wstage = reinterpret_cast<float*>(ws + L.off_wstage);
     a.seg = reinterpret_cast<double*>(ws + L.off_seg);
     a.tickets = reinterpret_cast<uint32_t*>(ws + L.off_tickets) + 2 * c.B;

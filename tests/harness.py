@@ -49,7 +49,7 @@ class OracleSide:
         B, n, g, V = wl.B, wl.n, wl.gamma, wl.V
         w = o.update_weights(n=n, B=B, gamma=g, h=wl.h, policy=self.policy, tau_w=self.tau_w, eps=self.eps,
                              dev=self.dev, n_valid=self.n_valid, ring=self.ring, ring_head=self.head,
-                             ring_count=self.count)
+                             ring_count=self.count, seed=self.seed, rnd=rnd)
         dl = np.zeros((g, B, n, V), np.float32)
         lse = np.zeros((g, B, n), np.float64)
         tok = np.zeros((B, g), np.int32)
@@ -82,7 +82,7 @@ class GpuSide:
         temp_t, tgt_t = t(temp), t(target)
         ud, ua, ur = t(u_draft), t(u_acc), t(u_res)
         if self.need_update:
-            buf.update_weights(self.first)
+            buf.update_weights(self.first, rnd=rnd)
         self.first = False
         self.need_update = not self.fused
         w_used = buf.weights.clone()

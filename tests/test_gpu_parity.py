@@ -80,8 +80,8 @@ def test_static_policy_and_other_tau(oracle):
 
 
 # ------------------------------------------------------------------ total variation distance and the two-draft grid policy
-@pytest.mark.parametrize("policy,distance,n", [(0, 1, 4), (2, 0, 2), (2, 1, 2), (1, 1, 3)],
-                         ids=["tvd", "grid-kl", "grid-tvd", "static-tvd"])
+@pytest.mark.parametrize("policy,distance,n", [(0, 1, 4), (2, 0, 2), (2, 1, 2), (1, 1, 3), (3, 0, 5)],
+                         ids=["tvd", "grid-kl", "grid-tvd", "static-tvd", "random-weights"])
 def test_distance_and_policy_variants(oracle, policy, distance, n):
     for V, d, B, mode in ((4100, 64, 5, "mixed07"), (4099, 72, 3, "one"), (32000, 768, 4, "one")):
         wl = synth.scaled(SERVING, V=V, d=d, n=n, B=B, gamma=3, h=5, cfg_id=70 + policy * 2 + distance)
@@ -92,8 +92,8 @@ def test_distance_and_policy_variants(oracle, policy, distance, n):
 
 
 @pytest.mark.parametrize("policy,distance,n,h,mode", [(0, 0, 4, 8, "one"), (0, 0, 3, 5, "mixed07"), (2, 1, 2, 0, "one"),
-                                                        (0, 0, 4, 0, "greedy")],
-                         ids=["softmax", "mixed-rows", "grid-tvd-all", "greedy-all"])
+                                                        (0, 0, 4, 0, "greedy"), (3, 0, 16, 4, "mixed07")],
+                         ids=["softmax", "mixed-rows", "grid-tvd-all", "greedy-all", "random-16-drafts"])
 def test_verify_with_fused_window_update(oracle, policy, distance, n, h, mode):
     """tabed_verify given the window pointers must leave the same window and next weights as the separate
     tabed_update_weights call the oracle models."""
@@ -170,11 +170,11 @@ def test_update_weights_alone_matches_oracle_bitwise_state(oracle):
         dev = (rng.random((B, gamma, n)) * (10.0 ** rng.uniform(-4, 0.5, (B, 1, 1)))).astype(np.float32)
         nv = rng.integers(1, gamma + 1, B).astype(np.int32)
         if step == 0:
-            binding.tabed_update_weights(cfg, ws, None, None, ring, head, count, w)
+            binding.tabed_update_weights(cfg, ws, 0, None, None, ring, head, count, w)
             ow = oracle.update_weights(n=n, B=B, gamma=gamma, h=h, policy=0, tau_w=0.5, eps=1e-6, dev=None,
                                        n_valid=None, ring=o_ring, ring_head=o_head, ring_count=o_count)
         else:
-            binding.tabed_update_weights(cfg, ws, torch.from_numpy(dev).to(DEV), torch.from_numpy(nv).to(DEV),
+            binding.tabed_update_weights(cfg, ws, step, torch.from_numpy(dev).to(DEV), torch.from_numpy(nv).to(DEV),
                                          ring, head, count, w)
             ow = oracle.update_weights(n=n, B=B, gamma=gamma, h=h, policy=0, tau_w=0.5, eps=1e-6, dev=dev,
                                        n_valid=nv, ring=o_ring, ring_head=o_head, ring_count=o_count)
