@@ -250,6 +250,7 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
     auto tile_of = [&](int i) { return CHUNKED ? ((i / 4) * kBlock + tid) * 4 + (i & 3) : tid * TI + i; };
 
     float uu[(N > 0) ? N : 1][TI];                     // single pass: terms of this thread's tiles, all drafts
+    double lse_mine = 0.0;
     if (N > 0) {
         // ---- single pass over the partials of every draft
         float pmv[(N > 0) ? N : 1][TI], psv[(N > 0) ? N : 1][TI];
@@ -298,13 +299,15 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
             if (lane == 0) s_wsum[wave][j] = S;
         }
         __syncthreads();
-        if (tid < N) {
+        if (tid < N) {                                     // thread j: everything the later phases need of draft j
             const int j = tid;
             const float M = fmaxf(fmaxf(s_wm[0][j], s_wm[1][j]), fmaxf(s_wm[2][j], s_wm[3][j]));
             const double S = (s_wsum[0][j] + s_wsum[1][j]) + (s_wsum[2][j] + s_wsum[3][j]);
             s_m[j] = M;
             s_S[j] = S;
-            if (c == 0) a.draft_lse[((size_t)a.pos * a.B + b) * n + j] = (double)M + log(S);
+            s_c[j] = (double)wj / S;
+            s_cf[j] = (float)s_c[j];
+            lse_mine = (double)M + log(S);                 // stored after the barrier below
         }
     } else {
         // ---- per-draft log-sum-exp: one wave per draft row, lanes strided over the row's tiles
@@ -335,11 +338,15 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
     const bool greedy = !(T > 0.f);
     const float invT = greedy ? 1.f : 1.f / T;
     __syncthreads();
-    if (tid < n) {
-        s_c[tid] = (double)wj / s_S[tid];
-        s_cf[tid] = (float)s_c[tid];
+    if (N > 0) {
+        if (tid < N && c == 0) a.draft_lse[((size_t)a.pos * a.B + b) * n + tid] = lse_mine;
+    } else {
+        if (tid < n) {
+            s_c[tid] = (double)wj / s_S[tid];
+            s_cf[tid] = (float)s_c[tid];
+        }
+        __syncthreads();
     }
-    __syncthreads();
 
     const float* rows = a.logits + (size_t)b * n * V;
 
