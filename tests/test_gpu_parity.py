@@ -289,3 +289,26 @@ def test_hip_graph_replay_matches_eager_bitwise(oracle):
         for k in keys:
             assert torch.equal(got[k], eager[k]), (replay, k)
         del scratch
+
+
+def test_seeded_sweep_of_small_shapes(oracle):
+    """Twenty seeded random configurations (vocabulary, hidden size, drafts, sequences, block length, window,
+    storage type, temperature mix, policy, distance, fused or separate window update)."""
+    rng = np.random.default_rng(2024)
+    for case in range(20):
+        w_dtype = int(rng.integers(0, 2))
+        d = int(rng.choice([8, 24, 64, 72, 128, 256, 512] if w_dtype else [5, 8, 33, 64]))
+        policy = int(rng.choice([0, 0, 0, 1, 2, 3]))
+        n = 2 if policy == 2 else int(rng.integers(1, 10))
+        distance = int(rng.integers(0, 2))
+        B = int(rng.integers(1, 23))
+        wl = synth.scaled(SERVING, V=int(rng.integers(1, 9000)), d=d, n=n, B=B, gamma=int(rng.integers(1, 7)),
+                          h=int(rng.integers(0, 9)), w_dtype=w_dtype, cfg_id=200 + case,
+                          target=str(rng.choice(["per_seq_sigma", "independent", "student_t"])), sigma=1.0)
+        mode = str(rng.choice(["one", "greedy", "mixed07"]))
+        fused = bool(rng.integers(0, 2))
+        _say(f"case {case}: V={wl.V} d={d} n={n} B={B} gamma={wl.gamma} h={wl.h} w_dtype={w_dtype} {mode} "
+             f"policy={policy} distance={distance} fused={fused} target={wl.target}")
+        tally = harness.run_rounds(oracle, wl, 4, synth.make_temperature(wl, mode), seed=case, policy=policy,
+                                   distance=distance, fused=fused)
+        assert tally.flagged_divergences <= max(2, tally.decisions // 25), tally
