@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--launch", default="graph", choices=["graph", "eager"],
                     help="graph: the pool's rounds are captured once into a HIP graph (stream capture of the same "
                          "C-ABI calls) and replayed; eager: every call is issued from Python each round")
+    ap.add_argument("--policy", type=int, default=0, help="weight policy (0 softmax of 1/e, 1 static, 2 two-draft grid, 3 random)")
+    ap.add_argument("--distance", type=int, default=0, help="0 KL, 1 total variation")
+    ap.add_argument("--drafts", type=int, default=0, help="override the workload's number of drafts n (2 for --policy 2)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MB",
                     help="only run a plain device copy of MB megabytes 10 times: the known-size kernel against "
                          "which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
@@ -132,11 +135,14 @@ def main():
         return
 
     wl = synth.WORKLOADS[args.workload]
+    if args.drafts:
+        wl = synth.scaled(wl, n=args.drafts)
     device = "cuda:0"
     torch.cuda.set_device(0)
     binding.load()
     Ws, Hs, Ts, temp = gen_inputs(wl, args.pool, args.w_copies, device)
-    cfg = binding.make_cfg(V=wl.V, d=wl.d, n=wl.n, B=wl.B, gamma=wl.gamma, h=wl.h, w_dtype=wl.w_dtype, seed=0)
+    cfg = binding.make_cfg(V=wl.V, d=wl.d, n=wl.n, B=wl.B, gamma=wl.gamma, h=wl.h, w_dtype=wl.w_dtype, seed=0,
+                           policy=args.policy, distance=args.distance)
     buf = binding.RoundBuffers(cfg, device)
 
     upd_first = buf.prepare_update_weights(True)
@@ -271,7 +277,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if wl.w_dtype == 1 else "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: V={wl.V} d={wl.d} n={wl.n} B={wl.B} gamma={wl.gamma} h={wl.h} "
-                               f"temperature={wl.temperature}", "pool_rounds": args.pool, "w_copies": args.w_copies,
+                               f"temperature={wl.temperature} policy={args.policy} distance={args.distance}",
+                   "pool_rounds": args.pool, "w_copies": args.w_copies,
                    "calls_per_step": (2 if args.separate_update else 1) + wl.gamma, "launch": launch,
                    "window_update": "separate call" if args.separate_update else "fused into tabed_verify"},
         "roofline": roofline,

@@ -732,6 +732,13 @@ __global__ __launch_bounds__(kBlock) void k_dist(DistArgs a) {
     float4 tx[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) tx[u] = load4<VEC>(trow, cb + (u * kBlock + tid) * 4, V);
+    float4 yq[2][4];                                   // grid modes: both draft rows, requested up front
+    if (MODE != 0) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) yq[j][u] = load4<VEC>(qbase + (size_t)j * V, cb + (u * kBlock + tid) * 4, V);
+    }
     const float T = a.temperature[b];
     const float invT = (T > 0.f) ? 1.f / T : 1.f;
     if (tid < n) {
@@ -787,31 +794,29 @@ __global__ __launch_bounds__(kBlock) void k_dist(DistArgs a) {
             if (lane == 0) s_sum[wave][j] = t;
         }
     } else {
-        float acc[NC];
+        // both drafts' probabilities of this thread's 16 elements, then one candidate mixture at a time
+        float q0[16], q1[16];
 #pragma unroll
-        for (int k = 0; k < NC; ++k) acc[k] = 0.f;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const float4 y0 = load4<VEC>(qbase, cb + (u * kBlock + tid) * 4, V);
-            const float4 y1 = load4<VEC>(qbase + (size_t)V, cb + (u * kBlock + tid) * 4, V);
+        for (int u = 0; u < 4; ++u)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float a0 = f4get(y0, e), a1 = f4get(y1, e);
-                const float q0 = (a0 > -INFINITY) ? __expf(a0 * invT - s_hi[0]) * s_oml[0] : 0.f;
-                const float q1 = (a1 > -INFINITY) ? __expf(a1 * invT - s_hi[1]) * s_oml[1] : 0.f;
-                const float p = pv[u * 4 + e];
-#pragma unroll
-                for (int k = 0; k < NC; ++k) {
-                    const float w1 = (float)((double)k / (double)(NC - 1)), w0 = (float)(1.0 - (double)k / (double)(NC - 1));
-                    const float mix = w0 * q0 + w1 * q1;
-                    if (MODE == 1) { if (p > 0.f) acc[k] += p * (lp[u * 4 + e] - logf(mix)); }
-                    else acc[k] += fabsf(p - mix);
-                }
+                const float a0 = f4get(yq[0][u], e), a1 = f4get(yq[1][u], e);
+                q0[u * 4 + e] = (a0 > -INFINITY) ? __expf(a0 * invT - s_hi[0]) * s_oml[0] : 0.f;
+                q1[u * 4 + e] = (a1 > -INFINITY) ? __expf(a1 * invT - s_hi[1]) * s_oml[1] : 0.f;
             }
-        }
-#pragma unroll
         for (int k = 0; k < NC; ++k) {
-            const double t = wave_sum((double)acc[k]);
+            const float w1 = (float)k / (float)(NC - 1), w0 = 1.f - w1;
+            float acc = 0.f;
+#pragma unroll
+            for (int x = 0; x < 16; ++x) {
+                const float mix = w0 * q0[x] + w1 * q1[x];
+                // bare v_log_f32 (log2): its ~1e-7 relative error is random per element and averages out under
+                // sum p (..); a mixture below the normal range only occurs where p is negligible too
+                if (MODE == 1) acc += (pv[x] > 0.f) ? pv[x] * (lp[x] * 1.44269504f - __builtin_amdgcn_logf(fmaxf(mix, 1e-37f))) : 0.f;
+                else acc += fabsf(pv[x] - mix);
+            }
+            if (MODE == 1) acc *= 0.693147181f;            // back from log2 to natural log
+            const double t = wave_sum((double)acc);
             if (lane == 0) s_sum[wave][k] = t;
         }
     }
