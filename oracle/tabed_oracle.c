@@ -20,7 +20,8 @@
  *     tau = 1, and the two-draft policy that scores the fixed candidates
  *     w^c = [1 - c/10, c/10] by the accumulated distance of the MIXTURE
  *     q(.; w^c) from the target and takes the arg-min (Alg. 1 line 3);
- *     Sec. 4.1 last paragraph: TVD as the alternative distance.
+ *     Sec. 4.1 last paragraph: TVD as the alternative distance; Sec. 4.1:
+ *     selection by hard labels (token matches) instead of soft labels.
  *   - Eq. 1: speedup = block_eff / (gamma * Tq/Tp + 1).
  *
  * Notation: n = number of drafting methods (the paper's m), B independent
@@ -320,6 +321,8 @@ void oracle_verify(int V, int n, int B, int gamma, int distance, int n_cand,
         double* mixlog = (double*)malloc((size_t)V * sizeof(double));
         uint8_t* fl = flags + (size_t)b * (gamma + 1);
         for (int i = 0; i <= gamma; ++i) fl[i] = 0;
+        /* hard labels (distance 2): arg-max token of every candidate distribution at every position */
+        int* pred = (int*)malloc((size_t)gamma * 64 * sizeof(int));
 
         int k = 0, rejected = 0;
         for (int i = 0; i < gamma; ++i) {
@@ -329,6 +332,7 @@ void oracle_verify(int V, int n, int B, int gamma, int distance, int n_cand,
                 const float* Lq = draft_logits + (((size_t)i * B + b) * n + j) * V;
                 oracle_softmax(Lq, V, T_eff, q + (size_t)j * V, logq + (size_t)j * V);
                 if (n_cand > 0) continue;
+                if (distance == 2) { pred[i * 64 + j] = oracle_argmax(q + (size_t)j * V, V, NULL); continue; }
                 double D = distance == 0 ? oracle_kl(p, logp, logq + (size_t)j * V, V)
                                          : oracle_tvd(p, q + (size_t)j * V, V);
                 dev[((size_t)b * gamma + i) * DW + j] = (float)D;
@@ -339,6 +343,7 @@ void oracle_verify(int V, int n, int B, int gamma, int distance, int n_cand,
                     f[v] = w0 * q[v] + w1 * q[(size_t)V + v];
                     mixlog[v] = log(f[v]);
                 }
+                if (distance == 2) { pred[i * 64 + c] = oracle_argmax(f, V, NULL); continue; }
                 double D = distance == 0 ? oracle_kl(p, logp, mixlog, V) : oracle_tvd(p, f, V);
                 dev[((size_t)b * gamma + i) * DW + c] = (float)D;
             }
@@ -397,7 +402,20 @@ void oracle_verify(int V, int n, int B, int gamma, int distance, int n_cand,
         for (int i = k + 1; i <= gamma; ++i) out_tokens[(size_t)b * (gamma + 1) + i] = -1;
         accept_len[b] = k;
         n_valid[b] = k + 1 < gamma ? k + 1 : gamma;
-        free(p); free(logp); free(q); free(logq); free(f); free(mixlog);
+        if (distance == 2) {
+            /* reading: the hard label of a verified position is the token emitted there (accepted draft token,
+             * or the corrected token at the rejected position); "matches sampled from q^j" is taken as the
+             * arg-max of the candidate distribution; the distance is the mismatch indicator, so that the
+             * window sum counts mismatches and its arg-min maximises matches.  Positions beyond the rejected
+             * one have no label: 1. */
+            const int DW = oracle_dev_width(n, n_cand);
+            for (int i = 0; i < gamma; ++i)
+                for (int c = 0; c < DW; ++c) {
+                    const int label = i <= k ? out_tokens[(size_t)b * (gamma + 1) + i] : -1;
+                    dev[((size_t)b * gamma + i) * DW + c] = (pred[i * 64 + c] == label) ? 0.0f : 1.0f;
+                }
+        }
+        free(p); free(logp); free(q); free(logq); free(f); free(mixlog); free(pred);
     }
 }
 

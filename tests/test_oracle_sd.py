@@ -452,3 +452,36 @@ def test_random_weights_are_uniform_on_the_simplex(oracle):
                               ring=np.zeros((2, h, n), np.float32), ring_head=np.zeros(2, np.int32),
                               ring_count=np.zeros(2, np.int32), seed=10, rnd=7)
     assert not np.array_equal(a, b)
+
+
+def test_hard_label_distance_counts_token_mismatches(oracle):
+    """distance 2: 1 where the arg-max of a candidate distribution differs from the token emitted at that
+    position, 0 where it matches; positions after the rejected one carry no label."""
+    rng = np.random.default_rng(51)
+    V, gamma = 40, 4
+    for n_cand, n in ((0, 3), (11, 2)):
+        for trial in range(12):
+            w = rng.dirichlet(np.ones(n)).astype(np.float32)
+            logq, logp, p, q, qj = _dists(rng, gamma, n, V, w)
+            for i in range(trial % (gamma + 1)):                       # make the target agree on a prefix
+                logp[i, int(np.argmax(q[i]))] = logp[i].max() + 2
+            W = _identity_head(V)
+            dl = np.ascontiguousarray(logq.astype(np.float32)[:, None])
+            temp = np.zeros(1, np.float32)                             # greedy: emitted tokens are arg-maxes
+            tok = np.array([[int(np.argmax(q[i])) for i in range(gamma)]], np.int32)
+            out = oracle.verify(V=V, n=n, B=1, gamma=gamma, distance=2, seed=0, rnd=0, n_cand=n_cand,
+                                target_logits=logp.astype(np.float32)[None], draft_logits=dl, draft_tokens=tok,
+                                draft_q=np.ones((1, gamma), np.float32), weights=w[None], temperature=temp)
+            k = int(out["accept_len"][0])
+            cands = [qj[:, j] for j in range(n)] if n_cand == 0 else \
+                    [(1 - c / 10) * qj[:, 0] + (c / 10) * qj[:, 1] for c in range(11)]
+            for i in range(gamma):
+                for c, dist in enumerate(cands):
+                    want = 1.0 if i > k else float(int(np.argmax(dist[i])) != int(out["out_tokens"][0, i]))
+                    assert out["dev"][0, i, c] == want, (n_cand, trial, i, c)
+    # with the grid policy the window then prefers the candidate with the most matches
+    ring = np.zeros((1, 8, 11), np.float32); head = np.zeros(1, np.int32); count = np.zeros(1, np.int32)
+    dev = np.ones((1, 3, 11), np.float32); dev[0, :, 6] = 0; dev[0, 0, 2] = 0
+    wts = oracle.update_weights(n=2, B=1, gamma=3, h=8, policy=2, tau_w=1.0, eps=1e-6, dev=dev,
+                                n_valid=np.array([3], np.int32), ring=ring, ring_head=head, ring_count=count)
+    np.testing.assert_allclose(wts[0], [0.4, 0.6], atol=1e-7)
