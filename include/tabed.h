@@ -79,7 +79,9 @@ typedef struct tabed_cfg {
     int32_t h;        /* observation window length in verified positions, >= 1; 0 = ALL    */
                       /* positions since the start (the paper's default, App. B.1)         */
     int32_t w_dtype;  /* storage type of W and H: 0 = fp32, 1 = bf16                       */
-    int32_t distance; /* D of Alg. 1: 0 = KL(p || q) (Sec. 4.1); 1 = total variation       */
+    int32_t distance; /* D of Alg. 1: 0 = KL(p || q) (Sec. 4.1); 1 = total variation;      */
+                      /* 2 = hard labels: 1 where the candidate's arg-max token differs    */
+                      /*     from the token emitted at the position, else 0                */
     int32_t policy;   /* 0 = softmax(1/e; tau_w) (App. B.2); 1 = static equal weights;     */
                       /* 2 = two-draft grid (App. B.2): arg-min over w^c = [1-c/10, c/10], */
                       /*     c = 0..10, of the window sum of D(p, mixture); needs n = 2;   */

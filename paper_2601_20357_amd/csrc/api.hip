@@ -19,7 +19,7 @@ int validate_cfg(const tabed_cfg* c) {
     if (c->n > TABED_MAX_N || c->gamma > TABED_MAX_GAMMA) return TABED_ERANGE;
     if (c->w_dtype != 0 && c->w_dtype != 1) return TABED_EINVAL;
     if (c->w_dtype == 1 && (c->d % 8) != 0) return TABED_EINVAL;
-    if (c->distance != 0 && c->distance != 1) return TABED_EINVAL;
+    if (c->distance < 0 || c->distance > 2) return TABED_EINVAL;
     if (c->policy < 0 || c->policy > 3) return TABED_EINVAL;
     if (c->policy == 2 && c->n != 2) return TABED_EINVAL;
     if (!(c->tau_w > 0.f) || !(c->eps > 0.f)) return TABED_EINVAL;
@@ -48,7 +48,7 @@ WsLayout ws_layout(const tabed_cfg& c) {
     L.off_stats = off;   off = align_up(off + sizeof(double) * (size_t)c.B * (c.gamma + 1) * L.C3max * L.RS);
     L.off_seg = off;     off = align_up(off + sizeof(double) * 2 * (size_t)c.B * L.NSEG);
     L.off_wstage = off;  off = align_up(off + sizeof(float) * (size_t)c.B * c.n);
-    L.off_dist = off;    off = align_up(off + sizeof(double) * (size_t)c.B * c.gamma * L.DW * L.Cd);
+    L.off_dist = off;    off = align_up(off + sizeof(double) * 2 * (size_t)c.B * c.gamma * L.DW * L.Cd);
     L.total = off;
     return L;
 }

@@ -38,7 +38,7 @@ struct WsLayout {
     size_t off_stats;    // double [B][gamma+1][C3max][RS]
     size_t off_seg;      // double [B][2][NSEG] segment masses: residual, target
     size_t off_wstage;   // float [B][n] next weights staged by the fused window update
-    size_t off_dist;     // double [B][gamma][DW][Cd] chunk sums of the second-pass distances (TVD, grid policy)
+    size_t off_dist;     // double [B][gamma][DW][Cd][2] chunk sums, or chunk arg-maxes (value, index), of the second pass
     size_t total;
 };
 WsLayout ws_layout(const tabed_cfg& c);

@@ -705,7 +705,10 @@ __global__ __launch_bounds__(kBlock) void k_stats(StatsArgs a) {
 //   MODE 0: |p - q_j|                         per draft j                (TVD, DW = n)
 //   MODE 1: p (log p - log mix_c)             per candidate c = 0..10    (KL of the mixtures, n = 2)
 //   MODE 2: |p - mix_c|                       per candidate c            (TVD of the mixtures, n = 2)
-// with mix_c = (1 - c/10) q_1 + (c/10) q_2.  Chunk sums go to dist[b][i][c][chunk]; k_finish adds them.
+//   MODE 3: arg-max_v q_j(v)                  per draft j                (hard labels; needs no target row)
+//   MODE 4: arg-max_v mix_c(v)                per candidate c            (hard labels, n = 2)
+// with mix_c = (1 - c/10) q_1 + (c/10) q_2.  Chunk sums go to dist[b][i][c][chunk][0] (k_finish adds them);
+// chunk arg-maxes go to dist[b][i][c][chunk][0..1] as (value, index), lowest index on ties.
 // =====================================================================================================
 struct DistArgs {
     int V, n, B, gamma, C3, RS, DW, Cd;
@@ -725,10 +728,76 @@ __global__ __launch_bounds__(kBlock) void k_dist(DistArgs a) {
     __shared__ double s_lse;
     __shared__ float s_hi[TABED_MAX_N], s_oml[TABED_MAX_N];
     __shared__ double s_sum[kWavesPerBlock][TABED_MAX_N];
+    __shared__ ArgMax s_amx[kWavesPerBlock][TABED_MAX_N];
 
     const float* trow = a.target + ((size_t)b * (gamma + 1) + i) * V;
     const float* qbase = a.dlogits + (((size_t)i * a.B + b) * n) * V;
     const int cb = c * kChunkV;
+    if (MODE >= 3) {
+        // ---- hard labels: arg-max of every candidate distribution over this chunk
+        const float T3 = a.temperature[b];
+        const float invT3 = (T3 > 0.f) ? 1.f / T3 : 1.f;
+        if (MODE == 3) {
+            for (int j = 0; j < n; ++j) {                  // softmax is monotone: the arg-max of the raw logits
+                ArgMax am{-INFINITY, 0x7fffffff};
+                float4 y[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) y[u] = load4<VEC>(qbase + (size_t)j * V, cb + (u * kBlock + tid) * 4, V);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int v = cb + (u * kBlock + tid) * 4 + e;
+                        if (v < V) am = argmax_merge(am, ArgMax{f4get(y[u], e), v});
+                    }
+                am = wave_argmax(am);
+                if (lane == 0) s_amx[wave][j] = am;
+            }
+        } else {
+            if (tid < 2) {
+                const double l = a.dlse[((size_t)i * a.B + b) * n + tid];
+                const float hi = (float)l;
+                s_hi[tid] = hi;
+                s_oml[tid] = (float)(1.0 - (l - (double)hi));
+            }
+            float4 y0[4], y1[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                y0[u] = load4<VEC>(qbase, cb + (u * kBlock + tid) * 4, V);
+                y1[u] = load4<VEC>(qbase + (size_t)V, cb + (u * kBlock + tid) * 4, V);
+            }
+            __syncthreads();
+            float q0[16], q1[16];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float a0 = f4get(y0[u], e), a1 = f4get(y1[u], e);
+                    q0[u * 4 + e] = (a0 > -INFINITY) ? __expf(a0 * invT3 - s_hi[0]) * s_oml[0] : 0.f;
+                    q1[u * 4 + e] = (a1 > -INFINITY) ? __expf(a1 * invT3 - s_hi[1]) * s_oml[1] : 0.f;
+                }
+            for (int k = 0; k < NC; ++k) {
+                const float w1 = (float)k / (float)(NC - 1), w0 = 1.f - w1;
+                ArgMax am{-INFINITY, 0x7fffffff};
+#pragma unroll
+                for (int x = 0; x < 16; ++x) {
+                    const int v = cb + ((x >> 2) * kBlock + tid) * 4 + (x & 3);
+                    if (v < V) am = argmax_merge(am, ArgMax{w0 * q0[x] + w1 * q1[x], v});
+                }
+                am = wave_argmax(am);
+                if (lane == 0) s_amx[wave][k] = am;
+            }
+        }
+        __syncthreads();
+        if (tid < a.DW) {
+            ArgMax t = s_amx[0][tid];
+            for (int w = 1; w < kWavesPerBlock; ++w) t = argmax_merge(t, s_amx[w][tid]);
+            double* rec = a.dist + ((((size_t)b * gamma + i) * a.DW + tid) * a.Cd + c) * 2;
+            rec[0] = (double)t.v;
+            rec[1] = (double)t.i;
+        }
+        return;
+    }
     float4 tx[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) tx[u] = load4<VEC>(trow, cb + (u * kBlock + tid) * 4, V);
@@ -822,7 +891,7 @@ __global__ __launch_bounds__(kBlock) void k_dist(DistArgs a) {
     }
     __syncthreads();
     if (tid < a.DW)
-        a.dist[(((size_t)b * gamma + i) * a.DW + tid) * a.Cd + c] =
+        a.dist[((((size_t)b * gamma + i) * a.DW + tid) * a.Cd + c) * 2] =
             (s_sum[0][tid] + s_sum[1][tid]) + (s_sum[2][tid] + s_sum[3][tid]);
 }
 
@@ -876,6 +945,7 @@ struct FinishArgs {
     const double* dist;   // [B][gamma][DW][Cd] second-pass chunk sums, or nullptr (KL from the records)
     int DW, Cd;
     float dist_scale;     // 0.5 for total variation, 1 for KL
+    int hard;             // 1: dist holds chunk arg-maxes and the distance is the token-mismatch indicator
     int fuse;             // 1: the call also advances every sequence's window and writes the next weights
     WindowArgs win;
     float* wstage;        // [B][n] next weights, staged until every workgroup of the sequence has arrived
@@ -960,6 +1030,13 @@ __device__ __forceinline__ void resid_eval(const ResidRow& r, int n, int V, cons
         }
 }
 
+// Arg-max over the chunk arg-maxes of one (position, candidate): records are (value, index) pairs.
+__device__ __forceinline__ int hard_pred(const double* rec, int Cd) {
+    ArgMax am{-INFINITY, 0x7fffffff};
+    for (int cc = 0; cc < Cd; ++cc) am = argmax_merge(am, ArgMax{(float)rec[cc * 2], (int)rec[cc * 2 + 1]});
+    return am.i;
+}
+
 template <bool VEC, int N>
 __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
     extern __shared__ __attribute__((aligned(16))) double s_scale[];   // [gamma+1][C3]: exp(m_c - m_row)
@@ -975,6 +1052,7 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
     __shared__ int s_last, s_first[kWavesPerBlock], s_lastw[kWavesPerBlock], s_seg;
     __shared__ double s_prefix;
     __shared__ double s_wpart[64], s_wx[TABED_MAX_N];    // fused window update (one wave)
+    __shared__ int s_y[TABED_MAX_GAMMA];                 // drafted tokens (hard labels)
 
     // ---- everything that does not depend on another load is requested first
     int y = -1;
@@ -983,6 +1061,7 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
         y = a.dtok[(size_t)b * gamma + tid];
         uacc = a.u_acc ? a.u_acc[(size_t)b * gamma + tid] : tabed_uniform(a.seed, a.round, (uint32_t)b, (uint32_t)tid, 1);
         qy = a.dq[(size_t)b * gamma + tid];
+        s_y[tid] = y;
     }
     for (int q = tid; q < gamma * n; q += kBlock) {      // draft log-sum-exps of every position, split hi + lo
         const double l = a.dlse[((size_t)(q / n) * a.B + b) * n + (q % n)];
@@ -1117,13 +1196,24 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
                 const double kl = A / s_rowZ[ii] - s_rowlse[ii] + a.dlse[((size_t)ii * a.B + b) * n + j];
                 publish_store(&a.dev[((size_t)b * gamma + ii) * n + j], (float)kl);
             }
-        } else {
+        } else if (!a.hard) {
             // ---- distances from the second pass: add the chunk sums in chunk order
             for (int q = tid; q < gamma * a.DW; q += kBlock) {
-                const double* r0 = a.dist + ((size_t)b * gamma * a.DW + q) * a.Cd;
+                const double* r0 = a.dist + ((size_t)b * gamma * a.DW + q) * a.Cd * 2;
                 double D = 0.0;
-                for (int cc = 0; cc < a.Cd; ++cc) D += r0[cc];
+                for (int cc = 0; cc < a.Cd; ++cc) D += r0[cc * 2];
                 publish_store(&a.dev[(size_t)b * gamma * a.DW + q], (float)((double)a.dist_scale * D));
+            }
+        } else {
+            // ---- hard labels: 1 where a candidate's arg-max differs from the token emitted at the position.
+            //      The label of the rejected position of a sampling row is the corrected token, which only
+            //      the sampler's last workgroup knows: that entry is written there.
+            for (int q = tid; q < gamma * a.DW; q += kBlock) {
+                const int ii = q / a.DW;
+                if (ii == k && !greedy) continue;
+                const int label = ii < k ? s_y[ii] : (ii == k ? s_rowam[k] : -1);
+                publish_store(&a.dev[(size_t)b * gamma * a.DW + q],
+                              hard_pred(a.dist + ((size_t)b * gamma * a.DW + q) * a.Cd * 2, a.Cd) == label ? 0.f : 1.f);
             }
         }
         if (tid <= gamma) {
@@ -1156,7 +1246,7 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
     if (book) {
         // window + next weights, off the critical path of the sampler.  The weights are staged: the buffer
         // they go to may be the one the siblings are still reading this block's weights from.
-        if (a.fuse) {
+        if (a.fuse && !a.hard) {
             __syncthreads();                               // the distances above are acknowledged
             if (tid < kWave) {
                 WindowArgs wa = a.win;
@@ -1177,7 +1267,18 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
     if (tid == 0) s_last = arrive(&a.tickets[b], (uint32_t)(a.C5 + 1)) ? 1 : 0;
     __syncthreads();
     if (!s_last) return;
-    if (a.fuse && tid < n) a.win.weights[(size_t)b * n + tid] = published_load(&a.wstage[(size_t)b * n + tid]);
+    if (a.fuse && !a.hard && tid < n) a.win.weights[(size_t)b * n + tid] = published_load(&a.wstage[(size_t)b * n + tid]);
+    // hard labels: the rejected position's distances and the window update wait for the corrected token
+    auto finish_hard = [&](int tok) {                      // wave 0 only
+        if (k < gamma)
+            for (int cidx = lane; cidx < a.DW; cidx += kWave)
+                publish_store(&a.dev[((size_t)b * gamma + k) * a.DW + cidx],
+                              hard_pred(a.dist + (((size_t)b * gamma + k) * a.DW + cidx) * a.Cd * 2, a.Cd) == tok ? 0.f : 1.f);
+        if (a.fuse) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's published distances are acknowledged
+            window_update<true>(a.win, b, lane, a.dev, nv_k, s_wpart, s_wx);
+        }
+    };
 
     // ---- last workgroup of sequence b: locate the segment, then the token
     const int S = (NSEG + kBlock - 1) / kBlock;
@@ -1202,6 +1303,7 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
             a.out_tokens[out_idx] = 0;
             a.flags[out_idx] = (uint8_t)(flag | TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE);
         }
+        if (a.hard && tid < kWave) finish_hard(0);
         return;
     }
     if (tid == owner) {
@@ -1249,6 +1351,11 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
         a.out_tokens[out_idx] = tok < V ? tok : V - 1;
         a.flags[out_idx] = (uint8_t)flag;
     }
+    if (a.hard) {
+        const int e = cross ? hit : (live ? lastlive : 0);
+        const int mine = (v + e < V) ? v + e : V - 1;
+        finish_hard(__builtin_amdgcn_readlane(mine, pick));
+    }
 }
 
 hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round,
@@ -1258,7 +1365,7 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
                          int32_t* out_tokens, float* dev, int32_t* n_valid, uint8_t* flags, float* ring,
                          int32_t* ring_head, int32_t* ring_count, float* next_weights, hipStream_t s) {
     const bool vec = (c.V % 4 == 0);
-    const bool second_pass = (c.distance == 1 || c.policy == 2);   // distances that need lse_p before the pass
+    const bool second_pass = (c.distance != 0 || c.policy == 2);   // distances that take a pass of their own
     const int ncomp = (vec && (c.n == 2 || c.n == 4 || c.n == 8)) ? c.n : 0;   // compile-time draft counts
     const int U = pick_stats_unroll(c, ncomp == 8 ? 2 : 4);
     const int C3 = (c.V + kBlock * 4 * U - 1) / (kBlock * 4 * U);
@@ -1284,15 +1391,19 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
             d.stats = a.stats;
             d.dist = reinterpret_cast<double*>(ws + L.off_dist);
             const dim3 gd(L.Cd, c.gamma, c.B);
-            const int mode = (c.policy != 2) ? 0 : (c.distance == 0 ? 1 : 2);
+            const int mode = (c.distance == 2) ? (c.policy != 2 ? 3 : 4) : (c.policy != 2) ? 0 : (c.distance == 0 ? 1 : 2);
             if (vec) {
                 if (mode == 0) launch(&prof, k_dist<true, 0>, gd, dim3(kBlock), 0, s, d);
                 else if (mode == 1) launch(&prof, k_dist<true, 1>, gd, dim3(kBlock), 0, s, d);
-                else launch(&prof, k_dist<true, 2>, gd, dim3(kBlock), 0, s, d);
+                else if (mode == 2) launch(&prof, k_dist<true, 2>, gd, dim3(kBlock), 0, s, d);
+                else if (mode == 3) launch(&prof, k_dist<true, 3>, gd, dim3(kBlock), 0, s, d);
+                else launch(&prof, k_dist<true, 4>, gd, dim3(kBlock), 0, s, d);
             } else {
                 if (mode == 0) launch(&prof, k_dist<false, 0>, gd, dim3(kBlock), 0, s, d);
                 else if (mode == 1) launch(&prof, k_dist<false, 1>, gd, dim3(kBlock), 0, s, d);
-                else launch(&prof, k_dist<false, 2>, gd, dim3(kBlock), 0, s, d);
+                else if (mode == 2) launch(&prof, k_dist<false, 2>, gd, dim3(kBlock), 0, s, d);
+                else if (mode == 3) launch(&prof, k_dist<false, 3>, gd, dim3(kBlock), 0, s, d);
+                else launch(&prof, k_dist<false, 4>, gd, dim3(kBlock), 0, s, d);
             }
             e = hipGetLastError();
             if (e != hipSuccess) return e;
@@ -1306,7 +1417,7 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
     a.weights = weights; a.temperature = temperature; a.u_acc = u_acc; a.u_res = u_res;
     a.stats = reinterpret_cast<const double*>(ws + L.off_stats);
     a.dist = second_pass ? reinterpret_cast<const double*>(ws + L.off_dist) : nullptr;
-    a.DW = L.DW; a.Cd = L.Cd; a.dist_scale = (c.distance == 1) ? 0.5f : 1.f;
+    a.DW = L.DW; a.Cd = L.Cd; a.dist_scale = (c.distance == 1) ? 0.5f : 1.f; a.hard = (c.distance == 2) ? 1 : 0;
     a.fuse = (ring != nullptr) ? 1 : 0;
     a.win = window_args(c, round + 1, ring, ring_head, ring_count, next_weights);   // the weights of the NEXT round
     a.wstage = reinterpret_cast<float*>(ws + L.off_wstage);

@@ -121,7 +121,7 @@ class Tally:
                 f"max|ddev|={self.max_dev_err:.2e} max|dw|={self.max_w_err:.2e}")
 
 
-def compare_round(g, o, wl, tally: Tally, check_logits=True):
+def compare_round(g, o, wl, tally: Tally, check_logits=True, hard=False):
     """Element-by-element comparison of one round.  Returns True if every sequence stayed in lock-step;
     False if a flagged decision diverged (the caller then resyncs the window state)."""
     B, n, gamma = wl.B, wl.n, wl.gamma
@@ -147,11 +147,13 @@ def compare_round(g, o, wl, tally: Tally, check_logits=True):
             rel = abs(float(g["draft_q"][b, pos]) - float(o["draft_q"][b, pos])) / max(float(o["draft_q"][b, pos]), 1e-30)
             tally.max_q_rel = max(tally.max_q_rel, rel)
             assert rel <= 1e-5, (b, pos, g["draft_q"][b, pos], o["draft_q"][b, pos])
-        # distances do not depend on any decision: always comparable
+        # KL / TVD distances do not depend on any decision: always comparable.  Hard-label distances depend on
+        # the emitted tokens: they are compared below, once the sequence is known to be in lock-step.
         d_g, d_o = g["dev"][b], o["dev"][b]
-        derr = np.abs(d_g - d_o)
-        tally.max_dev_err = max(tally.max_dev_err, float(derr.max()))
-        assert np.all(derr <= 1e-5 * np.abs(d_o) + 1e-6), (b, d_g, d_o)
+        if not hard:
+            derr = np.abs(d_g - d_o)
+            tally.max_dev_err = max(tally.max_dev_err, float(derr.max()))
+            assert np.all(derr <= 1e-5 * np.abs(d_o) + 1e-6), (b, d_g, d_o)
         if not alive:
             lock = False
             continue
@@ -172,7 +174,11 @@ def compare_round(g, o, wl, tally: Tally, check_logits=True):
             flagged = (g["flags"][b, ko] | o["flags"][b, ko]) & binding.FLAG_SAMPLE_MARGIN
             assert flagged, f"unflagged emitted-token mismatch b={b} k={ko}: {g['out_tokens'][b]} vs {o['out_tokens'][b]}"
             tally.flagged_divergences += 1
-            # the emitted token does not enter the window state: still in lock-step
+            # the emitted token does not enter the window state (unless it is a hard label): still in lock-step
+            if hard:
+                lock = False
+        elif hard:
+            assert np.array_equal(d_g, d_o), (b, d_g, d_o)       # mismatch indicators: exact
     return lock
 
 
@@ -188,6 +194,6 @@ def run_rounds(oracle, wl, rounds, temp, seed=0, policy=0, check_logits=True, un
         u = uniforms(rnd) if uniforms else {}
         o = orc.round(rnd, W, H, target, temp, **u)
         g = gpu.round(rnd, W_t, H, target, temp, **u)
-        if not compare_round(g, o, wl, tally, check_logits):
+        if not compare_round(g, o, wl, tally, check_logits, hard=(distance == 2)):
             gpu.resync_from(orc)
     return tally

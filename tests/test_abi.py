@@ -56,7 +56,7 @@ def test_workspace_bytes_and_cfg_validation(lib):
     assert binding.tabed_workspace_bytes(good_cfg()) > 2 * 64 * 1000 * 4
     assert binding.tabed_workspace_bytes(good_cfg(V=1, d=8, n=1, B=1, gamma=1, h=1)) > 0
     for bad in (dict(V=0), dict(n=0), dict(n=17), dict(gamma=0), dict(gamma=33), dict(h=-1), dict(B=0),
-                dict(d=100), dict(w_dtype=2), dict(tau_w=0.0), dict(eps=0.0), dict(policy=4), dict(distance=7),
+                dict(d=100), dict(w_dtype=2), dict(tau_w=0.0), dict(eps=0.0), dict(policy=4), dict(distance=3),
                 dict(policy=2)):                      # the grid policy is defined for two drafts only
         assert binding.tabed_workspace_bytes(good_cfg(**bad)) == 0, bad
     assert binding.tabed_workspace_bytes(good_cfg(d=100, w_dtype=0)) > 0      # fp32 storage has no d % 8 rule

@@ -80,8 +80,8 @@ def test_static_policy_and_other_tau(oracle):
 
 
 # ------------------------------------------------------------------ total variation distance and the two-draft grid policy
-@pytest.mark.parametrize("policy,distance,n", [(0, 1, 4), (2, 0, 2), (2, 1, 2), (1, 1, 3), (3, 0, 5)],
-                         ids=["tvd", "grid-kl", "grid-tvd", "static-tvd", "random-weights"])
+@pytest.mark.parametrize("policy,distance,n", [(0, 1, 4), (2, 0, 2), (2, 1, 2), (1, 1, 3), (3, 0, 5), (2, 2, 2), (0, 2, 4)],
+                         ids=["tvd", "grid-kl", "grid-tvd", "static-tvd", "random-weights", "grid-hard", "hard"])
 def test_distance_and_policy_variants(oracle, policy, distance, n):
     for V, d, B, mode in ((4100, 64, 5, "mixed07"), (4099, 72, 3, "one"), (32000, 768, 4, "one")):
         wl = synth.scaled(SERVING, V=V, d=d, n=n, B=B, gamma=3, h=5, cfg_id=70 + policy * 2 + distance)
@@ -92,8 +92,10 @@ def test_distance_and_policy_variants(oracle, policy, distance, n):
 
 
 @pytest.mark.parametrize("policy,distance,n,h,mode", [(0, 0, 4, 8, "one"), (0, 0, 3, 5, "mixed07"), (2, 1, 2, 0, "one"),
-                                                        (0, 0, 4, 0, "greedy"), (3, 0, 16, 4, "mixed07")],
-                         ids=["softmax", "mixed-rows", "grid-tvd-all", "greedy-all", "random-16-drafts"])
+                                                        (0, 0, 4, 0, "greedy"), (3, 0, 16, 4, "mixed07"), (2, 2, 2, 6, "mixed07"),
+                                                        (2, 2, 2, 0, "greedy")],
+                         ids=["softmax", "mixed-rows", "grid-tvd-all", "greedy-all", "random-16-drafts", "grid-hard-mixed",
+                              "grid-hard-greedy"])
 def test_verify_with_fused_window_update(oracle, policy, distance, n, h, mode):
     """tabed_verify given the window pointers must leave the same window and next weights as the separate
     tabed_update_weights call the oracle models."""
@@ -300,7 +302,7 @@ def test_seeded_sweep_of_small_shapes(oracle):
         d = int(rng.choice([8, 24, 64, 72, 128, 256, 512] if w_dtype else [5, 8, 33, 64]))
         policy = int(rng.choice([0, 0, 0, 1, 2, 3]))
         n = 2 if policy == 2 else int(rng.integers(1, 10))
-        distance = int(rng.integers(0, 2))
+        distance = int(rng.integers(0, 3))
         B = int(rng.integers(1, 23))
         wl = synth.scaled(SERVING, V=int(rng.integers(1, 9000)), d=d, n=n, B=B, gamma=int(rng.integers(1, 7)),
                           h=int(rng.integers(0, 9)), w_dtype=w_dtype, cfg_id=200 + case,
