@@ -194,33 +194,41 @@ def main():
     if launch == "graph" and args.steps % args.pool != 0:
         launch = "eager"                      # a replay is one pass over the pool: steps must be a multiple of it
     if launch == "graph":
-        # Capture one pass over the pool (pool x (2 + gamma) C-ABI calls = pool x 13 kernels) on a side stream
-        # and replay it: the library enqueues only kernels (no memset, no allocation, no sync), so the same
-        # calls are capturable as they are.  The round counter of a captured call is fixed, so the Philox
-        # uniforms repeat with the pool, like the inputs do; the window state still evolves across replays.
-        import ctypes as C
-        side = torch.cuda.Stream()
-        every = [upd, upd_first] + [c for drafts, ver in slots for c in drafts + [ver]]
-        for c in every:
-            c.args[-1] = C.c_void_p(side.cuda_stream)
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            for _ in range(args.pool):
-                step()                        # once eagerly on the side stream
-            side.synchronize()
-            with torch.cuda.graph(graph, stream=side):
+        try:
+            # Capture one pass over the pool (pool x (1 + gamma) C-ABI calls, two kernels each) on a side stream
+            # and replay it: the library enqueues only kernels (no memset, no allocation, no sync), so the same
+            # calls are capturable as they are.  The round counter of a captured call is fixed, so the Philox
+            # uniforms repeat with the pool, like the inputs do; the window state still evolves across replays.
+            import ctypes as C
+            side = torch.cuda.Stream()
+            every = [upd, upd_first] + [c for drafts, ver in slots for c in drafts + [ver]]
+            for c in every:
+                c.args[-1] = C.c_void_p(side.cuda_stream)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
                 for _ in range(args.pool):
-                    step()
-        torch.cuda.synchronize()
-        graph.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps // args.pool):
+                    step()                        # once eagerly on the side stream
+                side.synchronize()
+                with torch.cuda.graph(graph, stream=side):
+                    for _ in range(args.pool):
+                        step()
+            torch.cuda.synchronize()
             graph.replay()
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        for c in every:                       # back to the default stream for the instrumented pass
-            c.args[-1] = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps // args.pool):
+                graph.replay()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            for c in every:                       # back to the default stream for the instrumented pass
+                c.args[-1] = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        except Exception as exc:                   # a capture that fails must not cost the measurement
+            import ctypes as C
+            for c in [upd, upd_first] + [c for drafts, ver in slots for c in drafts + [ver]]:
+                c.args[-1] = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            launch = f"eager (graph capture failed: {type(exc).__name__})"
+            dt = timed(args.steps)
     else:
         dt = timed(args.steps)
     ms_per_step = dt / args.steps * 1e3
