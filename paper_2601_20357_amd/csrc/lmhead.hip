@@ -189,27 +189,30 @@ __global__ __launch_bounds__(kBlock) void k_lmhead_bf16(int M, int d, int V, int
     store_tile_32x32(acc, m0 + wm * 32, v0 + wn * 32, M, V, NT, s_invt, m0, L, pm, ps);
 }
 
-// ---------------------------------------------------------------- bf16, skinny M (<= 64 rows): W-streaming kernel
-// With n*B <= 64 rows the GEMM moves 2*d bytes of W per n*B*2*d flops: it is bound by streaming W from HBM
-// once, not by the matrix cores.  Design:
-//   * 8 waves per workgroup, one workgroup per compute unit.  All of H (<= 64 x d bf16) is staged once into
-//     LDS (rows padded by 16 bytes, so the 16-byte A-operand reads of 16 consecutive rows hit distinct banks).
-//   * A pair of waves owns one 32-row vocabulary tile; each wave of the pair takes one half of K.  The whole
-//     half-tile of W (KH k-blocks of 32 rows x 128 bytes) is requested up front with coalesced 16-byte loads
-//     (8 lanes cover one row's 128 bytes), so a wave keeps KH*4 KB in flight -- that, not occupancy, is what
-//     saturates HBM.  W is read exactly once; no wave shares W with another.
-//   * The MFMA B operand wants "lane = vocabulary row, 8 consecutive k": each k-block goes through a
-//     wave-private 32 x 144-byte LDS patch that only re-maps lanes (write coalesced layout, read operand
-//     layout); LDS ops of one wave execute in order, so the patch needs no barrier.
-//   * The two K-halves meet through the same patches (one workgroup barrier), each wave finishing one 32-row
-//     block of the 64 x 32 result: logits store + softmax partials of the tile.
-// KH = k-blocks (of 64) per wave = d / 128; MT = 32-row blocks of M (1 or 2).
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global
-// load (vmcnt(0)); here that would stall the kernel until all of W has arrived.
+// load (vmcnt(0)); in the streaming kernels below that would stall a workgroup until all of its W requests
+// have landed.
 __device__ __forceinline__ void lds_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// ---------------------------------------------------------------- bf16, skinny M (<= 64 rows): W-streaming kernel
+// With n*B <= 64 rows the GEMM moves 2*d bytes of W per n*B*2*d flops: it is bound by streaming W from HBM
+// once, not by the matrix cores.  Design:
+//   * 8 waves per workgroup, one workgroup per compute unit.  All of H (<= 64 x d bf16) is staged once into
+//     LDS (rows padded by 16 bytes, so the 16-byte operand reads of 16 consecutive rows hit distinct banks).
+//   * A pair of waves owns one 32-row vocabulary tile; each wave of the pair takes one half of K and streams
+//     it k-block by k-block (32 rows x 128 bytes, coalesced 16-byte loads: 8 lanes cover one row's 128 bytes),
+//     three k-blocks ahead of the one being multiplied.  W is read exactly once; no wave shares W with another.
+//   * The MFMA wants "lane = vocabulary row, 8 consecutive k": each k-block goes through a wave-private
+//     32 x 144-byte LDS patch that only re-maps lanes (write coalesced layout, read operand layout); LDS ops of
+//     one wave execute in order, so the patch needs no barrier.
+//   * W is the MFMA's row operand, so the accumulator is [vocabulary][result row]: the softmax partials of a
+//     row are an in-register reduction plus one half-wave exchange.
+//   * The two K-halves meet through the same patches (LDS-only barriers), each wave finishing one 32-row
+//     block of the 64 x 32 result: logits (turned through the patch once more, stored as whole 128-byte lines
+//     past L2) + softmax partials of the tile.
+// KH = k-blocks (of 64) per wave = d / 128; MT = 32-row blocks of M (1 or 2).
 constexpr int kSkinnyWaves = 8;
 constexpr int kSkinnyThreads = kSkinnyWaves * 64;
 constexpr int kPatchBytes = 32 * 144;
