@@ -57,6 +57,7 @@ SHAPES = [
     (33000,  768, 3, 11, 2,    3, 1, "greedy"),     # n*B = 33: second row block almost empty
     (70004,  64,  4, 3, 2,     3, 1, "mixed07"),    # more than 2048 softmax tiles: 20 tiles per sampler thread
     (200003, 64,  2, 2, 1,     2, 1, "mixed07"),    # beyond 163840: 32 tiles per sampler thread, two-pass sampler
+    (700,    16,  16, 2, 32,   300, 1, "mixed07"),  # maximum block length and draft count, window longer than the run
     # shapes that take the many-rows LM-head kernel (bf16, n*B > 64, d % 64 == 0)
     (4099,   256, 8, 40, 2,    3, 1, "one"),        # 320 rows: two row blocks, V % 4 != 0 (element-wise epilogue)
     (3000,   128, 8, 70, 1,    3, 1, "mixed07"),    # 560 rows: three row blocks, ragged last vocabulary block
