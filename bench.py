@@ -51,6 +51,7 @@ def parse():
     ap.add_argument("--policy", type=int, default=0, help="weight policy (0 softmax of 1/e, 1 static, 2 two-draft grid, 3 random)")
     ap.add_argument("--distance", type=int, default=0, help="0 KL, 1 total variation")
     ap.add_argument("--drafts", type=int, default=0, help="override the workload's number of drafts n (2 for --policy 2)")
+    ap.add_argument("--hidden", type=int, default=0, help="override the workload's draft hidden size d")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MB",
                     help="only run a plain device copy of MB megabytes 10 times: the known-size kernel against "
                          "which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
@@ -137,6 +138,8 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     if args.drafts:
         wl = synth.scaled(wl, n=args.drafts)
+    if args.hidden:
+        wl = synth.scaled(wl, d=args.hidden)
     device = "cuda:0"
     torch.cuda.set_device(0)
     binding.load()

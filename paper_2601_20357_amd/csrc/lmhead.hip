@@ -341,15 +341,150 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
     }
 }
 
+// ---------------------------------------------------------------- bf16, skinny M, larger hidden sizes
+// Same design as k_lmhead_skinny for hidden sizes whose H (64 x d) does not fit LDS: K is walked in chunks of
+// KH*128, and LDS holds one chunk of H at a time.  The next chunk of H is requested into registers at the
+// start of a chunk's k-loop and written to LDS between two LDS-only barriers at its end; the W request
+// stream (kPF k-blocks ahead) runs straight across chunk boundaries.  d = nchunks * KH * 128.
+template <int KH, int MT>
+__global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny_kc(int M, int V, int n, int NT, int num_tiles,
+                                                                     int nchunks,
+                                                                     const uint16_t* __restrict__ W,
+                                                                     const uint16_t* __restrict__ H,
+                                                                     const float* __restrict__ temperature,
+                                                                     float* __restrict__ L, float* __restrict__ pm,
+                                                                     float* __restrict__ ps) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    __shared__ float s_invt[64];
+    constexpr int DC = KH * 128;                    // k per chunk
+    constexpr int CH = DC / 8;                      // 16-byte pieces per row of one H chunk
+    constexpr int HROW = CH * 16 + 16;              // padded LDS row of H in bytes
+    const int d = nchunks * DC;
+    unsigned char* const ldsH = lds;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int pair = wave & 3, khalf = wave >> 2;
+    unsigned char* const patch = lds + MT * 32 * HROW + wave * kPatchBytes;
+    unsigned char* const partner_patch = lds + MT * 32 * HROW + (wave ^ 4) * kPatchBytes;
+    const int nn = lane & 31, half = lane >> 5;
+    if (tid < M) s_invt[tid] = row_inv_temperature(temperature, tid, n);
+
+    u32x4 hreg[MT * KH];
+    auto request_h = [&](int chunk) {               // rows >= M are clamped: their results are never stored
+#pragma unroll
+        for (int q = 0; q < MT * KH; ++q) {
+            const int p = tid + q * kSkinnyThreads, row = min(p / CH, M - 1), c = p % CH;
+            hreg[q] = *reinterpret_cast<const u32x4*>(H + (size_t)row * d + (size_t)chunk * DC + c * 8);
+        }
+    };
+    auto write_h = [&]() {
+#pragma unroll
+        for (int q = 0; q < MT * KH; ++q) {
+            const int p = tid + q * kSkinnyThreads, row = p / CH, c = p % CH;
+            *reinterpret_cast<u32x4*>(ldsH + row * HROW + c * 16) = hreg[q];
+        }
+    };
+    const int lrow = lane >> 3, lchunk = lane & 7;
+    u32x4 wreg[KH][4];
+    auto aim_tile = [&](size_t (&off)[4], int tile) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int v = min(tile * 32 + 8 * i + lrow, V - 1);
+            off[i] = (size_t)v * d + (size_t)khalf * (KH * 64) + lchunk * 8;
+        }
+    };
+    auto request_kblock = [&](const size_t (&off)[4], int chunk, int kb) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            wreg[kb][i] = *reinterpret_cast<const u32x4*>(W + off[i] + (size_t)chunk * DC + kb * 64);
+    };
+    constexpr int kPF = 3;                          // KH >= 4 here
+    request_h(0);
+    size_t src[4];
+    aim_tile(src, blockIdx.x * 4 + pair);
+#pragma unroll
+    for (int kb = 0; kb < kPF; ++kb) request_kblock(src, 0, kb);
+    __builtin_amdgcn_sched_barrier(0);
+    write_h();
+    lds_barrier();                                  // also publishes s_invt
+
+    for (int g = blockIdx.x;; g += gridDim.x) {
+        const int this_tile = g * 4 + pair;
+        f32x16 acc[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
+        const bool more = ((g + (int)gridDim.x) * 4 < num_tiles);
+        size_t nsrc[4];
+        aim_tile(nsrc, more ? this_tile + (int)gridDim.x * 4 : this_tile);
+        for (int chunk = 0; chunk < nchunks; ++chunk) {
+            const bool last_chunk = (chunk + 1 == nchunks);
+            const bool h_next = !last_chunk || more;  // another chunk of H follows (of this tile or the next)
+            if (h_next) request_h(last_chunk ? 0 : chunk + 1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kb = 0; kb < KH; ++kb) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    *reinterpret_cast<u32x4*>(patch + (8 * i + lrow) * 144 + lchunk * 16) = wreg[kb][i];
+                __builtin_amdgcn_sched_barrier(0);
+                if (kb + kPF < KH) request_kblock(src, chunk, kb + kPF);
+                else if (!last_chunk) request_kblock(src, chunk + 1, kb + kPF - KH);
+                else if (more) request_kblock(nsrc, 0, kb + kPF - KH);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const bf16x8 bv = *reinterpret_cast<const bf16x8*>(patch + nn * 144 + (2 * ks + half) * 16);
+                    const int hc = (khalf * KH + kb) * 8 + 2 * ks + half;
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        const bf16x8 av = *reinterpret_cast<const bf16x8*>(ldsH + (mt * 32 + nn) * HROW + hc * 16);
+                        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv, av, acc[mt], 0, 0, 0);
+                    }
+                }
+            }
+            if (h_next) {
+                lds_barrier();                      // every wave is done with this chunk of H
+                write_h();
+                lds_barrier();
+            }
+        }
+
+        f32x16 fin = acc[0], giv = acc[MT - 1];
+        if (MT == 2 && khalf == 1) { fin = acc[MT - 1]; giv = acc[0]; }
+        if (MT == 2 || khalf == 1) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<float4*>(patch + q * 1024 + lane * 16) =
+                    make_float4(giv[4 * q], giv[4 * q + 1], giv[4 * q + 2], giv[4 * q + 3]);
+        }
+        lds_barrier();
+        if (MT == 2 || khalf == 0) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 o = *reinterpret_cast<const float4*>(partner_patch + q * 1024 + lane * 16);
+                fin[4 * q] += o.x; fin[4 * q + 1] += o.y; fin[4 * q + 2] += o.z; fin[4 * q + 3] += o.w;
+            }
+        }
+        lds_barrier();
+        if ((MT == 2 || khalf == 0) && this_tile < num_tiles)
+            store_tile_32x32_t(fin, (MT == 2) ? khalf * 32 : 0, this_tile * 32, M, V, NT, s_invt, L, pm, ps, patch);
+        if (!more) break;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) src[i] = nsrc[i];
+    }
+}
+
 // ---------------------------------------------------------------- bf16, many rows (M > 64): MFMA-bound tiled GEMM
 // With hundreds of rows (stress shape: n*B = 512) the LM head is a real GEMM: 2*M*d*V flops against one
-// pass over W.  Workgroup tile 256 (rows) x 128 (vocabulary) x 64 (k), 8 waves, each wave a 64 x 64 block
-// (2 x 2 MFMA 32x32x16 tiles, W as the row operand so the accumulator is [vocabulary][row] and the cheap
-// transposed epilogue applies).  Both operands are staged through LDS in two buffers: while the MFMAs of
-// k-block i run out of one buffer, the 16-byte loads of k-block i+1 are in flight into registers and are
-// then written to the other buffer -- one barrier per k-block.  Rows padded by 16 bytes against bank
-// conflicts.  Workgroups are numbered so that the row blocks that share a vocabulary block run back to back
-// on the same XCD (workgroup w goes to XCD w % 8): W is then read from HBM once and from L2 afterwards.
+// pass over W.  Workgroup tile 256 (rows) x 256 (vocabulary) x 32 (k), 8 waves, each wave a 128 (rows) x 64
+// (vocabulary) block (2 x 4 MFMA 32x32x16 tiles, W as the row operand so the accumulator is
+// [vocabulary][row] and the cheap transposed epilogue applies).  Both operands are staged through LDS in two
+// buffers; the operand fragments of k-step s+1 are read from LDS while the MFMAs of k-step s run, and the
+// global loads of k-blocks i+2 and i+3 are in flight (two register sets) while k-block i is multiplied --
+// one barrier per k-block.  Rows padded by 16 bytes against bank conflicts.  Workgroups are numbered so that
+// the row blocks that share a vocabulary block run back to back on the same XCD (workgroup w goes to XCD
+// w % 8): W is then read from HBM once and from L2 afterwards.
 constexpr int kLBM = 256, kLBN = 256, kLBK = 32, kLRow = (kLBK + 8) * 2;   // LDS row stride in bytes (80)
 constexpr int kLCh = kLBK / 8;                                              // 16-byte chunks per row of a k-block
 constexpr int kLargeThreads = 512;
@@ -507,6 +642,45 @@ __global__ __launch_bounds__(kBlock) void k_lmhead_f32(int M, int d, int V, int 
     }
 }
 
+// Chunked variant: d a multiple of 768, 512 or 896 (k per chunk), at least two chunks.
+static int skinny_kc_kh(const tabed_cfg& c, int M) {
+    if (c.w_dtype != 1 || M > 64) return 0;
+    // with two row blocks the 512-wide chunk is the one that keeps the H prefetch in registers without spills
+    const int order_two[3] = {4, 6, 7}, order_one[3] = {6, 4, 7};
+    for (int KH : (M > 32 ? order_two : order_one))
+        if (c.d % (KH * 128) == 0 && c.d / (KH * 128) >= 2) return KH;
+    return 0;
+}
+
+template <int KH, int MT>
+static void launch_skinny_kc_t(const ProfScope* prof, const tabed_cfg& c, const WsLayout& Lay, int M, const void* W,
+                               const void* H, const float* temperature, float* logits, float* pm, float* ps,
+                               hipStream_t s) {
+    const size_t lds = (size_t)MT * 32 * (KH * 256 + 16) + (size_t)kSkinnyWaves * kPatchBytes;
+    static std::once_flag attr_once;
+    std::call_once(attr_once, [&] {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_lmhead_skinny_kc<KH, MT>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    });
+    const int num_tiles = Lay.NT, groups = (num_tiles + 3) / 4;
+    const dim3 grid(groups < 256 ? groups : 256);
+    launch(prof, k_lmhead_skinny_kc<KH, MT>, grid, dim3(kSkinnyThreads), lds, s, M, c.V, c.n, Lay.NT, num_tiles,
+           c.d / (KH * 128), static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), temperature, logits, pm, ps);
+}
+
+static void launch_skinny_kc(const ProfScope* prof, int KH, const tabed_cfg& c, const WsLayout& Lay, int M,
+                             const void* W, const void* H, const float* temperature, float* logits, float* pm,
+                             float* ps, hipStream_t s) {
+    const int MT = (M + 31) / 32;
+#define TABED_SKINNY_KC(KH_)                                                                              \
+    if (KH == KH_) {                                                                                      \
+        if (MT == 1) launch_skinny_kc_t<KH_, 1>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);   \
+        else         launch_skinny_kc_t<KH_, 2>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);   \
+    }
+    TABED_SKINNY_KC(4) TABED_SKINNY_KC(6) TABED_SKINNY_KC(7)
+#undef TABED_SKINNY_KC
+}
+
 static bool skinny_applies(const tabed_cfg& c, int M) {
     if (c.w_dtype != 1 || M > 64 || c.d % 128 != 0) return false;
     const int KH = c.d / 128, MT = (M + 31) / 32;
@@ -556,6 +730,8 @@ hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& Lay, char* ws, cons
                            static_cast<const float*>(W), static_cast<const float*>(H), temperature, logits, pm, ps);
     } else if (skinny_applies(c, M)) {
         launch_skinny(&prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);
+    } else if (skinny_kc_kh(c, M) != 0) {
+        launch_skinny_kc(&prof, skinny_kc_kh(c, M), c, Lay, M, W, H, temperature, logits, pm, ps, s);
     } else if (M > 64 && c.d % 64 == 0) {
         static std::once_flag attr_once;                   // raise the dynamic-LDS limit once
         const size_t lds = 2 * (size_t)kLargeStage;

@@ -58,6 +58,11 @@ SHAPES = [
     (70004,  64,  4, 3, 2,     3, 1, "mixed07"),    # more than 2048 softmax tiles: 20 tiles per sampler thread
     (200003, 64,  2, 2, 1,     2, 1, "mixed07"),    # beyond 163840: 32 tiles per sampler thread, two-pass sampler
     (700,    16,  16, 2, 32,   300, 1, "mixed07"),  # maximum block length and draft count, window longer than the run
+    # larger hidden sizes with n*B <= 64: the K-chunked streaming LM head
+    (2100,  1024, 4, 16, 2,    3, 1, "one"),        # two chunks of 512, two row blocks
+    (40000, 1536, 2, 5, 1,     3, 1, "mixed07"),    # two chunks of 768, one row block, persistent loop twice
+    (1000,  2048, 4, 12, 2,    3, 1, "one"),        # four chunks of 512, ragged last tile
+    (700,   1792, 3, 3, 1,     2, 1, "greedy"),     # two chunks of 896
     # shapes that take the many-rows LM-head kernel (bf16, n*B > 64, d % 64 == 0)
     (4099,   256, 8, 40, 2,    3, 1, "one"),        # 320 rows: two row blocks, V % 4 != 0 (element-wise epilogue)
     (3000,   128, 8, 70, 1,    3, 1, "mixed07"),    # 560 rows: three row blocks, ragged last vocabulary block
