@@ -71,11 +71,12 @@ __device__ __forceinline__ void store_tile_32x32(const f32x16& acc, int m_base, 
 // Epilogue of one 32x32 accumulator tile held TRANSPOSED: lane holds result row m_base + lane % 32 and the 16
 // vocabulary entries v_base + 8*(r/4) + 4*(lane/32) + r%4.  The softmax partials of a row are then a
 // 16-value in-register reduction plus one exchange between the two half-waves, and every lane stores four
-// runs of four consecutive logits.  inv_t[m] = 1/T of row m (LDS table).
+// runs of four consecutive logits.  inv_t[m] = 1/T of row m (LDS table).  With `pstage` the partials go to an
+// LDS table instead, from which the caller writes a workgroup's four tiles of a row as one 16-byte store.
 __device__ __forceinline__ void store_tile_32x32_t(const f32x16& acc, int m_base, int v_base, int M, int V, int NT,
                                                    const float* inv_t, float* __restrict__ L,
                                                    float* __restrict__ pm, float* __restrict__ ps,
-                                                   unsigned char* tpatch) {
+                                                   unsigned char* tpatch, float* pstage = nullptr, int pslot = 0) {
     if (v_base >= V) return;
     const int lane = threadIdx.x & 63;
     const int col = lane & 31, half = lane >> 5;
@@ -96,8 +97,13 @@ __device__ __forceinline__ void store_tile_32x32_t(const f32x16& acc, int m_base
     for (int r = 0; r < 16; ++r) sum += (sc[r] > -INFINITY) ? __expf(sc[r] - mx) : 0.f;
     sum += __shfl_xor(sum, 32);
     if (live && half == 0) {
-        pm[(size_t)m * NT + v_base / kTileV] = mx;
-        ps[(size_t)m * NT + v_base / kTileV] = sum;
+        if (pstage != nullptr) {                    // collected per workgroup: [array][row][tile of the group]
+            pstage[(0 * 64 + m) * 4 + pslot] = mx;
+            pstage[(1 * 64 + m) * 4 + pslot] = sum;
+        } else {
+            pm[(size_t)m * NT + v_base / kTileV] = mx;
+            ps[(size_t)m * NT + v_base / kTileV] = sum;
+        }
     }
     if ((V & 3) == 0 && v_base + 32 <= V) {
         // Full tile: turn the block through the wave's LDS patch ([32 rows][32 v] floats, 144-byte rows) so
@@ -226,6 +232,7 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
                                                                   float* __restrict__ ps) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ float s_invt[64];
+    __shared__ __attribute__((aligned(16))) float s_pstage[2 * 64 * 4];   // softmax partials of the group's 4 tiles
     constexpr int d = KH * 128;
     constexpr int CH = d / 8;                       // 16-byte chunks per row of H / W
     constexpr int HROW = CH * 16 + 16;              // padded LDS row of H in bytes
@@ -334,7 +341,16 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
         }
         lds_barrier();                                 // both patches of the pair are read: they may be reused
         if ((MT == 2 || khalf == 0) && this_tile < num_tiles)
-            store_tile_32x32_t(fin, (MT == 2) ? khalf * 32 : 0, this_tile * 32, M, V, NT, s_invt, L, pm, ps, patch);
+            store_tile_32x32_t(fin, (MT == 2) ? khalf * 32 : 0, this_tile * 32, M, V, NT, s_invt, L, pm, ps, patch, s_pstage, pair);
+        // the four tiles of this group sit side by side in a row of the partial tables: 16 bytes per row
+        lds_barrier();
+        if (tid < 128 && (tid & 63) < M) {
+            const int arr = tid >> 6, row = tid & 63, t0 = g * 4;
+            float* dst = (arr == 0 ? pm : ps) + (size_t)row * NT + t0;
+            const float* srcp = s_pstage + (arr * 64 + row) * 4;
+            if ((NT & 3) == 0 && t0 + 3 < NT) *reinterpret_cast<float4*>(dst) = *reinterpret_cast<const float4*>(srcp);
+            else for (int q = 0; q < 4; ++q) if (t0 + q < NT) dst[q] = srcp[q];
+        }
         if (!more) break;
 #pragma unroll
         for (int i = 0; i < 4; ++i) src[i] = nsrc[i];
@@ -356,6 +372,7 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny_kc(int M, int 
                                                                      float* __restrict__ ps) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ float s_invt[64];
+    __shared__ __attribute__((aligned(16))) float s_pstage[2 * 64 * 4];   // softmax partials of the group's 4 tiles
     constexpr int DC = KH * 128;                    // k per chunk
     constexpr int CH = DC / 8;                      // 16-byte pieces per row of one H chunk
     constexpr int HROW = CH * 16 + 16;              // padded LDS row of H in bytes
@@ -468,7 +485,16 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny_kc(int M, int 
         }
         lds_barrier();
         if ((MT == 2 || khalf == 0) && this_tile < num_tiles)
-            store_tile_32x32_t(fin, (MT == 2) ? khalf * 32 : 0, this_tile * 32, M, V, NT, s_invt, L, pm, ps, patch);
+            store_tile_32x32_t(fin, (MT == 2) ? khalf * 32 : 0, this_tile * 32, M, V, NT, s_invt, L, pm, ps, patch, s_pstage, pair);
+        // the four tiles of this group sit side by side in a row of the partial tables: 16 bytes per row
+        lds_barrier();
+        if (tid < 128 && (tid & 63) < M) {
+            const int arr = tid >> 6, row = tid & 63, t0 = g * 4;
+            float* dst = (arr == 0 ? pm : ps) + (size_t)row * NT + t0;
+            const float* srcp = s_pstage + (arr * 64 + row) * 4;
+            if ((NT & 3) == 0 && t0 + 3 < NT) *reinterpret_cast<float4*>(dst) = *reinterpret_cast<const float4*>(srcp);
+            else for (int q = 0; q < 4; ++q) if (t0 + q < NT) dst[q] = srcp[q];
+        }
         if (!more) break;
 #pragma unroll
         for (int i = 0; i < 4; ++i) src[i] = nsrc[i];
