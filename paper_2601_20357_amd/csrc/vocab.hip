@@ -241,10 +241,10 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
     const float wj = (tid < n) ? a.weights[(size_t)b * n + tid] : 0.f;
     const float u = a.u_draft ? a.u_draft[out_idx] : tabed_uniform(a.seed, a.round, (uint32_t)b, (uint32_t)a.pos, 0);
 
-    // Which tiles a thread owns.  Few tiles per thread: the contiguous run [tid*TI, tid*TI + TI).  Many
-    // (single-pass kernels of large vocabularies): TI/4 chunks of 4 consecutive tiles, chunk q*256 + tid for
-    // q < TI/4 -- then every 16-byte load of a wave is one contiguous kilobyte.
-    constexpr bool CHUNKED = (N > 0 && TI > 4);
+    // Which tiles a thread owns.  Two-pass kernels and TI = 1: the contiguous run [tid*TI, tid*TI + TI).
+    // Single-pass kernels: TI/4 chunks of 4 consecutive tiles, chunk q*256 + tid for q < TI/4 (for TI = 4 that
+    // is the same run) -- every load is then 16 bytes and a wave's load is one contiguous kilobyte.
+    constexpr bool CHUNKED = (N > 0 && TI >= 4);
     constexpr int TPC = CHUNKED ? 4 : TI;              // tiles per chunk
     constexpr int Q = TI / TPC;                        // chunks per thread
     auto tile_of = [&](int i) { return CHUNKED ? ((i / 4) * kBlock + tid) * 4 + (i & 3) : tid * TI + i; };
