@@ -513,12 +513,14 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny_kc(int M, int 
 // w % 8): W is then read from HBM once and from L2 afterwards.
 constexpr int kLBM = 256, kLBN = 256, kLBK = 32, kLRow = (kLBK + 8) * 2;   // LDS row stride in bytes (80)
 constexpr int kLCh = kLBK / 8;                                              // 16-byte chunks per row of a k-block
-constexpr int kLargeThreads = 512;
 constexpr int kLargeStage = (kLBM + kLBN) * kLRow;                          // bytes per buffer (40960)
-static_assert(kLBN * kLCh % kLargeThreads == 0 && kLBM * kLCh % kLargeThreads == 0, "staging split");
-constexpr int kLWPieces = kLBN * kLCh / kLargeThreads, kLHPieces = kLBM * kLCh / kLargeThreads;
 
-__global__ __launch_bounds__(kLargeThreads) void k_lmhead_large(int M, int d, int V, int n, int NT, int mblocks,
+// NW = waves per workgroup: 8 (each wave 128 rows x 64 vocabulary entries, two waves per SIMD) or 4 (each wave
+// 128 x 128, one wave per SIMD with the accumulators in the upper half of the register file).
+constexpr int kLargeWaves = 8;
+
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void k_lmhead_large(int M, int d, int V, int n, int NT, int mblocks,
                                                                 const uint16_t* __restrict__ W,
                                                                 const uint16_t* __restrict__ H,
                                                                 const float* __restrict__ temperature,
@@ -526,6 +528,10 @@ __global__ __launch_bounds__(kLargeThreads) void k_lmhead_large(int M, int d, in
                                                                 float* __restrict__ ps) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ float s_invt[kLBM];
+    constexpr int kLargeThreads = NW * 64;
+    constexpr int kLWPieces = kLBN * kLCh / kLargeThreads, kLHPieces = kLBM * kLCh / kLargeThreads;
+    static_assert(kLBN * kLCh % kLargeThreads == 0 && kLBM * kLCh % kLargeThreads == 0, "staging split");
+    constexpr int WNT = (NW == 8) ? 2 : 4;                // 32-wide vocabulary tiles per wave
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nn = lane & 31, half = lane >> 5;
     // XCD-aware numbering: workgroup w runs on XCD w % 8; consecutive slots of one XCD walk the row blocks
@@ -534,7 +540,8 @@ __global__ __launch_bounds__(kLargeThreads) void k_lmhead_large(int M, int d, in
     const int mb = slot % mblocks, nb = (slot / mblocks) * 8 + xcd;
     const int m0 = mb * kLBM, v0 = nb * kLBN;
     if (v0 >= V) return;                                  // uniform: padding workgroups of the last XCD round
-    const int wm = wave >> 2, wn = wave & 3;              // wave block: rows m0 + 128*wm.., vocabulary v0 + 64*wn..
+    const int wm = (NW == 8) ? wave >> 2 : wave >> 1;     // wave block: rows m0 + 128*wm ..,
+    const int wn = (NW == 8) ? wave & 3 : wave & 1;       // vocabulary v0 + 32*WNT*wn ..
     if (tid < kLBM && m0 + tid < M) s_invt[tid] = row_inv_temperature(temperature, m0 + tid, n);
 
     // ---- global -> register staging: two register sets, so that the loads of k-block kb+2 and kb+3 are in
@@ -575,9 +582,9 @@ __global__ __launch_bounds__(kLargeThreads) void k_lmhead_large(int M, int d, in
     using Set0 = std::integral_constant<int, 0>;
     using Set1 = std::integral_constant<int, 1>;
 
-    f32x16 acc[2][4];                                     // [vocabulary tile][row tile]
+    f32x16 acc[WNT][4];                                   // [vocabulary tile][row tile]
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < WNT; ++a)
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
@@ -587,11 +594,11 @@ __global__ __launch_bounds__(kLargeThreads) void k_lmhead_large(int M, int d, in
         const unsigned char* sW = lds + buf * kLargeStage;
         const unsigned char* sH = sW + kLBN * kLRow;
         // operand fragments of k-step ks+1 are read from LDS while the MFMAs of k-step ks run
-        bf16x8 wf[2][2], hf[2][4];
+        bf16x8 wf[2][WNT], hf[2][4];
         auto read_frags = [&](int ks, int set) {
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
-                wf[set][a] = *reinterpret_cast<const bf16x8*>(sW + (wn * 64 + a * 32 + nn) * kLRow + (2 * ks + half) * 16);
+            for (int a = 0; a < WNT; ++a)
+                wf[set][a] = *reinterpret_cast<const bf16x8*>(sW + (wn * 32 * WNT + a * 32 + nn) * kLRow + (2 * ks + half) * 16);
 #pragma unroll
             for (int b = 0; b < 4; ++b)
                 hf[set][b] = *reinterpret_cast<const bf16x8*>(sH + (wm * 128 + b * 32 + nn) * kLRow + (2 * ks + half) * 16);
@@ -602,7 +609,7 @@ __global__ __launch_bounds__(kLargeThreads) void k_lmhead_large(int M, int d, in
             if (ks + 1 < kLBK / 16) read_frags(ks + 1, (ks + 1) & 1);
             __builtin_amdgcn_sched_barrier(0);            // keep the reads ahead of the MFMAs they overlap with
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < WNT; ++a)
 #pragma unroll
                 for (int b = 0; b < 4; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks & 1][a], hf[ks & 1][b], acc[a][b], 0, 0, 0);
@@ -630,10 +637,10 @@ __global__ __launch_bounds__(kLargeThreads) void k_lmhead_large(int M, int d, in
     // ---- epilogue: every wave turns its four 32x32 blocks through a private patch carved from buffer 0
     unsigned char* tpatch = lds + wave * kPatchBytes;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < WNT; ++a)
 #pragma unroll
         for (int b = 0; b < 4; ++b)
-            store_tile_32x32_t(acc[a][b], m0 + wm * 128 + b * 32, v0 + wn * 64 + a * 32, M, V, NT, s_invt - m0, L, pm, ps,
+            store_tile_32x32_t(acc[a][b], m0 + wm * 128 + b * 32, v0 + wn * 32 * WNT + a * 32, M, V, NT, s_invt - m0, L, pm, ps,
                                tpatch);
 }
 
@@ -762,13 +769,13 @@ hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& Lay, char* ws, cons
         static std::once_flag attr_once;                   // raise the dynamic-LDS limit once
         const size_t lds = 2 * (size_t)kLargeStage;
         std::call_once(attr_once, [&] {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_lmhead_large),
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_lmhead_large<kLargeWaves>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         });
         const int mblocks = (M + kLBM - 1) / kLBM, nblocks = (c.V + kLBN - 1) / kLBN;
         const int nrounds = (nblocks + 7) / 8;             // vocabulary blocks are dealt to the 8 XCDs in rounds
         const dim3 grid(nrounds * mblocks * 8);
-        launch(&prof, k_lmhead_large, grid, dim3(kLargeThreads), lds, s, M, c.d, c.V, c.n, Lay.NT, mblocks,
+        launch(&prof, k_lmhead_large<kLargeWaves>, grid, dim3(kLargeWaves * 64), lds, s, M, c.d, c.V, c.n, Lay.NT, mblocks,
                static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), temperature, logits, pm, ps);
     } else {
         const dim3 grid((c.V + kBN - 1) / kBN, (M + kBM - 1) / kBM);
