@@ -15,7 +15,7 @@
  *   tabed_verify           Sec. 3 items 2-3: accept each drafted token with
  *                          probability min(1, p/q), resample the first rejected
  *                          one from norm(max(0, p - q)); plus the per-position
- *                          distances D(p, q^(j)) of Sec. 4.1 that feed the
+ *                          distances D(p, q^(j)) of Sec. 5.1 that feed the
  *                          next tabed_update_weights.
  *
  * Notation: n = number of drafting methods (the paper's m), B independent
@@ -79,14 +79,14 @@ typedef struct tabed_cfg {
     int32_t h;        /* observation window length in verified positions, >= 1; 0 = ALL    */
                       /* positions since the start (the paper's default, App. B.1)         */
     int32_t w_dtype;  /* storage type of W and H: 0 = fp32, 1 = bf16                       */
-    int32_t distance; /* D of Alg. 1: 0 = KL(p || q) (Sec. 4.1); 1 = total variation;      */
+    int32_t distance; /* D of Alg. 1: 0 = KL(p || q) (Sec. 5.1); 1 = total variation;      */
                       /* 2 = hard labels: 1 where the candidate's arg-max token differs    */
                       /*     from the token emitted at the position, else 0                */
     int32_t policy;   /* 0 = softmax(1/e; tau_w) (App. B.2); 1 = static equal weights;     */
                       /* 2 = two-draft grid (App. B.2): arg-min over w^c = [1-c/10, c/10], */
                       /*     c = 0..10, of the window sum of D(p, mixture); needs n = 2;   */
                       /* 3 = random weights, uniform on the simplex, fresh for every block */
-                      /*     (the random-weights ablation of Sec. 5)                       */
+                      /*     (the random-weights ablation of Sec. 6.2)                       */
     float tau_w;      /* temperature of the weight softmax, > 0 (paper default 1)          */
     float eps;        /* e is clamped to >= eps before 1/e, > 0                            */
     uint64_t seed;    /* Philox key                                                        */
@@ -118,7 +118,7 @@ int tabed_last_hip_error(void);
  *
  *   W            [V,d]            in   LM-head matrix shared by all drafts (w_dtype)
  *   H            [B,n,d]          in   last hidden state of every draft (w_dtype)
- *   weights      [B,n]     fp32   in   w*_t, constant over the block (Sec. 4.1)
+ *   weights      [B,n]     fp32   in   w*_t, constant over the block (Sec. 5.1)
  *   temperature  [B]       fp32   in   0 => greedy row
  *   u_draft      [B,gamma] fp32   in   optional explicit uniforms, column pos is read; NULL => Philox
  *   draft_logits [gamma,B,n,V] fp32 out slot pos is written
@@ -136,7 +136,7 @@ int tabed_draft_step(const tabed_cfg* cfg, void* ws, uint64_t round, int32_t pos
 /*
  * Sec. 3 items 2-3 for all B sequences, given the target's logits at the
  * gamma drafted positions and one position beyond; plus D(p_i, q_i^(j)) for
- * every drafted position i and draft j (Sec. 4.1).
+ * every drafted position i and draft j (Sec. 5.1).
  *
  *   target_logits [B,gamma+1,V] fp32 in
  *   draft_logits, draft_lse, draft_tokens, draft_q, weights, temperature: as written by / passed to
@@ -204,8 +204,9 @@ int tabed_philox_uniforms(const tabed_cfg* cfg, uint64_t round, float* out, void
 #define TABED_K_STATS 2   /* target statistics + distances + accept chain */
 #define TABED_K_RESID 3   /* corrected / bonus token            */
 #define TABED_K_WEIGHTS 4 /* window + weights                   */
-#define TABED_K_NULL 5    /* empty kernel, see tabed_prof_null  */
-#define TABED_K_COUNT 6
+#define TABED_K_DIST 5    /* second-pass distances (total variation, hard labels, grid mixtures) */
+#define TABED_K_NULL 6    /* empty kernel, see tabed_prof_null  */
+#define TABED_K_COUNT 7
 int tabed_prof_enable(int on);
 int tabed_prof_read(int id, double* total_ms, int64_t* launches);
 int tabed_prof_reset(void);

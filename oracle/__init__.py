@@ -37,8 +37,14 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        build()
-        _lib = C.CDLL(_LIB)
+        # TABED_ORACLE_LIB: a test that plants mistakes in a COPY of the C file points this module at the copy's
+        # build, to show that the pins catch them
+        override = os.environ.get("TABED_ORACLE_LIB")
+        if override:
+            _lib = C.CDLL(override)
+        else:
+            build()
+            _lib = C.CDLL(_LIB)
         _lib.oracle_uniform.restype = C.c_float
         _lib.oracle_uniform.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32, C.c_int]
         _lib.oracle_speedup.restype = C.c_double

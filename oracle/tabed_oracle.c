@@ -10,7 +10,7 @@
  *   - Sec. 3 "Preliminaries", items 1-3: draft gamma tokens, verify in
  *     parallel, accept token y with probability min(1, p(y)/q(y)); at the
  *     first rejection drop the rest and resample from norm(max(0, p - q)).
- *   - Sec. 4.1 "Proposed Method" + Algorithm 1: the m drafting methods run
+ *   - Sec. 5.1 "Proposed Method" + Algorithm 1: the m drafting methods run
  *     as one batch through the shared draft model; their distributions are
  *     mixed by a weighted average (W-Avg) and the next draft token is sampled
  *     from the mixture; the weights are chosen at the start of a block from
@@ -20,7 +20,7 @@
  *     tau = 1, and the two-draft policy that scores the fixed candidates
  *     w^c = [1 - c/10, c/10] by the accumulated distance of the MIXTURE
  *     q(.; w^c) from the target and takes the arg-min (Alg. 1 line 3);
- *     Sec. 4.1 last paragraph: TVD as the alternative distance; Sec. 4.1:
+ *     Sec. 5.1 last paragraph: TVD as the alternative distance; Sec. 5.1:
  *     selection by hard labels (token matches) instead of soft labels.
  *   - Eq. 1: speedup = block_eff / (gamma * Tq/Tp + 1).
  *
@@ -31,11 +31,11 @@
  * function that takes it, marked "reading:".
  *
  * Pin status: every function below is pinned by tests that do not reuse its
- * formula (library cross-checks, closed forms, exact enumeration on tiny
- * vocabularies, the lossless-sampling invariant) EXCEPT oracle_philox4x32_10,
- * whose published known-answer vectors are not available offline:
- * "parity unpinned" against those vectors; it is pinned structurally
- * (inverse permutation written from the definition, uniformity statistics).
+ * formula: library cross-checks, closed forms, exact enumeration on tiny
+ * vocabularies, the lossless-sampling invariant; oracle_philox4x32_10 is
+ * compared word for word with rocRAND's Philox4x32-10 engine (another
+ * author's implementation, compiled for the host from the library's public
+ * header) on random 64-bit keys and 128-bit counters.
  *
  * All floating point is fp64 unless a value is an interface value that the
  * method stores in fp32 (logits, q(y), p(y), dev, ring, weights).
@@ -213,7 +213,7 @@ int oracle_sample_cdf(const double* f, int V, double u, uint32_t* flag)
 }
 
 /* D_KL(p || q) = sum_v p(v) (log p(v) - log q(v)), from log-probabilities;
- * a term with p(v) == 0 contributes 0.  (Sec. 4.1, the formula for e_t^j.) */
+ * a term with p(v) == 0 contributes 0.  (Sec. 5.1, the formula for e_t^j.) */
 double oracle_kl(const double* p, const double* logp, const double* logq, int V)
 {
     double acc = 0.0;
@@ -221,7 +221,7 @@ double oracle_kl(const double* p, const double* logp, const double* logq, int V)
     return acc;
 }
 
-/* Total variation distance, the alternative D of Sec. 4.1. */
+/* Total variation distance, the alternative D of Sec. 5.1. */
 double oracle_tvd(const double* p, const double* q, int V)
 {
     double acc = 0.0;
@@ -429,7 +429,7 @@ void oracle_verify(int V, int n, int B, int gamma, int distance, int n_cand,
  * window; policy 1: equal weights; policy 2 (n = 2, window entries are the 11
  * candidate distances): w = [1 - c/10, c/10] for the candidate c with the
  * smallest window sum (reading: lowest c on ties; equal weights while the
- * window is empty); policy 3: the random-weights ablation of Sec. 5 (reading:
+ * window is empty); policy 3: the random-weights ablation of Sec. 6.2 (reading:
  * uniform on the simplex, drawn afresh for every block: w_j = E_j / sum E,
  * E_j = -ln U_j, U_j = (x + 0.5) 2^-24 from word j % 4 of the Philox block
  * (seed; round, b, gamma + 1 + j / 4), `round` being the block the weights are

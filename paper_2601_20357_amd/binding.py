@@ -19,7 +19,7 @@ EXPORTS = [
 ]
 
 FLAG_ACCEPT_MARGIN, FLAG_SAMPLE_MARGIN, FLAG_DEGENERATE = 1, 2, 4
-K_LMHEAD, K_SAMPLE, K_STATS, K_RESID, K_WEIGHTS, K_NULL, K_COUNT = 0, 1, 2, 3, 4, 5, 6
+K_LMHEAD, K_SAMPLE, K_STATS, K_RESID, K_WEIGHTS, K_DIST, K_NULL, K_COUNT = 0, 1, 2, 3, 4, 5, 6, 7
 
 
 class TabedCfg(C.Structure):

@@ -225,6 +225,7 @@ const char* tabed_kernel_name(int id) {
         case TABED_K_STATS: return "stats";
         case TABED_K_RESID: return "resid";
         case TABED_K_WEIGHTS: return "weights";
+        case TABED_K_DIST: return "dist";
         case TABED_K_NULL: return "null";
         default: return "?";
     }

@@ -167,12 +167,28 @@ __device__ __forceinline__ int block_find_owner(double excl, double run, double 
 }
 
 // ---------------------------------------------------------------- publishing partial results across workgroups
-// "Last workgroup done" hand-over without a release/acquire fence.  On gfx950 an agent-scope fence writes
-// back and invalidates the whole L2 of the XCD (measured 2-3 us per fence inside these kernels); device-scope
-// atomic accesses instead go to the coherence point directly.  Protocol: every partial result is written
-// with publish_store(); the workgroup then meets at __syncthreads(), which also waits until those stores
-// have been acknowledged; one thread bumps the arrival counter with arrive(); the workgroup that sees the
-// final count reads the partial results with published_load() only.
+// "Last workgroup done" hand-over without an agent-scope fence.  On gfx950 such a fence writes back and
+// invalidates the whole L2 of the XCD (measured 2-3 us per fence inside these kernels).  What a release /
+// acquire pair has to guarantee here is narrower: (1) the partial results are at the device's coherence point
+// before the arrival counter moves, and (2) the finishing workgroup does not read them from a stale cache
+// line.  Both follow from the instructions themselves:
+//   * publish_store() is an agent-scope atomic store: it is emitted as a write-through store (sc1) that
+//     is acknowledged only once it has reached the memory side shared by all XCDs; nothing published is
+//     ever left dirty in an XCD's L2, which is all the fence's write-back would be for.
+//   * publish_barrier(): every thread waits until ALL of its outstanding vector-memory operations have been
+//     acknowledged (s_waitcnt vmcnt(0): on gfx9 the counter covers stores as well as loads), then the
+//     workgroup meets.  A plain __syncthreads() does not wait for stores.
+//   * arrive() is an agent-scope atomic add issued after that barrier, so it is ordered after every
+//     published store of the workgroup; the workgroup whose add returns the final count reads the partial
+//     results with published_load() only, an agent-scope atomic load (sc1) that is served from the
+//     coherence point, never from a line an XCD cached earlier; those loads are issued after the add has
+//     returned (its value decides the branch).
+// What would break it: a publish_store() that is not waited for before the barrier, an ordinary load of
+// published data in the finishing workgroup, or an ordinary store of data another workgroup then reads.
+__device__ __forceinline__ void publish_barrier() {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+}
 __device__ __forceinline__ void publish_store(double* p, double v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }

@@ -195,9 +195,9 @@ __global__ __launch_bounds__(kBlock) void k_lmhead_bf16(int M, int d, int V, int
     store_tile_32x32(acc, m0 + wm * 32, v0 + wn * 32, M, V, NT, s_invt, m0, L, pm, ps);
 }
 
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global
-// load (vmcnt(0)); in the streaming kernels below that would stall a workgroup until all of its W requests
-// have landed.
+// Workgroup barrier that orders LDS traffic only: it waits for this wave's LDS operations and nothing else, so
+// a wave reaches it with its W requests still in flight.  (A barrier written so that it also waits for vector
+// memory would stall a workgroup until all of its outstanding W requests have landed.)
 __device__ __forceinline__ void lds_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
@@ -685,33 +685,42 @@ static int skinny_kc_kh(const tabed_cfg& c, int M) {
     return 0;
 }
 
+// Raises a kernel's dynamic-LDS limit once per process; a failure is remembered and returned by every later call.
+template <typename K>
+static hipError_t raise_lds_limit(K kernel, size_t lds, std::once_flag& once, hipError_t& rc) {
+    std::call_once(once, [&] {
+        rc = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    });
+    return rc;
+}
+
 template <int KH, int MT>
-static void launch_skinny_kc_t(const ProfScope* prof, const tabed_cfg& c, const WsLayout& Lay, int M, const void* W,
+static hipError_t launch_skinny_kc_t(const ProfScope* prof, const tabed_cfg& c, const WsLayout& Lay, int M, const void* W,
                                const void* H, const float* temperature, float* logits, float* pm, float* ps,
                                hipStream_t s) {
     const size_t lds = (size_t)MT * 32 * (KH * 256 + 16) + (size_t)kSkinnyWaves * kPatchBytes;
     static std::once_flag attr_once;
-    std::call_once(attr_once, [&] {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_lmhead_skinny_kc<KH, MT>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    });
+    static hipError_t attr_rc = hipSuccess;
+    if (raise_lds_limit(&k_lmhead_skinny_kc<KH, MT>, lds, attr_once, attr_rc) != hipSuccess) return attr_rc;
     const int num_tiles = Lay.NT, groups = (num_tiles + 3) / 4;
     const dim3 grid(groups < 256 ? groups : 256);
     launch(prof, k_lmhead_skinny_kc<KH, MT>, grid, dim3(kSkinnyThreads), lds, s, M, c.V, c.n, Lay.NT, num_tiles,
            c.d / (KH * 128), static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), temperature, logits, pm, ps);
+    return hipSuccess;
 }
 
-static void launch_skinny_kc(const ProfScope* prof, int KH, const tabed_cfg& c, const WsLayout& Lay, int M,
+static hipError_t launch_skinny_kc(const ProfScope* prof, int KH, const tabed_cfg& c, const WsLayout& Lay, int M,
                              const void* W, const void* H, const float* temperature, float* logits, float* pm,
                              float* ps, hipStream_t s) {
     const int MT = (M + 31) / 32;
 #define TABED_SKINNY_KC(KH_)                                                                              \
     if (KH == KH_) {                                                                                      \
-        if (MT == 1) launch_skinny_kc_t<KH_, 1>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);   \
-        else         launch_skinny_kc_t<KH_, 2>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);   \
+        if (MT == 1) return launch_skinny_kc_t<KH_, 1>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);   \
+        else         return launch_skinny_kc_t<KH_, 2>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);   \
     }
     TABED_SKINNY_KC(4) TABED_SKINNY_KC(6) TABED_SKINNY_KC(7)
 #undef TABED_SKINNY_KC
+    return hipErrorInvalidValue;
 }
 
 static bool skinny_applies(const tabed_cfg& c, int M) {
@@ -723,32 +732,32 @@ static bool skinny_applies(const tabed_cfg& c, int M) {
 }
 
 template <int KH, int MT>
-static void launch_skinny_t(const ProfScope* prof, const tabed_cfg& c, const WsLayout& Lay, int M, const void* W, const void* H,
+static hipError_t launch_skinny_t(const ProfScope* prof, const tabed_cfg& c, const WsLayout& Lay, int M, const void* W, const void* H,
                             const float* temperature, float* logits, float* pm, float* ps, hipStream_t s) {
     const size_t lds = (size_t)MT * 32 * (KH * 256 + 16) + (size_t)kSkinnyWaves * kPatchBytes;
     static std::once_flag attr_once;                   // raise the dynamic-LDS limit of this instantiation once
-    std::call_once(attr_once, [&] {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_lmhead_skinny<KH, MT>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    });
+    static hipError_t attr_rc = hipSuccess;
+    if (raise_lds_limit(&k_lmhead_skinny<KH, MT>, lds, attr_once, attr_rc) != hipSuccess) return attr_rc;
     const int num_tiles = Lay.NT;
     int cus = 256;
     const int groups = (num_tiles + 3) / 4;
     const dim3 grid(groups < cus ? groups : cus);
     launch(prof, k_lmhead_skinny<KH, MT>, grid, dim3(kSkinnyThreads), lds, s, M, c.V, c.n, Lay.NT, num_tiles,
                        static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), temperature, logits, pm, ps);
+    return hipSuccess;
 }
 
-static void launch_skinny(const ProfScope* prof, const tabed_cfg& c, const WsLayout& Lay, int M, const void* W, const void* H,
+static hipError_t launch_skinny(const ProfScope* prof, const tabed_cfg& c, const WsLayout& Lay, int M, const void* W, const void* H,
                           const float* temperature, float* logits, float* pm, float* ps, hipStream_t s) {
     const int KH = c.d / 128, MT = (M + 31) / 32;
 #define TABED_SKINNY(KH_)                                                                              \
     if (KH == KH_) {                                                                                   \
-        if (MT == 1) launch_skinny_t<KH_, 1>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);         \
-        else         launch_skinny_t<KH_, 2>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);         \
+        if (MT == 1) return launch_skinny_t<KH_, 1>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);  \
+        else         return launch_skinny_t<KH_, 2>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);  \
     }
     TABED_SKINNY(4) TABED_SKINNY(6) TABED_SKINNY(7) TABED_SKINNY(8)
 #undef TABED_SKINNY
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& Lay, char* ws, const void* W, const void* H,
@@ -762,16 +771,16 @@ hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& Lay, char* ws, cons
         launch(&prof, k_lmhead_f32, grid, dim3(kBlock), 0, s, M, c.d, c.V, c.n, Lay.NT,
                            static_cast<const float*>(W), static_cast<const float*>(H), temperature, logits, pm, ps);
     } else if (skinny_applies(c, M)) {
-        launch_skinny(&prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);
+        const hipError_t e = launch_skinny(&prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);
+        if (e != hipSuccess) return e;
     } else if (skinny_kc_kh(c, M) != 0) {
-        launch_skinny_kc(&prof, skinny_kc_kh(c, M), c, Lay, M, W, H, temperature, logits, pm, ps, s);
+        const hipError_t e = launch_skinny_kc(&prof, skinny_kc_kh(c, M), c, Lay, M, W, H, temperature, logits, pm, ps, s);
+        if (e != hipSuccess) return e;
     } else if (M > 64 && c.d % 64 == 0) {
         static std::once_flag attr_once;                   // raise the dynamic-LDS limit once
+        static hipError_t attr_rc = hipSuccess;
         const size_t lds = 2 * (size_t)kLargeStage;
-        std::call_once(attr_once, [&] {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_lmhead_large<kLargeWaves>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        });
+        if (raise_lds_limit(&k_lmhead_large<kLargeWaves>, lds, attr_once, attr_rc) != hipSuccess) return attr_rc;
         const int mblocks = (M + kLBM - 1) / kLBM, nblocks = (c.V + kLBN - 1) / kLBN;
         const int nrounds = (nblocks + 7) / 8;             // vocabulary blocks are dealt to the 8 XCDs in rounds
         const dim3 grid(nrounds * mblocks * 8);

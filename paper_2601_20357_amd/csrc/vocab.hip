@@ -1,8 +1,9 @@
 // Vocabulary-wide passes of a TABED round on gfx950: ensemble + draft token (Alg. 1 lines 6-7),
-// target statistics + per-draft KL + accept chain (Sec. 3 items 2-3, Sec. 4.1), corrected / bonus token
+// target statistics + per-draft KL + accept chain (Sec. 3 items 2-3, Sec. 5.1), corrected / bonus token
 // (Sec. 3 item 3), window + weights (Alg. 1 lines 2-3, App. B.2).  All of them are HBM- or latency-bound:
 // DPP lane exchanges and a few LDS words do the reductions, fp64 carries the cross-wave and cross-workgroup
-// sums, and partial results cross workgroups through device-scope atomics (no fences).
+// sums, and partial results cross workgroups through device-scope atomic stores that are waited for before an
+// arrival counter moves (no cache-flushing fences).
 #include "device_utils.h"
 #include "internal.h"
 
@@ -515,7 +516,7 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
         publish_store(&rec->i1, t.i1);
         publish_store(&rec->v2, t.v2);
     }
-    __syncthreads();                                       // the candidate's stores are acknowledged
+    publish_barrier();                                     // the candidate's stores are acknowledged
     if (tid == 0) s_last = arrive(&a.tickets[b], (uint32_t)a.C2) ? 1 : 0;
     __syncthreads();
     if (!s_last || tid >= kWave) return;
@@ -1235,7 +1236,7 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
     if (greedy) {
         // a greedy row is complete here: its single workgroup also advances the window when asked to
         if (a.fuse) {
-            __syncthreads();                               // the distances above are acknowledged
+            publish_barrier();                             // the distances above are acknowledged
             if (tid < kWave) window_update<true>(a.win, b, lane, a.dev, nv_k, s_wpart, s_wx);
         }
         return;
@@ -1247,7 +1248,7 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
         // window + next weights, off the critical path of the sampler.  The weights are staged: the buffer
         // they go to may be the one the siblings are still reading this block's weights from.
         if (a.fuse && !a.hard) {
-            __syncthreads();                               // the distances above are acknowledged
+            publish_barrier();                             // the distances above are acknowledged
             if (tid < kWave) {
                 WindowArgs wa = a.win;
                 wa.weights = a.wstage;
@@ -1263,7 +1264,7 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
             if (lane == 0 && seg < NSEG) { publish_store(&segR[seg], mf); publish_store(&segP[seg], mp); }
         }
     }
-    __syncthreads();                                       // every wave's published stores are acknowledged
+    publish_barrier();                                     // every wave's published stores are acknowledged
     if (tid == 0) s_last = arrive(&a.tickets[b], (uint32_t)(a.C5 + 1)) ? 1 : 0;
     __syncthreads();
     if (!s_last) return;
@@ -1385,6 +1386,7 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         if (second_pass) {
+            ProfScope dprof(TABED_K_DIST, s);              // a dispatch of its own: its own event pair
             DistArgs d;
             d.V = c.V; d.n = c.n; d.B = c.B; d.gamma = c.gamma; d.C3 = C3; d.RS = L.RS; d.DW = L.DW; d.Cd = L.Cd;
             d.target = target_logits; d.dlogits = draft_logits; d.dlse = draft_lse; d.temperature = temperature;
@@ -1393,17 +1395,17 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
             const dim3 gd(L.Cd, c.gamma, c.B);
             const int mode = (c.distance == 2) ? (c.policy != 2 ? 3 : 4) : (c.policy != 2) ? 0 : (c.distance == 0 ? 1 : 2);
             if (vec) {
-                if (mode == 0) launch(&prof, k_dist<true, 0>, gd, dim3(kBlock), 0, s, d);
-                else if (mode == 1) launch(&prof, k_dist<true, 1>, gd, dim3(kBlock), 0, s, d);
-                else if (mode == 2) launch(&prof, k_dist<true, 2>, gd, dim3(kBlock), 0, s, d);
-                else if (mode == 3) launch(&prof, k_dist<true, 3>, gd, dim3(kBlock), 0, s, d);
-                else launch(&prof, k_dist<true, 4>, gd, dim3(kBlock), 0, s, d);
+                if (mode == 0) launch(&dprof, k_dist<true, 0>, gd, dim3(kBlock), 0, s, d);
+                else if (mode == 1) launch(&dprof, k_dist<true, 1>, gd, dim3(kBlock), 0, s, d);
+                else if (mode == 2) launch(&dprof, k_dist<true, 2>, gd, dim3(kBlock), 0, s, d);
+                else if (mode == 3) launch(&dprof, k_dist<true, 3>, gd, dim3(kBlock), 0, s, d);
+                else launch(&dprof, k_dist<true, 4>, gd, dim3(kBlock), 0, s, d);
             } else {
-                if (mode == 0) launch(&prof, k_dist<false, 0>, gd, dim3(kBlock), 0, s, d);
-                else if (mode == 1) launch(&prof, k_dist<false, 1>, gd, dim3(kBlock), 0, s, d);
-                else if (mode == 2) launch(&prof, k_dist<false, 2>, gd, dim3(kBlock), 0, s, d);
-                else if (mode == 3) launch(&prof, k_dist<false, 3>, gd, dim3(kBlock), 0, s, d);
-                else launch(&prof, k_dist<false, 4>, gd, dim3(kBlock), 0, s, d);
+                if (mode == 0) launch(&dprof, k_dist<false, 0>, gd, dim3(kBlock), 0, s, d);
+                else if (mode == 1) launch(&dprof, k_dist<false, 1>, gd, dim3(kBlock), 0, s, d);
+                else if (mode == 2) launch(&dprof, k_dist<false, 2>, gd, dim3(kBlock), 0, s, d);
+                else if (mode == 3) launch(&dprof, k_dist<false, 3>, gd, dim3(kBlock), 0, s, d);
+                else launch(&dprof, k_dist<false, 4>, gd, dim3(kBlock), 0, s, d);
             }
             e = hipGetLastError();
             if (e != hipSuccess) return e;

@@ -167,7 +167,7 @@ def test_sample_cdf_is_the_inverse_cdf(oracle):
     assert flag & oracle.FLAG_DEGENERATE
 
 
-# ------------------------------------------------------------------ Philox (structural pins only)
+# ------------------------------------------------------------------ Philox
 _M0, _M1 = 0xD2511F53, 0xCD9E8D57
 _W0, _W1 = 0x9E3779B9, 0xBB67AE85
 _MASK = 0xFFFFFFFF
@@ -205,6 +205,46 @@ def test_philox_is_the_keyed_bijection_of_its_definition(oracle):
         b = oracle.philox4x32_10(ctr, [1, 2])
         flips.append(sum(bin(int(x) ^ int(y)).count("1") for x, y in zip(a, b)))
     assert 50 < np.mean(flips) < 78
+
+
+def _rocrand_engine(tmp_path):
+    """rocRAND's Philox4x32-10 engine, compiled for the host from the library's public header."""
+    import ctypes as C
+    import shutil
+    import subprocess
+    src = os.path.join(os.path.dirname(__file__), "rocrand_philox_shim.cpp")
+    if shutil.which("g++") is None or not os.path.exists("/opt/rocm/include/rocrand/rocrand_philox4x32_10.h"):
+        pytest.skip("g++ or the rocRAND headers are not available")
+    so = str(tmp_path / "rocrand_philox_shim.so")
+    subprocess.run(["g++", "-O1", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", "-shared", "-fPIC", "-o", so, src],
+                   check=True)
+    lib = C.CDLL(so)
+    lib.shim_philox_next4.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_void_p]
+    lib.shim_philox_next4.restype = None
+    return lib
+
+
+def test_philox_matches_rocrand_engine_word_for_word(oracle, tmp_path):
+    """The generator IS Philox4x32-10: raw output words equal those of rocRAND's engine (another author's
+    implementation) for 4096 random 64-bit keys and full 128-bit counters, plus counters that carry between
+    words.  The library maps seed -> key, offset / 4 -> counter words 0-1, subsequence -> counter words 2-3."""
+    import ctypes as C
+    lib = _rocrand_engine(tmp_path)
+    rng = np.random.default_rng(11)
+    cases = [(0, 0, 0), (1, 0, 0), (0, 1, 0), (0, 0, 1), (2 ** 64 - 1, 2 ** 64 - 1, 2 ** 62 - 1), (5, 7, 2 ** 32 - 1),
+             (5, 7, 2 ** 32), (5, 2 ** 32, 9), (2 ** 32, 3, 9)]
+    cases += [tuple(int(x) for x in (rng.integers(0, 2 ** 64, dtype=np.uint64), rng.integers(0, 2 ** 64, dtype=np.uint64),
+                                     rng.integers(0, 2 ** 62, dtype=np.uint64))) for _ in range(4096)]
+    out = np.zeros(4, np.uint32)
+    for seed, sub, cnt in cases:
+        lib.shim_philox_next4(seed, sub, cnt * 4, out.ctypes.data_as(C.c_void_p))
+        ours = oracle.philox4x32_10([cnt & _MASK, cnt >> 32, sub & _MASK, sub >> 32], [seed & _MASK, seed >> 32])
+        assert np.array_equal(out, ours), (seed, sub, cnt)
+    # the method's own keying: key = seed, counter = (round lo, round hi, b, pos); u = (word >> 8) * 2^-24
+    for seed, rnd, b, pos in [(0, 0, 0, 0), (0x123456789ABCDEF, (1 << 40) + 5, 63, 15), (7, 3, 2, 1)]:
+        lib.shim_philox_next4(seed, b | (pos << 32), rnd * 4, out.ctypes.data_as(C.c_void_p))
+        for word in (0, 1):
+            assert oracle.uniform(seed, rnd, b, pos, word) == float(np.float32(int(out[word]) >> 8) * np.float32(2.0 ** -24))
 
 
 def test_uniforms_are_uniform_exact_and_keyed_by_seed_round_b_pos(oracle):
