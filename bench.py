@@ -80,7 +80,7 @@ def gen_inputs(wl, pool, w_copies, device):
         if wl.target == "independent":
             tgt = torch.randn(shape, generator=g, device=device) * wl.sigma
         else:
-            jstar = (r // 64) % wl.n if wl.target == "switching" else 0
+            jstar = (r // wl.switch_every) % wl.n if wl.target == "switching" else 0
             base = torch.einsum("ibk,vk->biv", H[:, :, jstar, :].float(), W.float())
             if wl.target == "student_t":
                 z = torch.randn(shape, generator=g, device=device)

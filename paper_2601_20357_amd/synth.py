@@ -34,6 +34,7 @@ class Workload:
     rounds: int
     sigma: float = 0.0
     temperature: str = "one"   # "one" | "greedy" | "mixed07"
+    switch_every: int = 64     # "switching" recipe: rounds after which the target follows the next draft
 
     @property
     def M(self) -> int:
@@ -110,6 +111,11 @@ def make_seq_sigma(wl: Workload) -> np.ndarray:
     return _rng(wl, 1).uniform(0.2, 1.5, size=wl.B).astype(np.float32)
 
 
+def matching_draft(wl: Workload, rnd: int) -> int:
+    """The draft whose logits the target's are built from in round `rnd`."""
+    return (rnd // wl.switch_every) % wl.n if wl.target == "switching" else 0
+
+
 def make_round(wl: Workload, W: np.ndarray, rnd: int):
     """Inputs of SD round `rnd`.
 
@@ -124,7 +130,7 @@ def make_round(wl: Workload, W: np.ndarray, rnd: int):
     shape = (wl.B, wl.gamma + 1, wl.V)
     if wl.target == "independent":
         return H, (g.standard_normal(shape, dtype=np.float32) * np.float32(wl.sigma))
-    jstar = (rnd // 64) % wl.n if wl.target == "switching" else 0
+    jstar = matching_draft(wl, rnd)
     Wf = as_f32(W, wl.w_dtype)
     Hj = as_f32(H, wl.w_dtype)[:, :, jstar, :]                        # [gamma+1, B, d]
     base = np.einsum("ibk,vk->biv", Hj, Wf, optimize=True).astype(np.float32)

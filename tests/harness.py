@@ -76,7 +76,8 @@ class GpuSide:
         self.fused = fused          # tabed_verify also opens the next round (window push + next weights)
         self.need_update = True
 
-    def round(self, rnd, W_t, H, target, temp, u_draft=None, u_acc=None, u_res=None):
+    def round(self, rnd, W_t, H, target, temp, u_draft=None, u_acc=None, u_res=None, rows=None):
+        """rows: indices of the sequences whose results are copied back (default: all of them)."""
         wl, buf = self.wl, self.buf
         t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV)
         temp_t, tgt_t = t(temp), t(target)
@@ -90,19 +91,29 @@ class GpuSide:
             buf.draft_step(rnd, pos, W_t, to_dev_store(H[pos], wl.w_dtype), temp_t, ud)
         buf.verify(rnd, tgt_t, temp_t, ua, ur, fused_update=self.fused)
         torch.cuda.synchronize()
-        c = lambda x: x.cpu().numpy()
-        return dict(weights=c(w_used), draft_logits=c(buf.draft_logits), draft_lse=c(buf.draft_lse),
+        if rows is None:
+            c = lambda x: x.cpu().numpy()
+            c1 = c
+        else:
+            idx = torch.as_tensor(np.asarray(rows), device=DEV, dtype=torch.long)
+            c = lambda x: x.index_select(0, idx).cpu().numpy()       # [B, ...]
+            c1 = lambda x: x.index_select(1, idx).cpu().numpy()      # [gamma, B, ...]
+        return dict(weights=c(w_used), draft_logits=c1(buf.draft_logits), draft_lse=c1(buf.draft_lse),
                     draft_tokens=c(buf.draft_tokens), draft_q=c(buf.draft_q), draft_flags=c(buf.draft_flags),
                     accept_len=c(buf.accept_len), out_tokens=c(buf.out_tokens), dev=c(buf.dev),
                     n_valid=c(buf.n_valid), flags=c(buf.verify_flags))
 
-    def resync_from(self, orc: OracleSide):
-        """After a flagged divergence: continue from the oracle's window state (HIP input <- oracle is allowed)."""
-        self.buf.ring.copy_(torch.from_numpy(orc.ring).to(DEV))
-        self.buf.ring_head.copy_(torch.from_numpy(orc.head).to(DEV))
-        self.buf.ring_count.copy_(torch.from_numpy(orc.count).to(DEV))
-        self.buf.dev.copy_(torch.from_numpy(orc.dev).to(DEV))
-        self.buf.n_valid.copy_(torch.from_numpy(orc.n_valid).to(DEV))
+    def resync_from(self, orc: OracleSide, rows=None):
+        """After a flagged divergence: continue from the oracle's window state (HIP input <- oracle is allowed).
+        rows: the sequences the oracle ran (default: all of them)."""
+        idx = slice(None) if rows is None else torch.as_tensor(np.asarray(rows), device=DEV, dtype=torch.long)
+        self.buf.ring[idx] = torch.from_numpy(orc.ring).to(DEV)
+        self.buf.ring_head[idx] = torch.from_numpy(orc.head).to(DEV)
+        self.buf.ring_count[idx] = torch.from_numpy(orc.count).to(DEV)
+        self.buf.dev[idx] = torch.from_numpy(orc.dev).to(DEV)
+        self.buf.n_valid[idx] = torch.from_numpy(orc.n_valid).to(DEV)
+        if rows is not None and not self.need_update:
+            raise AssertionError("a subset resync needs the separate window update (fused=False)")
         self.need_update = True     # fused mode: redo the push from the oracle's distances with the plain call
 
 
@@ -114,17 +125,87 @@ class Tally:
         self.max_q_rel = 0.0
         self.max_dev_err = 0.0
         self.max_w_err = 0.0
+        self.gpu_flags = 0          # decisions the GPU flagged as closer than 1e-6
+        self.oracle_flags = 0
+        self.gpu_only_flags = 0     # ... that the oracle did not flag (its own margin is then checked)
+        self.max_gpu_only_margin = 0.0
+
+    def count_flag(self, g_flag, o_flag, margin_fn):
+        """Book-keeping of one decision's margin flags.  A flag the GPU raises alone must correspond to a real
+        near-tie: the oracle-side margin of the same decision (fp64) has to be below 1e-5."""
+        self.gpu_flags += bool(g_flag)
+        self.oracle_flags += bool(o_flag)
+        if g_flag and not o_flag and margin_fn is not None:
+            m = float(margin_fn())
+            self.gpu_only_flags += 1
+            self.max_gpu_only_margin = max(self.max_gpu_only_margin, m)
+            assert m < 1e-5, f"the GPU flagged a decision whose oracle-side margin is {m:.3e}"
 
     def __repr__(self):
         return (f"decisions={self.decisions} flagged_divergences={self.flagged_divergences} "
+                f"gpu_flags={self.gpu_flags} oracle_flags={self.oracle_flags} gpu_only_flags={self.gpu_only_flags} "
                 f"max|dL|={self.max_logit_err:.2e} max rel dq={self.max_q_rel:.2e} "
                 f"max|ddev|={self.max_dev_err:.2e} max|dw|={self.max_w_err:.2e}")
 
 
-def compare_round(g, o, wl, tally: Tally, check_logits=True, hard=False):
-    """Element-by-element comparison of one round.  Returns True if every sequence stayed in lock-step;
-    False if a flagged decision diverged (the caller then resyncs the window state)."""
+class Margins:
+    """Oracle-side margin (fp64) of a decision of one round, computed on request from the oracle's own building
+    blocks: how close the decision was to going the other way, in the units the flags use."""
+
+    def __init__(self, oracle, wl, o, target, temp, seed, rnd, b_index, u_draft=None, u_acc=None, u_res=None):
+        self.o_, self.wl, self.o, self.target, self.temp = oracle, wl, o, target, temp
+        self.seed, self.rnd, self.b_index = seed, rnd, b_index      # b_index[b] = the sequence's Philox stream
+        self.u_draft, self.u_acc, self.u_res = u_draft, u_acc, u_res
+
+    def _t_eff(self, b):
+        return float(self.temp[b]) if self.temp[b] > 0 else 1.0
+
+    def _q_ens(self, b, pos):
+        o, wl = self.o_, self.wl
+        q = np.stack([o.softmax(self.o["draft_logits"][pos, b, j], self._t_eff(b))[0] for j in range(wl.n)])
+        return o.ensemble(q, self.o["weights"][b])
+
+    @staticmethod
+    def _cdf_margin(f, u, tok):
+        Z = float(f.sum())
+        cdf = np.cumsum(f)
+        m = np.inf
+        if tok + 1 < len(f):
+            m = min(m, abs(cdf[tok] - u * Z))
+        if tok > 0:
+            m = min(m, abs(cdf[tok - 1] - u * Z))
+        return m / Z
+
+    def draft(self, b, pos):
+        f = self._q_ens(b, pos)
+        if not self.temp[b] > 0:
+            top = np.sort(f)[-2:]
+            return (top[1] - top[0]) / abs(top[1])
+        u = self.u_draft[b, pos] if self.u_draft is not None else self.o_.uniform(self.seed, self.rnd, int(self.b_index[b]), pos, 0)
+        return self._cdf_margin(f, float(u), int(self.o["draft_tokens"][b, pos]))
+
+    def accept(self, b, i):
+        y = int(self.o["draft_tokens"][b, i])
+        p = self.o_.softmax(self.target[b, i], self._t_eff(b))[0]
+        u = self.u_acc[b, i] if self.u_acc is not None else self.o_.uniform(self.seed, self.rnd, int(self.b_index[b]), i, 1)
+        lhs, py = float(np.float32(u) * np.float32(self.o["draft_q"][b, i])), float(np.float32(p[y]))
+        return abs(lhs - py) / max(lhs, py)
+
+    def emitted(self, b, k):
+        p = self.o_.softmax(self.target[b, k], self._t_eff(b))[0]
+        f = p if k == self.wl.gamma else np.maximum(0.0, p - self._q_ens(b, k))
+        if not f.sum() > 0:
+            return 0.0
+        u = self.u_res[b] if self.u_res is not None else self.o_.uniform(self.seed, self.rnd, int(self.b_index[b]), self.wl.gamma, 0)
+        return self._cdf_margin(f, float(u), int(self.o["out_tokens"][b, k]))
+
+
+def compare_round(g, o, wl, tally: Tally, check_logits=True, hard=False, margins: Margins | None = None):
+    """Element-by-element comparison of one round (wl: the workload of the sequences compared).  Returns True
+    if every sequence stayed in lock-step; False if a flagged decision diverged (the caller then resyncs the
+    window state)."""
     B, n, gamma = wl.B, wl.n, wl.gamma
+    SM, AM = binding.FLAG_SAMPLE_MARGIN, binding.FLAG_ACCEPT_MARGIN
     np.testing.assert_allclose(g["weights"], o["weights"], rtol=1e-5, atol=1e-6)
     tally.max_w_err = max(tally.max_w_err, float(np.max(np.abs(g["weights"] - o["weights"]))))
     if check_logits:
@@ -138,8 +219,10 @@ def compare_round(g, o, wl, tally: Tally, check_logits=True, hard=False):
         alive = True      # this sequence still comparable in this round
         for pos in range(gamma):
             tally.decisions += 1
+            tally.count_flag(g["draft_flags"][b, pos] & SM, o["draft_flags"][b, pos] & SM,
+                             (lambda b=b, pos=pos: margins.draft(b, pos)) if margins else None)
             if g["draft_tokens"][b, pos] != o["draft_tokens"][b, pos]:
-                flagged = (g["draft_flags"][b, pos] | o["draft_flags"][b, pos]) & binding.FLAG_SAMPLE_MARGIN
+                flagged = (g["draft_flags"][b, pos] | o["draft_flags"][b, pos]) & SM
                 assert flagged, f"unflagged draft token mismatch b={b} pos={pos}: {g['draft_tokens'][b]} vs {o['draft_tokens'][b]}"
                 tally.flagged_divergences += 1
                 alive = False
@@ -159,9 +242,12 @@ def compare_round(g, o, wl, tally: Tally, check_logits=True, hard=False):
             continue
         tally.decisions += 1
         kg, ko = int(g["accept_len"][b]), int(o["accept_len"][b])
+        for i in range(min(min(kg, ko) + 1, gamma)):       # accept tests both sides evaluated
+            tally.count_flag(g["flags"][b, i] & AM, o["flags"][b, i] & AM,
+                             (lambda b=b, i=i: margins.accept(b, i)) if margins else None)
         if kg != ko:
             i = min(kg, ko)
-            flagged = (g["flags"][b, i] | o["flags"][b, i]) & binding.FLAG_ACCEPT_MARGIN
+            flagged = (g["flags"][b, i] | o["flags"][b, i]) & AM
             assert flagged, f"unflagged accept-length mismatch b={b}: {kg} vs {ko}"
             tally.flagged_divergences += 1
             lock = False
@@ -170,8 +256,10 @@ def compare_round(g, o, wl, tally: Tally, check_logits=True, hard=False):
         assert np.array_equal(g["out_tokens"][b, :ko], o["out_tokens"][b, :ko])
         assert np.all(g["out_tokens"][b, ko + 1:] == -1)
         tally.decisions += 1
+        tally.count_flag(g["flags"][b, ko] & SM, o["flags"][b, ko] & SM,
+                         (lambda b=b, ko=ko: margins.emitted(b, ko)) if margins else None)
         if g["out_tokens"][b, ko] != o["out_tokens"][b, ko]:
-            flagged = (g["flags"][b, ko] | o["flags"][b, ko]) & binding.FLAG_SAMPLE_MARGIN
+            flagged = (g["flags"][b, ko] | o["flags"][b, ko]) & SM
             assert flagged, f"unflagged emitted-token mismatch b={b} k={ko}: {g['out_tokens'][b]} vs {o['out_tokens'][b]}"
             tally.flagged_divergences += 1
             # the emitted token does not enter the window state (unless it is a hard label): still in lock-step
@@ -183,17 +271,43 @@ def compare_round(g, o, wl, tally: Tally, check_logits=True, hard=False):
 
 
 def run_rounds(oracle, wl, rounds, temp, seed=0, policy=0, check_logits=True, uniforms=None, W=None, distance=0,
-               fused=False):
-    """Drive both sides for `rounds` rounds with state carried over; returns the tally."""
+               fused=False, start_round=0, rows=None, on_round=None, max_gpu_flags=None):
+    """Drive both sides for `rounds` rounds with state carried over; returns the tally.
+
+    rows: the GPU runs all wl.B sequences, the oracle only these (sequences are independent: each has its own
+    window, weights, temperature and Philox stream b); their results are compared element by element.
+    on_round(rnd, g, o): extra assertions of the caller on the two sides' outputs (those sequences only).
+    Besides the comparison itself the run asserts that the GPU raises margin flags rarely (at most
+    max_gpu_flags, default 1 % of the decisions and never fewer than 2 allowed) and only on real near-ties."""
     W = synth.make_lm_head(wl) if W is None else W
     W_t = to_dev_store(W, wl.w_dtype)
-    orc, gpu = OracleSide(oracle, wl, seed, policy, distance=distance), GpuSide(wl, seed, policy, distance=distance, fused=fused)
+    b_index = np.arange(wl.B) if rows is None else np.asarray(rows)
+    wl_o = wl if rows is None else synth.scaled(wl, B=len(b_index))
+    assert rows is None or (policy != 3 and not fused), "a subset run needs per-sequence state only"
+    orc = OracleSide(oracle, wl_o, seed, policy, distance=distance)
+    gpu = GpuSide(wl, seed, policy, distance=distance, fused=fused)
     tally = Tally()
-    for rnd in range(rounds):
+    for rnd in range(start_round, start_round + rounds):
         H, target = synth.make_round(wl, W, rnd)
         u = uniforms(rnd) if uniforms else {}
-        o = orc.round(rnd, W, H, target, temp, **u)
-        g = gpu.round(rnd, W_t, H, target, temp, **u)
-        if not compare_round(g, o, wl, tally, check_logits, hard=(distance == 2)):
-            gpu.resync_from(orc)
+        g = gpu.round(rnd, W_t, H, target, temp, rows=rows, **u)
+        if rows is None:
+            H_o, target_o, temp_o, u_o = H, target, temp, u
+        else:
+            # the oracle sees the subset as sequences 0..len-1, so its Philox streams are handed over explicitly:
+            # the uniforms of the ORIGINAL sequence indices, drawn from the oracle's own generator
+            assert not u, "explicit uniforms and a subset are not combined"
+            H_o, target_o, temp_o = np.ascontiguousarray(H[:, b_index]), np.ascontiguousarray(target[b_index]), temp[b_index]
+            g_ = wl.gamma
+            u_o = dict(u_draft=np.array([[oracle.uniform(seed, rnd, int(b), p, 0) for p in range(g_)] for b in b_index], np.float32),
+                       u_acc=np.array([[oracle.uniform(seed, rnd, int(b), p, 1) for p in range(g_)] for b in b_index], np.float32),
+                       u_res=np.array([oracle.uniform(seed, rnd, int(b), g_, 0) for b in b_index], np.float32))
+        o = orc.round(rnd, W, H_o, target_o, temp_o, **u_o)
+        margins = Margins(oracle, wl_o, o, target_o, temp_o, seed, rnd, b_index, **{k: u_o.get(k) for k in ("u_draft", "u_acc", "u_res")})
+        if not compare_round(g, o, wl_o, tally, check_logits, hard=(distance == 2), margins=margins):
+            gpu.resync_from(orc, rows)
+        if on_round is not None:
+            on_round(rnd, g, o)
+    limit = max(2, tally.decisions // 100) if max_gpu_flags is None else max_gpu_flags
+    assert tally.gpu_flags <= limit, f"the GPU flagged {tally.gpu_flags} of {tally.decisions} decisions"
     return tally

@@ -30,6 +30,25 @@ def test_philox_uniforms_bit_equal_to_oracle(oracle):
         assert np.array_equal(got, ref)
 
 
+def test_philox_two_implementations_agree_on_a_million_counters(oracle):
+    """2^20 counters (round, b, pos), two words each: the HIP generator against the oracle's (which is itself
+    pinned against rocRAND's engine on the CPU)."""
+    import ctypes as C
+    B, npos = 16384, 32                                         # B * npos = 2^19 counters per round value
+    cfg = binding.make_cfg(V=8, d=8, n=1, B=B, gamma=npos - 1, h=1, w_dtype=0, seed=0xC0FFEE1234567)
+    out = torch.zeros((B, npos, 2), dtype=torch.float32, device=DEV)
+    lib = oracle.lib()
+    for rnd in (3, (1 << 33) + 9):
+        binding.tabed_philox_uniforms(cfg, rnd, out)
+        got = out.cpu().numpy()
+        ref = np.empty((B, npos, 2), np.float32)
+        for b in range(B):
+            for p in range(npos):
+                ref[b, p, 0] = lib.oracle_uniform(cfg.seed, rnd, b, p, 0)
+                ref[b, p, 1] = lib.oracle_uniform(cfg.seed, rnd, b, p, 1)
+        assert np.array_equal(got, ref), rnd
+
+
 # ------------------------------------------------------------------ the paper-scale tiny configuration, 64 rounds
 @pytest.mark.parametrize("mode", ["greedy", "one"])
 def test_tiny_64_rounds_state_carried(oracle, mode):
@@ -235,13 +254,67 @@ def test_lvlm_full_size(oracle):
 
 def test_stress_shape_fewer_sequences(oracle):
     """The stress vocabulary, hidden size, draft count and temperature mix (V=128256, d=2048, n=8, greedy and
-    T=0.7 rows, heavy-tailed target noise) on 12 sequences and 2 positions: 96 rows through the many-rows LM head.
-    The full 64-sequence shape differs only in the number of row blocks and is too slow for the oracle here."""
+    T=0.7 rows, heavy-tailed target noise) on 12 sequences and 2 positions: 96 rows through the many-rows LM head,
+    every sequence compared."""
     wl = synth.scaled(synth.WORKLOADS["stress"], B=12, gamma=2, cfg_id=95)
     _say("stress shape, 12 sequences")
     tally = harness.run_rounds(oracle, wl, 2, synth.make_temperature(wl))
     _say(tally)
     assert tally.flagged_divergences <= 3
+
+
+def test_stress_full_size_against_oracle_on_a_subset(oracle):
+    """The stress workload at its real size (V=128256, d=2048, n=8, B=64, gamma=5, h=16: 512 rows through the
+    many-rows LM head, two row blocks): the GPU runs all 64 sequences, the oracle a subset of six of them
+    (greedy and T=0.7 rows, first / middle / last row block), element by element, state carried over two rounds."""
+    wl = synth.WORKLOADS["stress"]
+    rows = [0, 1, 30, 33, 62, 63]
+    _say("stress full size, oracle on sequences " + str(rows))
+    tally = harness.run_rounds(oracle, wl, 2, synth.make_temperature(wl), rows=rows)
+    _say(tally)
+    assert tally.flagged_divergences <= 2
+
+
+def test_lvlm_full_size_across_a_draft_switch(oracle):
+    """The large-vocabulary workload at full size, rounds 60..73: the draft the target follows changes at round
+    64, the 16-entry window wraps, and on both sides the largest weight moves from the old matching draft to
+    the new one."""
+    wl = synth.WORKLOADS["lvlm"]
+    rows = [0, 3, 7]
+    seen = {}
+
+    def on_round(rnd, g, o):
+        seen[rnd] = (np.argmax(g["weights"], axis=1), np.argmax(o["weights"], axis=1), o["n_valid"].copy())
+        _say(f"  round {rnd}: matching draft {synth.matching_draft(wl, rnd)} argmax w gpu {seen[rnd][0]} oracle {seen[rnd][1]} "
+             f"n_valid {seen[rnd][2]}")
+
+    _say("lvlm full size across the switch at round 64")
+    tally = harness.run_rounds(oracle, wl, 14, synth.make_temperature(wl), start_round=60, rows=rows, on_round=on_round)
+    _say(tally)
+    assert tally.flagged_divergences <= 3
+    old, new = synth.matching_draft(wl, 63), synth.matching_draft(wl, 64)
+    assert old != new
+    # weights used in round 63 were learned from rounds 60..62 (old draft); the weights used in round 73 from a
+    # window that holds only positions verified after the switch (>= 16 of them in rounds 64..72)
+    assert np.all(seen[63][0] == old) and np.all(seen[63][1] == old)
+    assert np.all(sum(seen[r][2] for r in range(64, 73)) >= wl.h)       # every sequence's window has wrapped
+    assert np.all(seen[73][0] == new) and np.all(seen[73][1] == new)
+
+
+def test_lvlm_recipe_70_rounds_reduced_vocabulary(oracle):
+    """The same recipe (d=896, n=4, B=8, gamma=7, h=16, switch every 64 rounds) at a reduced vocabulary, all
+    sequences, state carried from round 0 across the switch: window wrap and adaptation through the same kernels."""
+    wl = synth.scaled(synth.WORKLOADS["lvlm"], V=4100)
+    last = {}
+
+    def on_round(rnd, g, o):
+        last[rnd] = (np.argmax(g["weights"], axis=1), np.argmax(o["weights"], axis=1))
+
+    tally = harness.run_rounds(oracle, wl, 72, synth.make_temperature(wl), on_round=on_round)
+    _say(tally)
+    assert tally.flagged_divergences <= 4
+    assert np.all(last[63][0] == 0) and np.all(last[63][1] == 0)
+    assert np.all(last[71][0] == 1) and np.all(last[71][1] == 1)
 
 
 def test_hip_graph_replay_matches_eager_bitwise(oracle):
