@@ -277,8 +277,11 @@ def run_rounds(oracle, wl, rounds, temp, seed=0, policy=0, check_logits=True, un
     rows: the GPU runs all wl.B sequences, the oracle only these (sequences are independent: each has its own
     window, weights, temperature and Philox stream b); their results are compared element by element.
     on_round(rnd, g, o): extra assertions of the caller on the two sides' outputs (those sequences only).
-    Besides the comparison itself the run asserts that the GPU raises margin flags rarely (at most
-    max_gpu_flags, default 1 % of the decisions and never fewer than 2 allowed) and only on real near-ties."""
+    Besides the comparison itself the run asserts that the GPU raises margin flags only on real near-ties: every
+    flag the oracle does not raise too is checked against the oracle-side margin of that decision (count_flag),
+    and there are few of those (at most max_gpu_flags, default 1 % of the decisions, never fewer than 2 allowed).
+    (Flags as such are not rare on flat distributions: with probabilities around 1/V = 2.5e-5 a uniform lands
+    within 1e-6 of a bin edge in 8 % of the draws, on both sides alike.)"""
     W = synth.make_lm_head(wl) if W is None else W
     W_t = to_dev_store(W, wl.w_dtype)
     b_index = np.arange(wl.B) if rows is None else np.asarray(rows)
@@ -309,5 +312,5 @@ def run_rounds(oracle, wl, rounds, temp, seed=0, policy=0, check_logits=True, un
         if on_round is not None:
             on_round(rnd, g, o)
     limit = max(2, tally.decisions // 100) if max_gpu_flags is None else max_gpu_flags
-    assert tally.gpu_flags <= limit, f"the GPU flagged {tally.gpu_flags} of {tally.decisions} decisions"
+    assert tally.gpu_only_flags <= limit, f"the GPU alone flagged {tally.gpu_only_flags} of {tally.decisions} decisions"
     return tally
