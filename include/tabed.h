@@ -65,6 +65,7 @@ extern "C" {
 #define TABED_EALIGN (-4)       /* a base pointer is not 16-byte aligned              */
 #define TABED_EUNSUPPORTED (-5) /* valid request this build does not implement        */
 #define TABED_EHIP (-6)         /* a kernel launch failed (see tabed_last_hip_error)  */
+#define TABED_ETOOBIG (-7)      /* cfg needs more scratch than tabed_draft_step_static's built-in buffer */
 
 #define TABED_FLAG_ACCEPT_MARGIN 1u /* accept test u*q < p closer than 1e-6 relative          */
 #define TABED_FLAG_SAMPLE_MARGIN 2u /* CDF crossing / arg-max runner-up closer than 1e-6      */
@@ -132,6 +133,28 @@ int tabed_draft_step(const tabed_cfg* cfg, void* ws, uint64_t round, int32_t pos
                      const float* u_draft,
                      float* draft_logits, double* draft_lse, int32_t* draft_tokens, float* draft_q,
                      uint8_t* flags, void* stream);
+
+/*
+ * tabed_draft_step without a workspace argument, for callers that cannot allocate device memory at all: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels
+ * and bit-identical results; the scratch memory is a buffer of TABED_STATIC_SCRATCH_BYTES built into the
+ * library's code object (every GPU the library runs on holds one copy until the process ends), so the call
+ * neither allocates nor frees anything, directly or through a library.
+ *   - returns TABED_ETOOBIG when tabed_workspace_bytes(cfg) exceeds TABED_STATIC_SCRATCH_BYTES (e.g. the
+ *     512-row stress shape); nothing is enqueued then.
+ *   - every call on a GPU uses that GPU's one buffer, which keeps the previous call's contents; the call
+ *     clears what must start at zero itself (a fill kernel on `stream`).  Calls that overlap on one GPU
+ *     (different streams, or threads) race on it: serialise them, or use tabed_draft_step with one
+ *     workspace per stream.
+ *   - the buffer's device address is looked up on the first call on each device (with that device current);
+ *     make that first call outside graph capture.
+ */
+#define TABED_STATIC_SCRATCH_BYTES (8u << 20)
+int tabed_draft_step_static(const tabed_cfg* cfg, uint64_t round, int32_t pos,
+                            const void* W, const void* H, const float* weights, const float* temperature,
+                            const float* u_draft,
+                            float* draft_logits, double* draft_lse, int32_t* draft_tokens, float* draft_q,
+                            uint8_t* flags, void* stream);
 
 /*
  * Sec. 3 items 2-3 for all B sequences, given the target's logits at the

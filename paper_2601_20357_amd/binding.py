@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libtabed.so")
 
 EXPORTS = [
     "tabed_workspace_bytes", "tabed_workspace_init", "tabed_strerror", "tabed_last_hip_error", "tabed_dev_width",
-    "tabed_draft_step", "tabed_verify", "tabed_update_weights", "tabed_philox_uniforms",
+    "tabed_draft_step", "tabed_draft_step_static", "tabed_verify", "tabed_update_weights", "tabed_philox_uniforms",
     "tabed_prof_enable", "tabed_prof_read", "tabed_prof_reset", "tabed_kernel_name", "tabed_prof_null",
 ]
 
@@ -58,6 +58,8 @@ def load():
     lib.tabed_last_hip_error.restype = C.c_int
     lib.tabed_draft_step.restype = C.c_int
     lib.tabed_draft_step.argtypes = [cfgp, vp, u64, i32] + [vp] * 11
+    lib.tabed_draft_step_static.restype = C.c_int
+    lib.tabed_draft_step_static.argtypes = [cfgp, u64, i32] + [vp] * 11
     lib.tabed_verify.restype = C.c_int
     lib.tabed_verify.argtypes = [cfgp, vp, u64] + [vp] * 19
     lib.tabed_update_weights.restype = C.c_int
@@ -156,6 +158,28 @@ def tabed_draft_step(cfg, ws, rnd, pos, W, H, weights, temperature, draft_logits
         _ptr(draft_tokens, torch.int32, B * g, "draft_tokens"), _ptr(draft_q, torch.float32, B * g, "draft_q"),
         _ptr(flags, torch.uint8, B * g, "flags"), _stream(stream))
     _check(rc, "tabed_draft_step")
+
+
+STATIC_SCRATCH_BYTES = 8 << 20
+ETOOBIG = -7
+
+
+def tabed_draft_step_static(cfg, rnd, pos, W, H, weights, temperature, draft_logits, draft_lse, draft_tokens,
+                            draft_q, flags, u_draft=None, stream=None):
+    """tabed_draft_step on the library's built-in scratch buffer (no workspace argument, nothing allocated)."""
+    import torch
+    V, d, n, B, g = cfg.V, cfg.d, cfg.n, cfg.B, cfg.gamma
+    sd = _store_dtype(cfg)
+    rc = load().tabed_draft_step_static(
+        C.byref(cfg), rnd, pos,
+        _ptr(W, sd, V * d, "W"), _ptr(H, sd, B * n * d, "H"),
+        _ptr(weights, torch.float32, B * n, "weights"), _ptr(temperature, torch.float32, B, "temperature"),
+        _ptr(u_draft, torch.float32, B * g, "u_draft"),
+        _ptr(draft_logits, torch.float32, g * B * n * V, "draft_logits"),
+        _ptr(draft_lse, torch.float64, g * B * n, "draft_lse"),
+        _ptr(draft_tokens, torch.int32, B * g, "draft_tokens"), _ptr(draft_q, torch.float32, B * g, "draft_q"),
+        _ptr(flags, torch.uint8, B * g, "flags"), _stream(stream))
+    _check(rc, "tabed_draft_step_static")
 
 
 def tabed_verify(cfg, ws, rnd, target_logits, draft_logits, draft_lse, draft_tokens, draft_q, weights, temperature,

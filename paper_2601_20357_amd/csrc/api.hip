@@ -88,6 +88,32 @@ static int fail_hip(hipError_t e) {
 }
 static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
+// ---------------------------------------------------------------- built-in scratch of tabed_draft_step_static
+// One array per GPU, part of the loaded code object, so no call ever allocates it.  `scratch` is only a
+// host-side handle: the array's device address on the current GPU comes from hipGetSymbolAddress, looked up once
+// per device, and that pointer is what kernels and launchers receive.
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[TABED_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kMaxDevices];
+
+static int static_scratch(char** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e);
+    if (dev < 0 || dev >= kMaxDevices) return TABED_ERANGE;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return fail_hip(e);
+        if (p == nullptr) return fail_hip(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<char*>(g_scratch_ptr[dev]);
+    return TABED_OK;
+}
+
 }  // namespace tabed
 
 using namespace tabed;
@@ -122,6 +148,7 @@ const char* tabed_strerror(int code) {
         case TABED_EALIGN: return "a base pointer is not 16-byte aligned";
         case TABED_EUNSUPPORTED: return "valid request that this build does not implement";
         case TABED_EHIP: return "a kernel launch failed";
+        case TABED_ETOOBIG: return "the configuration needs more scratch than the built-in buffer holds";
         default: return "unknown error code";
     }
 }
@@ -145,6 +172,33 @@ int tabed_draft_step(const tabed_cfg* cfg, void* ws, uint64_t round, int32_t pos
     if (e != hipSuccess) return fail_hip(e);
     e = launch_sample(*cfg, L, static_cast<char*>(ws), round, pos, slot, weights, temperature, u_draft, draft_lse,
                       draft_tokens, draft_q, flags, s);
+    return e == hipSuccess ? TABED_OK : fail_hip(e);
+}
+
+int tabed_draft_step_static(const tabed_cfg* cfg, uint64_t round, int32_t pos, const void* W, const void* H,
+                            const float* weights, const float* temperature, const float* u_draft,
+                            float* draft_logits, double* draft_lse, int32_t* draft_tokens, float* draft_q,
+                            uint8_t* flags, void* stream) {
+    const int rc = validate_cfg(cfg);
+    if (rc != TABED_OK) return rc;
+    if (!W || !H || !weights || !temperature || !draft_logits || !draft_lse || !draft_tokens || !draft_q || !flags)
+        return TABED_ENULL;
+    if (pos < 0 || pos >= cfg->gamma) return TABED_ERANGE;
+    if (misaligned(W) || misaligned(H) || misaligned(draft_logits) || misaligned(draft_lse)) return TABED_EALIGN;
+    const WsLayout L = ws_layout(*cfg);
+    if (L.total > (size_t)TABED_STATIC_SCRATCH_BYTES) return TABED_ETOOBIG;
+    char* ws = nullptr;
+    const int rs = static_scratch(&ws);
+    if (rs != TABED_OK) return rs;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // the array keeps whatever the last call (of any configuration) left: the arrival counters start at zero
+    hipError_t e = launch_ws_init(*cfg, L, ws, s);
+    if (e != hipSuccess) return fail_hip(e);
+    float* slot = draft_logits + (size_t)pos * L.M * cfg->V;
+    e = launch_lmhead(*cfg, L, ws, W, H, temperature, slot, s);
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_sample(*cfg, L, ws, round, pos, slot, weights, temperature, u_draft, draft_lse, draft_tokens, draft_q,
+                      flags, s);
     return e == hipSuccess ? TABED_OK : fail_hip(e);
 }
 
