@@ -23,9 +23,36 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# HBM bytes per LM-head launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each in its own run, scaled by what
-# the counters read for a plain 256 MiB device copy): profiles/serving_hbm_traffic.md.  None = not measured.
-MEASURED_LMHEAD_TRAFFIC_BYTES = {"serving": (50.06 + 9.22) * 1e6}
+
+
+def source_digest():
+    """Short digest of the kernel sources: a traffic figure measured on other sources is not reported."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("device_utils.h", "internal.h", "lmhead.hip", "vocab.hip", "api.hip"):
+        with open(os.path.join(ROOT, "paper_2601_20357_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload
+    (profiles/<workload>_hbm_traffic.md, FETCH_SIZE and WRITE_SIZE each in a run of its own, scaled by a plain
+    device copy).  The summary carries a machine-readable line
+        traffic-bytes-per-launch: <kernel>=<bytes> ... sources=<digest>
+    Returns (bytes or None, note): None when there is no summary or it was measured on other kernel sources."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.md")
+    if not os.path.exists(path):
+        return None, "no rocprofv3 --pmc summary for this workload"
+    for line in open(path):
+        if line.startswith("traffic-bytes-per-launch:"):
+            fields = dict(f.split("=", 1) for f in line.split(":", 1)[1].split())
+            if fields.get("sources") != source_digest():
+                return None, f"{os.path.relpath(path, ROOT)} was measured on other kernel sources ({fields.get('sources')})"
+            if kernel in fields:
+                return float(fields[kernel]), f"{os.path.relpath(path, ROOT)} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, same kernel sources)"
+    return None, "summary holds no figure for this kernel"
+
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
@@ -40,7 +67,9 @@ def parse():
     ap.add_argument("--pool", type=int, default=8, help="distinct pre-generated rounds (and W copies) cycled through")
     ap.add_argument("--w-copies", type=int, default=8, help="device copies of W rotated per round (1 = warm cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rounds", type=int, default=60)
+    ap.add_argument("--cpu-rounds", type=int, default=0,
+                    help="rounds of the oracle's timed sample (0 = a workload-dependent default of 10-30 s)")
+    ap.add_argument("--print-source-digest", action="store_true", help="print the kernel-source digest and exit")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--separate-update", action="store_true",
                     help="call tabed_update_weights at the start of every round instead of letting tabed_verify "
@@ -96,23 +125,38 @@ def gen_inputs(wl, pool, w_copies, device):
     return Ws, Hs, Ts, temp.float().contiguous()
 
 
+CPU_SAMPLE = {"tiny": (2000, None), "llava": (120, None), "serving": (60, None), "lvlm": (4, None), "stress": (1, 8)}
+
+
 def cpu_baseline(wl, rounds):
-    """The oracle as it stands, on this machine's host cores, on `rounds` rounds of the same workload."""
+    """The oracle as it stands, on this machine's host cores, on a bounded sample of the same workload: `rounds` full
+    rounds, or -- where one round of all sequences takes minutes (stress) -- the first few sequences of a round,
+    scaled by their share (the oracle's work is per sequence)."""
     import numpy as np
     import oracle
     from paper_2601_20357_amd import synth
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     import harness
+    default_rounds, seqs = CPU_SAMPLE[wl.name]
+    rounds = rounds or default_rounds
     W = synth.make_lm_head(wl)
     temp = synth.make_temperature(wl)
-    side = harness.OracleSide(oracle, wl)
     inputs = [synth.make_round(wl, W, r) for r in range(rounds)]
+    wl_o = wl
+    if seqs is not None and seqs < wl.B:
+        wl_o = synth.scaled(wl, B=seqs)
+        temp = temp[:seqs]
+        inputs = [(np.ascontiguousarray(H[:, :seqs]), np.ascontiguousarray(t[:seqs])) for H, t in inputs]
+    side = harness.OracleSide(oracle, wl_o)
     t0 = time.perf_counter()
     for r, (H, tgt) in enumerate(inputs):
         side.round(r, W, H, tgt, temp)
     dt = time.perf_counter() - t0
-    return {"value": rounds / dt, "unit": "steps/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"{rounds} full rounds of the {wl.name} workload (all B={wl.B} sequences), {dt:.1f} s"}
+    share = wl_o.B / wl.B
+    what = (f"{rounds} full rounds of the {wl.name} workload (all B={wl.B} sequences)" if share == 1.0 else
+            f"{rounds} round(s) of the first {wl_o.B} of the {wl.name} workload's {wl.B} sequences, rate scaled by {share:.4f}")
+    return {"value": rounds / dt * share, "unit": "steps/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{what}, {dt:.1f} s"}
 
 
 def main():
@@ -121,6 +165,9 @@ def main():
         print("bench.py: this build runs on ONE GPU; "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
+    if args.print_source_digest:
+        print(source_digest())
+        return
     import torch
     from paper_2601_20357_amd import binding, synth
 
@@ -194,41 +241,50 @@ def main():
     torch.cuda.synchronize()
 
     launch = args.launch
-    if launch == "graph" and args.steps % args.pool != 0:
-        launch = "eager"                      # a replay is one pass over the pool: steps must be a multiple of it
+    every = [upd, upd_first] + [c for drafts, ver in slots for c in drafts + [ver]]
+
+    def set_stream(handle):
+        import ctypes as C
+        for c in every:
+            c.args[-1] = C.c_void_p(handle)
+
     if launch == "graph":
         try:
-            # Capture one pass over the pool (pool x (1 + gamma) C-ABI calls, two kernels each) on a side stream
-            # and replay it: the library enqueues only kernels (no memset, no allocation, no sync), so the same
-            # calls are capturable as they are.  The round counter of a captured call is fixed, so the Philox
+            # Capture one pass over the pool (pool x (1 + gamma) C-ABI calls) on a side stream and replay it: the
+            # library enqueues only kernels (no memset, no allocation, no sync), so the same calls are capturable
+            # as they are.  K steps = K // pool replays of that graph plus one replay of a second graph holding
+            # the first K % pool rounds of the pool.  The round counter of a captured call is fixed, so the Philox
             # uniforms repeat with the pool, like the inputs do; the window state still evolves across replays.
-            import ctypes as C
             side = torch.cuda.Stream()
-            every = [upd, upd_first] + [c for drafts, ver in slots for c in drafts + [ver]]
-            for c in every:
-                c.args[-1] = C.c_void_p(side.cuda_stream)
-            graph = torch.cuda.CUDAGraph()
+            set_stream(side.cuda_stream)
+            full, rem = args.steps // args.pool, args.steps % args.pool
+            graph, graph_rem = torch.cuda.CUDAGraph(), (torch.cuda.CUDAGraph() if rem else None)
             with torch.cuda.stream(side):
+                state["step"] = args.pool * ((state["step"] + args.pool - 1) // args.pool)   # a replay starts at slot 0
                 for _ in range(args.pool):
                     step()                        # once eagerly on the side stream
                 side.synchronize()
                 with torch.cuda.graph(graph, stream=side):
                     for _ in range(args.pool):
                         step()
+                if rem:
+                    with torch.cuda.graph(graph_rem, stream=side):
+                        for _ in range(rem):
+                            step()
+                    state["step"] += args.pool - rem
             torch.cuda.synchronize()
             graph.replay()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            for _ in range(args.steps // args.pool):
+            for _ in range(full):
                 graph.replay()
+            if rem:
+                graph_rem.replay()
             torch.cuda.synchronize()
             dt = time.perf_counter() - t0
-            for c in every:                       # back to the default stream for the instrumented pass
-                c.args[-1] = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+            set_stream(torch.cuda.current_stream().cuda_stream)   # back to the default stream for the instrumented pass
         except Exception as exc:                   # a capture that fails must not cost the measurement
-            import ctypes as C
-            for c in [upd, upd_first] + [c for drafts, ver in slots for c in drafts + [ver]]:
-                c.args[-1] = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+            set_stream(torch.cuda.current_stream().cuda_stream)
             torch.cuda.synchronize()
             launch = f"eager (graph capture failed: {type(exc).__name__})"
             dt = timed(args.steps)
@@ -242,7 +298,18 @@ def main():
     roofline = None
     M = wl.n * wl.B
     esz = 4 if wl.w_dtype == 0 else 2
-    lm_bytes = wl.V * wl.d * esz + M * wl.V * 4 + M * wl.d * esz      # W once + logits written once + H
+    NT = (wl.V + 31) // 32
+    n_sampling = int((temp > 0).sum().item())
+    # algorithmic bytes per launch: what the method must move, each logit written once and read once
+    alg_bytes = {
+        "lmhead": wl.V * wl.d * esz + M * wl.V * 4 + M * wl.d * esz,            # W once + logits once + H
+        "sample": M * NT * 8 + n_sampling * wl.n * 32 * 4                         # softmax partials + one tile per row
+                  + (wl.B - n_sampling) * wl.n * wl.V * 4,                        # greedy rows: the whole row
+        "stats": wl.B * (wl.gamma + 1) * wl.V * 4 + wl.gamma * M * wl.V * 4,     # target rows + draft rows
+        "resid": n_sampling * (1 + wl.n) * wl.V * 4,                              # one target row + n draft rows
+        "dist": wl.B * wl.gamma * (1 + wl.n) * wl.V * 4,
+    }
+    lm_bytes = alg_bytes["lmhead"]
     lm_flops = 2.0 * M * wl.d * wl.V
     if not args.no_kernel_timing:
         binding.tabed_prof_reset()
@@ -254,9 +321,15 @@ def main():
         for kid in range(binding.K_COUNT):
             ms, cnt = binding.tabed_prof_read(kid)
             if cnt:
-                kernels[binding.tabed_kernel_name(kid)] = {"avg_us": ms / cnt * 1e3, "launches": cnt}
+                name = binding.tabed_kernel_name(kid)
+                us = ms / cnt * 1e3
+                kernels[name] = {"avg_us": us, "launches": cnt}
+                if name in alg_bytes:
+                    gbs = alg_bytes[name] / (us * 1e-6) / 1e9
+                    kernels[name].update(algorithmic_bytes=alg_bytes[name], achieved_gbs=gbs,
+                                         frac_of_hbm_peak=gbs / HBM_PEAK_GBS)
         # the same pass with a fresh W copy for EVERY LM-head launch: all launches stream W from HBM
-        saved = slots
+        saved = list(slots)
         slots[:] = make_slots(True)
         binding.tabed_prof_reset()
         binding.tabed_prof_enable(True)
@@ -264,22 +337,33 @@ def main():
         binding.tabed_prof_enable(False)
         cold_ms, cold_cnt = binding.tabed_prof_read(binding.K_LMHEAD)
         cold_us = cold_ms / max(cold_cnt, 1) * 1e3
-        slots[:] = saved if saved is not slots else make_slots(False)
+        slots[:] = saved
         lm_us = kernels["lmhead"]["avg_us"]                 # events attached to the dispatch: the kernel's own time
         null_us = kernels.get("null", {}).get("avg_us", 0.0)
-        achieved = lm_bytes / (lm_us * 1e-6) / 1e9
-        roofline = {"kernel": "lmhead", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_LMHEAD_TRAFFIC_BYTES.get(wl.name),
-                    "algorithmic_bytes_per_launch": lm_bytes, "avg_launch_us": lm_us,
-                    "empty_kernel_us": null_us,
-                    "every_launch_fresh_w": {"avg_launch_us": cold_us, "achieved": lm_bytes / (cold_us * 1e-6) / 1e9,
-                                             "frac": lm_bytes / (cold_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
-                    "mfma_tflops": lm_flops / (lm_us * 1e-6) / 1e12,
-                    "mfma_frac_of_bf16_peak": lm_flops / (lm_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                    "instrumented_ms_per_step": dt_inst / args.steps * 1e3}
+        gbs = lm_bytes / (lm_us * 1e-6) / 1e9
+        tflops = lm_flops / (lm_us * 1e-6) / 1e12
+        kernels["lmhead"].update(flops=lm_flops, achieved_tflops=tflops, frac_of_bf16_mfma_peak=tflops / MFMA_BF16_PEAK_TFLOPS)
+        # the LM head is the dominant kernel; it is bound by the matrix cores only when its intensity
+        # (flop per algorithmic byte) exceeds the ridge of the chip, i.e. at several hundred rows
+        mfma_bound = wl.w_dtype == 1 and lm_flops / lm_bytes > MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
+        traffic, traffic_note = measured_traffic(wl.name, "lmhead")
+        roofline = {"kernel": "lmhead"}
+        if mfma_bound:
+            roofline.update(bound="mfma", achieved=tflops, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                            frac=tflops / MFMA_BF16_PEAK_TFLOPS)
+        else:
+            roofline.update(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s", frac=gbs / HBM_PEAK_GBS)
+        roofline.update(traffic=traffic, traffic_source=traffic_note,
+                        algorithmic_bytes_per_launch=lm_bytes, flops_per_launch=lm_flops, avg_launch_us=lm_us,
+                        empty_kernel_us=null_us,
+                        every_launch_fresh_w={"avg_launch_us": cold_us, "achieved_gbs": lm_bytes / (cold_us * 1e-6) / 1e9,
+                                              "frac_of_hbm_peak": lm_bytes / (cold_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
+                        hbm_gbs=gbs, frac_of_hbm_peak=gbs / HBM_PEAK_GBS,
+                        mfma_tflops=tflops, mfma_frac_of_bf16_peak=tflops / MFMA_BF16_PEAK_TFLOPS,
+                        instrumented_ms_per_step=dt_inst / args.steps * 1e3)
 
-    round_bytes = wl.gamma * (lm_bytes + 0) + (wl.B * (wl.gamma + 1) * wl.V * 4 + wl.gamma * M * wl.V * 4) \
-        + wl.B * (1 + wl.n) * wl.V * 4
+    round_bytes = wl.gamma * (lm_bytes + alg_bytes["sample"]) + alg_bytes["stats"] + alg_bytes["resid"] \
+        + (alg_bytes["dist"] if (args.distance != 0 or args.policy == 2) else 0)
     out = {
         "metric": ("ensemble-draft+verify steps/sec at V=32k,n=4,B=16; HBM GB/s & MFMA % of peak"
                    if wl.name == "serving" else "ensemble-draft+verify steps/sec"),
@@ -296,7 +380,8 @@ def main():
         "cpu_baseline": None,
         "detail": {"kernels": kernels, "mean_tokens_per_round": emitted,
                    "round_algorithmic_bytes": round_bytes,
-                   "round_frac_of_hbm_roofline": round_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                   "round_frac_of_hbm_roofline": round_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                   "kernel_source_digest": source_digest()},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_rounds)

@@ -31,5 +31,22 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+MICRO_SRC = os.path.join(HERE, "microbench", "chip_costs.hip")
+MICRO_BIN = os.path.join(HERE, "microbench", "chip_costs")
+
+
+def build_microbench(verbose: bool = False) -> str:
+    """The stand-alone fixed-cost microbenchmark (launch overhead, streaming reads, hand-over variants)."""
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-o", MICRO_BIN, MICRO_SRC]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stderr)
+    return MICRO_BIN
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_microbench(verbose=True))

@@ -1,0 +1,130 @@
+// Fixed costs of an MI355X that shaped the TABED kernels: launch-to-launch overhead, streaming reads of a
+// cache-resident and of an HBM-sized buffer, dependent-load round trips, and what it costs to hand partial
+// results from one workgroup to another (agent-scope fence vs. write-through stores that are waited for).
+// Stand-alone: hipcc --offload-arch=gfx950 -O3 chip_costs.hip -o chip_costs ; ./chip_costs
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <vector>
+
+#define CK(x)                                                                          \
+    do {                                                                               \
+        hipError_t e_ = (x);                                                           \
+        if (e_ != hipSuccess) {                                                        \
+            printf("HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__);      \
+            return 1;                                                                  \
+        }                                                                              \
+    } while (0)
+
+__global__ void k_empty() {}
+
+// `hops` dependent loads, one lane per workgroup matters: the time per hop is one memory round trip.
+__global__ void k_chain(const int* __restrict__ next, int start, int hops, int* out) {
+    int p = start;
+    for (int i = 0; i < hops; ++i) p = next[p];
+    if (threadIdx.x == 0) out[blockIdx.x] = p;
+}
+
+__global__ void k_read(const float4* __restrict__ a, float* out, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    float acc = 0.f;
+    for (; i < n; i += stride) {
+        const float4 v = a[i];
+        acc += v.x + v.y + v.z + v.w;
+    }
+    if (acc == 12345.678f) out[0] = acc;           // never true: keeps the loads alive
+}
+
+// Hand-over variants: every workgroup writes 256 floats, then one thread bumps a counter.
+__global__ void k_handover_fence_all(int* counter, float* buf) {
+    buf[blockIdx.x * 256 + threadIdx.x] = 1.f;
+    __threadfence();
+    if (threadIdx.x == 0) atomicAdd(counter, 1);
+}
+__global__ void k_handover_fence_one(int* counter, float* buf) {
+    buf[blockIdx.x * 256 + threadIdx.x] = 1.f;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        atomicAdd(counter, 1);
+    }
+}
+__global__ void k_handover_published(int* counter, float* buf) {
+    __hip_atomic_store(&buf[blockIdx.x * 256 + threadIdx.x], 1.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__global__ void k_handover_nothing(int* counter, float* buf) {
+    buf[blockIdx.x * 256 + threadIdx.x] = 1.f;
+    __syncthreads();
+    if (threadIdx.x == 0) __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+int main() {
+    const size_t NI = 64u << 20;                    // 256 MB of ints: a 1 MB stride never revisits a line soon
+    int* next;
+    CK(hipMalloc(&next, NI * sizeof(int)));
+    {
+        std::vector<int> h(NI);
+        const size_t stride = (1u << 20) / 4 + 16;
+        for (size_t i = 0; i < NI; ++i) h[i] = (int)((i + stride) % NI);
+        CK(hipMemcpy(next, h.data(), NI * sizeof(int), hipMemcpyHostToDevice));
+    }
+    int* out;
+    CK(hipMalloc(&out, 1 << 20));
+    CK(hipMemset(out, 0, 1 << 20));
+    float4* a;
+    const size_t NB = 1024u << 20;
+    CK(hipMalloc(&a, NB));
+    CK(hipMemset(a, 0, NB));
+    float* small;
+    CK(hipMalloc(&small, 4u << 20));
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0));
+    CK(hipEventCreate(&e1));
+    auto time_us = [&](auto fn, int reps) {
+        fn();
+        (void)hipDeviceSynchronize();
+        (void)hipEventRecord(e0, 0);
+        for (int i = 0; i < reps; ++i) fn();
+        (void)hipEventRecord(e1, 0);
+        (void)hipEventSynchronize(e1);
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        return (double)ms * 1e3 / reps;
+    };
+    printf("%-58s %9s\n", "measurement (back-to-back launches on one stream)", "us/launch");
+    printf("%-58s %9.2f\n", "empty kernel, 1 workgroup x 64", time_us([&] { hipLaunchKernelGGL(k_empty, dim3(1), dim3(64), 0, 0); }, 500));
+    printf("%-58s %9.2f\n", "empty kernel, 1024 workgroups x 256",
+           time_us([&] { hipLaunchKernelGGL(k_empty, dim3(1024), dim3(256), 0, 0); }, 500));
+    for (size_t mb : {8, 57, 512, 1024}) {
+        const size_t n = mb * (1u << 20) / 16;
+        const double us = time_us([&] { hipLaunchKernelGGL(k_read, dim3(2048), dim3(256), 0, 0, a, (float*)out, n); }, mb > 100 ? 20 : 100);
+        char nm[96];
+        snprintf(nm, sizeof nm, "read %zu MiB, same buffer every launch", mb);
+        printf("%-58s %9.2f   %7.2f TB/s\n", nm, us, (double)mb * 1048576.0 / us * 1e-6);
+    }
+    int start = 0;
+    double cold1 = 0, cold17 = 0;
+    cold1 = time_us([&] { hipLaunchKernelGGL(k_chain, dim3(16), dim3(64), 0, 0, next, start, 1, out); start = (start + 4099) % (int)NI; }, 200);
+    cold17 = time_us([&] { hipLaunchKernelGGL(k_chain, dim3(16), dim3(64), 0, 0, next, start, 17, out); start = (start + 4099) % (int)NI; }, 200);
+    printf("%-58s %9.2f\n", "1 dependent load, never-seen address", cold1);
+    printf("%-58s %9.2f   %7.2f us per extra hop\n", "17 dependent loads, never-seen addresses", cold17, (cold17 - cold1) / 16);
+    const double warm1 = time_us([&] { hipLaunchKernelGGL(k_chain, dim3(16), dim3(64), 0, 0, next, 0, 1, out); }, 200);
+    const double warm17 = time_us([&] { hipLaunchKernelGGL(k_chain, dim3(16), dim3(64), 0, 0, next, 0, 17, out); }, 200);
+    printf("%-58s %9.2f   %7.2f us per extra hop\n", "17 dependent loads, same addresses every launch", warm17, (warm17 - warm1) / 16);
+    for (int wgs : {128, 768}) {
+        char nm[96];
+        snprintf(nm, sizeof nm, "hand-over, %d workgroups: no ordering at all", wgs);
+        printf("%-58s %9.2f\n", nm, time_us([&] { hipLaunchKernelGGL(k_handover_nothing, dim3(wgs), dim3(256), 0, 0, out, small); }, 200));
+        snprintf(nm, sizeof nm, "hand-over, %d workgroups: published stores + wait", wgs);
+        printf("%-58s %9.2f\n", nm, time_us([&] { hipLaunchKernelGGL(k_handover_published, dim3(wgs), dim3(256), 0, 0, out, small); }, 200));
+        snprintf(nm, sizeof nm, "hand-over, %d workgroups: fence by one thread", wgs);
+        printf("%-58s %9.2f\n", nm, time_us([&] { hipLaunchKernelGGL(k_handover_fence_one, dim3(wgs), dim3(256), 0, 0, out, small); }, 200));
+        snprintf(nm, sizeof nm, "hand-over, %d workgroups: fence by every thread", wgs);
+        printf("%-58s %9.2f\n", nm, time_us([&] { hipLaunchKernelGGL(k_handover_fence_all, dim3(wgs), dim3(256), 0, 0, out, small); }, 200));
+    }
+    return 0;
+}
