@@ -77,9 +77,6 @@ def parse():
     ap.add_argument("--launch", default="graph", choices=["graph", "eager"],
                     help="graph: the pool's rounds are captured once into a HIP graph (stream capture of the same "
                          "C-ABI calls) and replayed; eager: every call is issued from Python each round")
-    ap.add_argument("--no-sampling-hint", action="store_true",
-                    help="leave cfg.sampling_only at 0 even when every row of the workload samples: tabed_draft_step "
-                         "then also enqueues its arg-max kernel (which finds no greedy row)")
     ap.add_argument("--policy", type=int, default=0, help="weight policy (0 softmax of 1/e, 1 static, 2 two-draft grid, 3 random)")
     ap.add_argument("--distance", type=int, default=0, help="0 KL, 1 total variation")
     ap.add_argument("--drafts", type=int, default=0, help="override the workload's number of drafts n (2 for --policy 2)")
@@ -194,10 +191,8 @@ def main():
     torch.cuda.set_device(0)
     binding.load()
     Ws, Hs, Ts, temp = gen_inputs(wl, args.pool, args.w_copies, device)
-    # a serving loop knows whether any request of the batch decodes greedily; this workload's rows all sample
-    sampling_only = 1 if (wl.temperature == "one" and not args.no_sampling_hint) else 0
     cfg = binding.make_cfg(V=wl.V, d=wl.d, n=wl.n, B=wl.B, gamma=wl.gamma, h=wl.h, w_dtype=wl.w_dtype, seed=0,
-                           policy=args.policy, distance=args.distance, sampling_only=sampling_only)
+                           policy=args.policy, distance=args.distance)
     buf = binding.RoundBuffers(cfg, device)
 
     upd_first = buf.prepare_update_weights(True)
@@ -380,7 +375,6 @@ def main():
                                f"temperature={wl.temperature} policy={args.policy} distance={args.distance}",
                    "pool_rounds": args.pool, "w_copies": args.w_copies,
                    "calls_per_step": (2 if args.separate_update else 1) + wl.gamma, "launch": launch,
-                   "sampling_only_hint": sampling_only,
                    "window_update": "separate call" if args.separate_update else "fused into tabed_verify"},
         "roofline": roofline,
         "cpu_baseline": None,

@@ -88,11 +88,6 @@ typedef struct tabed_cfg {
                       /*     c = 0..10, of the window sum of D(p, mixture); needs n = 2;   */
                       /* 3 = random weights, uniform on the simplex, fresh for every block */
                       /*     (the random-weights ablation of Sec. 6.2)                       */
-    int32_t sampling_only; /* performance hint, never changes a result: 1 = the caller expects no   */
-                      /* greedy row (temperature[b] > 0 for every b), so tabed_draft_step need */
-                      /* not enqueue its vocabulary-wide arg-max kernel; a greedy row that     */
-                      /* shows up anyway is still decided correctly, by one wavefront, slowly. */
-                      /* 0 = no assumption                                                     */
     float tau_w;      /* temperature of the weight softmax, > 0 (paper default 1)          */
     float eps;        /* e is clamped to >= eps before 1/e, > 0                            */
     uint64_t seed;    /* Philox key                                                        */

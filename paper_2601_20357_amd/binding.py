@@ -26,8 +26,7 @@ class TabedCfg(C.Structure):
     """Mirror of `tabed_cfg`."""
     _fields_ = [("V", C.c_int32), ("d", C.c_int32), ("n", C.c_int32), ("B", C.c_int32),
                 ("gamma", C.c_int32), ("h", C.c_int32), ("w_dtype", C.c_int32), ("distance", C.c_int32),
-                ("policy", C.c_int32), ("sampling_only", C.c_int32), ("tau_w", C.c_float), ("eps", C.c_float),
-                ("seed", C.c_uint64)]
+                ("policy", C.c_int32), ("tau_w", C.c_float), ("eps", C.c_float), ("seed", C.c_uint64)]
 
 
 class TabedError(RuntimeError):
@@ -83,9 +82,8 @@ def load():
 GRID_CANDIDATES = 11
 
 
-def make_cfg(*, V, d, n, B, gamma, h, w_dtype, distance=0, policy=0, tau_w=1.0, eps=1e-6, seed=0,
-             sampling_only=0) -> TabedCfg:
-    return TabedCfg(V, d, n, B, gamma, h, w_dtype, distance, policy, sampling_only, tau_w, eps, seed)
+def make_cfg(*, V, d, n, B, gamma, h, w_dtype, distance=0, policy=0, tau_w=1.0, eps=1e-6, seed=0) -> TabedCfg:
+    return TabedCfg(V, d, n, B, gamma, h, w_dtype, distance, policy, tau_w, eps, seed)
 
 
 def _check(rc: int, what: str):

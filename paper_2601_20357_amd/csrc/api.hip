@@ -22,7 +22,6 @@ int validate_cfg(const tabed_cfg* c) {
     if (c->distance < 0 || c->distance > 2) return TABED_EINVAL;
     if (c->policy < 0 || c->policy > 3) return TABED_EINVAL;
     if (c->policy == 2 && c->n != 2) return TABED_EINVAL;
-    if (c->sampling_only != 0 && c->sampling_only != 1) return TABED_EINVAL;
     if (!(c->tau_w > 0.f) || !(c->eps > 0.f)) return TABED_EINVAL;
     if (c->B > 65535 || (long long)c->B * c->n > (1ll << 24)) return TABED_ERANGE;   // B is a grid dimension
     if (c->V > kTileV * kBlock * 32) return TABED_ERANGE;      // 262144: largest vocabulary the sampler tiles
@@ -38,7 +37,6 @@ WsLayout ws_layout(const tabed_cfg& c) {
     L.C3max = (c.V + kBlock * 4 - 1) / (kBlock * 4);
     L.NSEG = (c.V + kSegV - 1) / kSegV;
     L.C5 = (c.V + kResidChunkV - 1) / kResidChunkV;
-    L.NG = (L.NT + 3) / 4;
     L.RS = kStatHdr + c.n;
     L.DW = (c.policy == 2) ? TABED_GRID_CANDIDATES : c.n;
     L.Cd = (c.V + kChunkV - 1) / kChunkV;
@@ -46,7 +44,6 @@ WsLayout ws_layout(const tabed_cfg& c) {
     L.off_tickets = off; off = align_up(off + sizeof(uint32_t) * 3 * (size_t)c.B);
     L.off_pm = off;      off = align_up(off + sizeof(float) * (size_t)L.M * L.NT);
     L.off_ps = off;      off = align_up(off + sizeof(float) * (size_t)L.M * L.NT);
-    L.off_gsum = off;    off = align_up(off + 2 * sizeof(float) * (size_t)L.NG * 64);
     L.off_cand = off;    off = align_up(off + sizeof(Top2Rec) * (size_t)c.B * L.C2);
     L.off_stats = off;   off = align_up(off + sizeof(double) * (size_t)c.B * (c.gamma + 1) * L.C3max * L.RS);
     L.off_seg = off;     off = align_up(off + sizeof(double) * 2 * (size_t)c.B * L.NSEG);
@@ -117,22 +114,6 @@ static int static_scratch(char** out) {
     return TABED_OK;
 }
 
-// LM head + ensemble + draft token on workspace `ws`: one kernel when the LM-head kernel can finish the
-// sampling rows itself and no greedy row is expected, otherwise the arg-max / sampler kernel follows.
-static int draft_step_on(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round, int pos, const void* W,
-                         const void* H, const float* weights, const float* temperature, const float* u_draft,
-                         float* slot, double* draft_lse, int32_t* draft_tokens, float* draft_q, uint8_t* flags,
-                         hipStream_t s) {
-    SamplerIo io{round, pos, weights, u_draft, draft_lse, draft_tokens, draft_q, flags};
-    bool fused = false;
-    hipError_t e = launch_lmhead(c, L, ws, W, H, temperature, slot, &io, &fused, s);
-    if (e != hipSuccess) return fail_hip(e);
-    if (fused && c.sampling_only) return TABED_OK;
-    e = launch_sample(c, L, ws, round, pos, slot, weights, temperature, u_draft, draft_lse, draft_tokens, draft_q,
-                      flags, /*greedy_only=*/fused, s);
-    return e == hipSuccess ? TABED_OK : fail_hip(e);
-}
-
 }  // namespace tabed
 
 using namespace tabed;
@@ -187,8 +168,11 @@ int tabed_draft_step(const tabed_cfg* cfg, void* ws, uint64_t round, int32_t pos
     const WsLayout L = ws_layout(*cfg);
     hipStream_t s = static_cast<hipStream_t>(stream);
     float* slot = draft_logits + (size_t)pos * L.M * cfg->V;
-    return draft_step_on(*cfg, L, static_cast<char*>(ws), round, pos, W, H, weights, temperature, u_draft, slot,
-                         draft_lse, draft_tokens, draft_q, flags, s);
+    hipError_t e = launch_lmhead(*cfg, L, static_cast<char*>(ws), W, H, temperature, slot, s);
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_sample(*cfg, L, static_cast<char*>(ws), round, pos, slot, weights, temperature, u_draft, draft_lse,
+                      draft_tokens, draft_q, flags, s);
+    return e == hipSuccess ? TABED_OK : fail_hip(e);
 }
 
 int tabed_draft_step_static(const tabed_cfg* cfg, uint64_t round, int32_t pos, const void* W, const void* H,
@@ -211,8 +195,11 @@ int tabed_draft_step_static(const tabed_cfg* cfg, uint64_t round, int32_t pos, c
     hipError_t e = launch_ws_init(*cfg, L, ws, s);
     if (e != hipSuccess) return fail_hip(e);
     float* slot = draft_logits + (size_t)pos * L.M * cfg->V;
-    return draft_step_on(*cfg, L, ws, round, pos, W, H, weights, temperature, u_draft, slot, draft_lse, draft_tokens,
-                         draft_q, flags, s);
+    e = launch_lmhead(*cfg, L, ws, W, H, temperature, slot, s);
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_sample(*cfg, L, ws, round, pos, slot, weights, temperature, u_draft, draft_lse, draft_tokens, draft_q,
+                      flags, s);
+    return e == hipSuccess ? TABED_OK : fail_hip(e);
 }
 
 int tabed_verify(const tabed_cfg* cfg, void* ws, uint64_t round, const float* target_logits,

@@ -29,12 +29,9 @@ struct Top2Rec {                // chunk candidate of the greedy draft arg-max
 // Where everything lives inside the caller's workspace (byte offsets, 256-byte aligned).
 struct WsLayout {
     int M, NT, C2, C3max, NSEG, C5, RS;
-    int NG;              // groups of four softmax tiles (the vocabulary span of one LM-head workgroup pass)
     int DW;              // width of one distance vector: n, or 11 candidate mixtures (policy 2)
     int Cd;              // vocabulary chunks of the second-pass distance kernel
-    size_t off_tickets;  // uint32 [3][B]: arrival counters (0: greedy draft arg-max, 1: element 0 counts the
-                         // LM-head workgroups of a launch, 2: corrected/bonus sampler)
-    size_t off_gsum;     // 2 x float [NG][64]: (max, sum of exp) of every row over one group of four tiles
+    size_t off_tickets;  // uint32 [3][B]: arrival counters (0: greedy draft arg-max, 2: corrected/bonus sampler)
     size_t off_pm;       // float  [M][NT] tile maxima of scaled logits
     size_t off_ps;       // float  [M][NT] tile sums of exp(scaled logit - tile max)
     size_t off_cand;     // Top2Rec [B][C2]
@@ -50,29 +47,13 @@ int validate_cfg(const tabed_cfg* c);
 // ---------------------------------------------------------------- launchers (each enqueues on `s`)
 hipError_t launch_ws_init(const tabed_cfg& c, const WsLayout& L, char* ws, hipStream_t s);
 
-// What the draft-token sampler needs beyond the LM head's own arguments.  When the LM-head kernel can finish
-// the sampling rows itself (its last workgroup to arrive runs the sampler on the group summaries), it does
-// so and reports it through *fused.
-struct SamplerIo {
-    uint64_t round;
-    int pos;
-    const float* weights;
-    const float* u_draft;
-    double* draft_lse;
-    int32_t* draft_tokens;
-    float* draft_q;
-    uint8_t* flags;
-};
-
 hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& L, char* ws, const void* W, const void* H,
-                         const float* temperature, float* logits /* slot pos: [M,V] */, const SamplerIo* io,
-                         bool* fused, hipStream_t s);
+                         const float* temperature, float* logits /* slot pos: [M,V] */, hipStream_t s);
 
-// greedy_only: the sampling rows were already decided inside the LM-head kernel; only greedy rows are left.
 hipError_t launch_sample(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round, int pos,
                          const float* logits /* slot pos */, const float* weights, const float* temperature,
                          const float* u_draft, double* draft_lse, int32_t* draft_tokens, float* draft_q,
-                         uint8_t* flags, bool greedy_only, hipStream_t s);
+                         uint8_t* flags, hipStream_t s);
 
 hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round,
                          const float* target_logits, const float* draft_logits, const double* draft_lse,

@@ -73,9 +73,6 @@ __device__ __forceinline__ void store_tile_32x32(const f32x16& acc, int m_base, 
 // 16-value in-register reduction plus one exchange between the two half-waves, and every lane stores four
 // runs of four consecutive logits.  inv_t[m] = 1/T of row m (LDS table).  With `pstage` the partials go to an
 // LDS table instead, from which the caller writes a workgroup's four tiles of a row as one 16-byte store.
-// PUB: the logits are read again inside this kernel, by the workgroup that finishes the launch (fused sampler): they
-// are then stored write-through at device scope (still streaming past L2) instead of as plain streaming stores.
-template <bool PUB = false>
 __device__ __forceinline__ void store_tile_32x32_t(const f32x16& acc, int m_base, int v_base, int M, int V, int NT,
                                                    const float* inv_t, float* __restrict__ L,
                                                    float* __restrict__ pm, float* __restrict__ ps,
@@ -121,21 +118,9 @@ __device__ __forceinline__ void store_tile_32x32_t(const f32x16& acc, int m_base
         for (int i = 0; i < 4; ++i) {
             const int mr = 8 * i + (lane >> 3), q = lane & 7;
             const float4 val = *reinterpret_cast<const float4*>(tpatch + mr * 144 + q * 16);
-            if (m_base + mr < M) {
-                if (PUB) {
-                    // buffer store with the "nt sc1" cache policy (aux bits 1 and 4): streaming and written through
-                    // to device scope; the compiler counts it like any other vector-memory store
-                    const __amdgpu_buffer_rsrc_t rs =
-                        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(L), 0, M * V * 4, 0x00020000);
-                    __builtin_amdgcn_raw_buffer_store_b128(
-                        u32x4{__builtin_bit_cast(uint32_t, val.x), __builtin_bit_cast(uint32_t, val.y),
-                              __builtin_bit_cast(uint32_t, val.z), __builtin_bit_cast(uint32_t, val.w)},
-                        rs, ((m_base + mr) * V + v_base + 4 * q) * 4, 0, 18);
-                } else {
-                    __builtin_nontemporal_store(f32x4{val.x, val.y, val.z, val.w},
-                                                reinterpret_cast<f32x4*>(L + (size_t)(m_base + mr) * V + v_base + 4 * q));
-                }
-            }
+            if (m_base + mr < M)
+                __builtin_nontemporal_store(f32x4{val.x, val.y, val.z, val.w},
+                                            reinterpret_cast<f32x4*>(L + (size_t)(m_base + mr) * V + v_base + 4 * q));
         }
         return;
     }
@@ -146,10 +131,7 @@ __device__ __forceinline__ void store_tile_32x32_t(const f32x16& acc, int m_base
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int v = v_base + 8 * g + 4 * half + e;
-            if (v < V) {
-                if (PUB) publish_store(&row[v], acc[4 * g + e]);
-                else row[v] = acc[4 * g + e];
-            }
+            if (v < V) row[v] = acc[4 * g + e];
         }
 }
 
@@ -241,261 +223,13 @@ constexpr int kSkinnyWaves = 8;
 constexpr int kSkinnyThreads = kSkinnyWaves * 64;
 constexpr int kPatchBytes = 32 * 144;
 
-// ---------------------------------------------------------------- fused sampler (Alg. 1 lines 6-7 in the LM head's tail)
-// A separate sampler kernel costs a launch gap and a cold start per draft position for half a megabyte of input.
-// Instead every LM-head workgroup also publishes, per row, the (max, sum of exp) of each group of four tiles it
-// finishes (128 vocabulary entries), waits for its stores, and bumps an arrival counter; the workgroup whose
-// arrival completes the launch runs the sampler for every sampling row:
-//   A  the group summaries of all rows ([NG][64] x 8 bytes) are staged in LDS (the H tiles are no longer needed);
-//      per row: log-sum-exp over the groups (fixed order: 512 threads = rows x slices, slices combined in order);
-//   B  per sequence (one wave each): group masses of the mixture  M_g = sum_j (w_j / S_j) s_jg exp(m_jg - m_j),
-//      prefix over the groups in vocabulary order, the group where it crosses u * Z;
-//   C  the 128 logits of that group for the sequence's n rows (written by another workgroup of this launch:
-//      device-scope loads), the mixture's value at each, prefix, the token where it crosses, q(y), margin flags.
-// Greedy rows need an arg-max over the whole vocabulary: they are left to the kernel that follows, unless the
-// caller announced that none is expected -- then a greedy row is walked here by one wave, correct but slow.
-struct TailArgs {
-    int B, gamma, pos, NG;
-    int greedy_here;           // 1: no arg-max kernel follows this launch
-    uint64_t seed, round;
-    const float* weights;
-    const float* u_draft;
-    double* draft_lse;
-    int32_t* draft_tokens;
-    float* draft_q;
-    uint8_t* flags;
-    unsigned long long* gsum;  // [NG][64]: low word = max, high word = sum of exp(. - max), as float bits
-    uint32_t* ticket;          // nullptr: no fused sampler in this launch
-};
-
-constexpr int kTailLoads = 32;                      // staged 8-byte entries per thread and batch
-
-// Bytes of dynamic LDS the tail needs for NG groups and MP (32 or 64) table rows.
-static size_t tail_lds_bytes(int NG, int MP) {
-    return (size_t)NG * (MP + 1) * 8;
-}
-
-// Called by threads tid < 64 of a workgroup once the partials of the group's four tiles are in s_pstage.
-__device__ __forceinline__ void publish_group_summary(const TailArgs& t, const float* s_pstage, int row, int M, int g,
-                                                      int NT) {
-    if (row >= M) return;
-    const float* pmr = s_pstage + (0 * 64 + row) * 4;
-    const float* psr = s_pstage + (1 * 64 + row) * 4;
-    float gm = -INFINITY;
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-        if (g * 4 + q < NT) gm = fmaxf(gm, pmr[q]);
-    float gs = 0.f;
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-        if (g * 4 + q < NT && psr[q] > 0.f) gs += psr[q] * __expf(pmr[q] - gm);
-    const unsigned long long packed =
-        (unsigned long long)__builtin_bit_cast(uint32_t, gm) | ((unsigned long long)__builtin_bit_cast(uint32_t, gs) << 32);
-    __hip_atomic_store(&t.gsum[(size_t)g * 64 + row], packed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-template <int MP>
-__device__ __forceinline__ void sampler_tail(const TailArgs& t, int M, int V, int n, const float* __restrict__ temperature,
-                                          const float* L, unsigned char* lds) {
-    constexpr int SL = kSkinnyThreads / MP;         // slices of the group range per row
-    constexpr int RP = MP + 1;                      // padded row count: lane-to-lane stride of 2 banks
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int NG = t.NG;
-    float2* sg = reinterpret_cast<float2*>(lds);                                     // [NG][RP]
-    __shared__ float s_redm[SL * MP];
-    __shared__ double s_reds[SL * MP];
-    __shared__ double s_S[64], s_c[64];                                              // s_c = w_j / S_j
-    __shared__ float s_m[64];
-
-    // ---- A: stage every row's group summaries (device-scope loads, kTailLoads in flight per thread; the loads
-    //      are never predicated -- an index past the end is clamped -- so that none of them waits for another)
-    const int total = NG * MP;
-    for (int base = 0; base < total; base += kTailLoads * kSkinnyThreads) {
-        unsigned long long v[kTailLoads];
-#pragma unroll
-        for (int k = 0; k < kTailLoads; ++k) {
-            const int idx = min(base + k * kSkinnyThreads + tid, total - 1);
-            v[k] = __hip_atomic_load(&t.gsum[(size_t)(idx / MP) * 64 + (idx % MP)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-#pragma unroll
-        for (int k = 0; k < kTailLoads; ++k) {
-            const int idx = base + k * kSkinnyThreads + tid;
-            if (idx < total)
-                sg[(idx / MP) * RP + (idx % MP)] = make_float2(__builtin_bit_cast(float, (uint32_t)v[k]),
-                                                               __builtin_bit_cast(float, (uint32_t)(v[k] >> 32)));
-        }
-    }
-    __syncthreads();
-    {
-        const int row = tid % MP, slice = tid / MP;
-        const bool rlive = row < M;
-        float ml = -INFINITY;
-        if (rlive)
-            for (int g = slice; g < NG; g += SL) ml = fmaxf(ml, sg[g * RP + row].x);
-        s_redm[slice * MP + row] = ml;
-        __syncthreads();
-        float m = -INFINITY;
-#pragma unroll
-        for (int q = 0; q < SL; ++q) m = fmaxf(m, s_redm[q * MP + row]);
-        float sl = 0.f;
-        if (rlive)
-            for (int g = slice; g < NG; g += SL) {
-                const float2 e = sg[g * RP + row];
-                if (e.y > 0.f) sl += e.y * __expf(e.x - m);
-            }
-        s_reds[slice * MP + row] = (double)sl;
-        __syncthreads();
-        if (tid < M) {                              // tid < MP here, so row == tid and m is this row's maximum
-            double S = 0.0;
-#pragma unroll
-            for (int q = 0; q < SL; ++q) S += s_reds[q * MP + tid];
-            const int b = tid / n, j = tid % n;
-            s_m[tid] = m;
-            s_S[tid] = S;
-            s_c[tid] = (double)t.weights[(size_t)b * n + j] / S;
-            t.draft_lse[((size_t)t.pos * t.B + b) * n + j] = (double)m + log(S);
-        }
-        __syncthreads();
-    }
-
-    // ---- B + C: one wave per sequence
-    for (int b = wave; b < t.B; b += kSkinnyWaves) {
-        const float T = temperature[b];
-        const bool greedy = !(T > 0.f);
-        const float invT = greedy ? 1.f : 1.f / T;
-        const size_t out_idx = (size_t)b * t.gamma + t.pos;
-        const int r0 = b * n;
-        const float* rows = L + (size_t)r0 * V;
-        if (greedy) {
-            if (!t.greedy_here) continue;           // the arg-max kernel that follows decides this row
-            Top2 best = top2_empty();
-            for (int v0 = 0; v0 < V; v0 += 4 * kWave) {
-                float q[4] = {0.f, 0.f, 0.f, 0.f};
-                for (int j = 0; j < n; ++j) {
-                    const float cj = (float)s_c[r0 + j], mj = s_m[r0 + j];
-                    float x[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int v = v0 + e * kWave + lane;
-                        x[e] = (v < V) ? published_load(rows + (size_t)j * V + v) : -INFINITY;
-                    }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) q[e] += cj * __expf(x[e] * invT - mj);
-                }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int v = v0 + e * kWave + lane;
-                    if (v < V) best = top2_push(best, q[e], v);
-                }
-            }
-            best = wave_top2(best);
-            if (lane == 0) {
-                const int y = (best.i1 >= 0 && best.i1 < V) ? best.i1 : 0;
-                double f = 0.0;
-                for (int j = 0; j < n; ++j)
-                    f += s_c[r0 + j] * (double)__expf(published_load(rows + (size_t)j * V + y) * invT - s_m[r0 + j]);
-                uint32_t flag = 0;
-                if (V > 1 && (best.v1 - best.v2) < kMargin * fabsf(best.v1)) flag |= TABED_FLAG_SAMPLE_MARGIN;
-                t.draft_tokens[out_idx] = y;
-                t.draft_q[out_idx] = (float)f;
-                t.flags[out_idx] = (uint8_t)flag;
-            }
-            continue;
-        }
-        const float u = t.u_draft ? t.u_draft[out_idx] : tabed_uniform(t.seed, t.round, (uint32_t)b, (uint32_t)t.pos, 0);
-        double Z = 0.0;
-        for (int j = 0; j < n; ++j) Z += s_c[r0 + j] * s_S[r0 + j];
-        const double target = (double)u * Z;
-        // group masses, 64 groups per sweep (lane = group: neighbouring lanes are 2 banks apart), running prefix
-        double carry = 0.0, P = 0.0, Plast = 0.0;
-        int gstar = -1, glast = -1;
-        for (int g0 = 0; g0 < NG; g0 += kWave) {
-            const int g = g0 + lane;
-            double mass = 0.0;
-            if (g < NG)
-                for (int j = 0; j < n; ++j) {
-                    const float2 e = sg[g * RP + r0 + j];
-                    if (e.y > 0.f) mass += s_c[r0 + j] * (double)(e.y * __expf(e.x - s_m[r0 + j]));
-                }
-            const double cdf = carry + wave_inclusive_scan(mass);
-            const unsigned long long cross = __ballot(mass > 0.0 && cdf > target);
-            const unsigned long long live = __ballot(mass > 0.0);
-            if (gstar < 0 && cross) {
-                const int l = __ffsll((long long)cross) - 1;
-                gstar = g0 + l;
-                P = lane_f64(cdf - mass, l);
-            }
-            if (live) {
-                const int l = 63 - __clzll((long long)live);
-                glast = g0 + l;
-                Plast = lane_f64(cdf - mass, l);
-            }
-            carry = lane_f64(cdf, 63);
-            if (gstar >= 0) break;                  // uniform over the wave
-        }
-        if (gstar < 0) { gstar = glast; P = Plast; }   // rounding let nothing cross: the last group with mass
-        if (gstar < 0) {                               // every mass is zero
-            if (lane == 0) {
-                t.draft_tokens[out_idx] = 0;
-                t.draft_q[out_idx] = 0.f;
-                t.flags[out_idx] = (uint8_t)(TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE);
-            }
-            continue;
-        }
-        // the group's 128 logits of every draft row: all loads first (at most 2 x 16), then the mixture
-        float x[2][TABED_MAX_N];
-#pragma unroll
-        for (int j = 0; j < TABED_MAX_N; ++j)
-#pragma unroll
-            for (int hh = 0; hh < 2; ++hh) {          // unpredicated: row and column clamped, masked below
-                const int v = min(gstar * 128 + hh * kWave + lane, V - 1);
-                x[hh][j] = published_load(rows + (size_t)min(j, n - 1) * V + v);
-            }
-        double f[2] = {0.0, 0.0};
-#pragma unroll
-        for (int j = 0; j < TABED_MAX_N; ++j)
-            if (j < n) {
-                const double cj = s_c[r0 + j];
-                const float mj = s_m[r0 + j];
-#pragma unroll
-                for (int hh = 0; hh < 2; ++hh)
-                    if (gstar * 128 + hh * kWave + lane < V) f[hh] += cj * (double)__expf(x[hh][j] * invT - mj);
-            }
-        const double inc0 = wave_inclusive_scan(f[0]);
-        const double inc1 = lane_f64(inc0, 63) + wave_inclusive_scan(f[1]);
-        const double cdf[2] = {P + inc0, P + inc1};
-        const unsigned long long cross0 = __ballot(cdf[0] > target && f[0] > 0.0), cross1 = __ballot(cdf[1] > target && f[1] > 0.0);
-        const unsigned long long live0 = __ballot(f[0] > 0.0), live1 = __ballot(f[1] > 0.0);
-        int ph, pl;                                  // half and lane of the chosen entry
-        uint32_t flag = 0;
-        if (cross0) { ph = 0; pl = __ffsll((long long)cross0) - 1; }
-        else if (cross1) { ph = 1; pl = __ffsll((long long)cross1) - 1; }
-        else {
-            flag = TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE;
-            if (live1) { ph = 1; pl = 63 - __clzll((long long)live1); }
-            else if (live0) { ph = 0; pl = 63 - __clzll((long long)live0); }
-            else { ph = 0; pl = 0; }
-        }
-        if (lane == pl) {
-            const int v = gstar * 128 + ph * kWave + lane;
-            const double fv = ph ? f[1] : f[0], cv = ph ? cdf[1] : cdf[0];
-            const double tol = (double)kMargin * Z;
-            if (fabs(cv - target) < tol && v + 1 < V) flag |= TABED_FLAG_SAMPLE_MARGIN;
-            if (v > 0 && fabs((cv - fv) - target) < tol) flag |= TABED_FLAG_SAMPLE_MARGIN;
-            t.draft_tokens[out_idx] = v < V ? v : V - 1;
-            t.draft_q[out_idx] = (float)fv;
-            t.flags[out_idx] = (uint8_t)flag;
-        }
-    }
-}
-
-template <int KH, int MT, bool FUSE>
+template <int KH, int MT>
 __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, int n, int NT, int num_tiles,
                                                                   const uint16_t* __restrict__ W,
                                                                   const uint16_t* __restrict__ H,
                                                                   const float* __restrict__ temperature,
-                                                                  float* L, float* __restrict__ pm,
-                                                                  float* __restrict__ ps, TailArgs tail) {
+                                                                  float* __restrict__ L, float* __restrict__ pm,
+                                                                  float* __restrict__ ps) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ float s_invt[64];
     __shared__ __attribute__((aligned(16))) float s_pstage[2 * 64 * 4];   // softmax partials of the group's 4 tiles
@@ -607,7 +341,7 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
         }
         lds_barrier();                                 // both patches of the pair are read: they may be reused
         if ((MT == 2 || khalf == 0) && this_tile < num_tiles)
-            store_tile_32x32_t<FUSE>(fin, (MT == 2) ? khalf * 32 : 0, this_tile * 32, M, V, NT, s_invt, L, pm, ps, patch, s_pstage, pair);
+            store_tile_32x32_t(fin, (MT == 2) ? khalf * 32 : 0, this_tile * 32, M, V, NT, s_invt, L, pm, ps, patch, s_pstage, pair);
         // the four tiles of this group sit side by side in a row of the partial tables: 16 bytes per row
         lds_barrier();
         if (tid < 128 && (tid & 63) < M) {
@@ -617,18 +351,9 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
             if ((NT & 3) == 0 && t0 + 3 < NT) *reinterpret_cast<float4*>(dst) = *reinterpret_cast<const float4*>(srcp);
             else for (int q = 0; q < 4; ++q) if (t0 + q < NT) dst[q] = srcp[q];
         }
-        if (FUSE && tid >= 128 && tid < 192) publish_group_summary(tail, s_pstage, tid - 128, M, g, NT);
         if (!more) break;
 #pragma unroll
         for (int i = 0; i < 4; ++i) src[i] = nsrc[i];
-    }
-    if (FUSE) {
-        // every store of this workgroup (logits, group summaries) is acknowledged before its arrival counts
-        __shared__ int s_last;
-        publish_barrier();
-        if (tid == 0) s_last = arrive(tail.ticket, gridDim.x) ? 1 : 0;
-        __syncthreads();
-        if (s_last) sampler_tail<MT * 32>(tail, M, V, n, temperature, L, lds);
     }
 }
 
@@ -637,14 +362,14 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny(int M, int V, 
 // KH*128, and LDS holds one chunk of H at a time.  The next chunk of H is requested into registers at the
 // start of a chunk's k-loop and written to LDS between two LDS-only barriers at its end; the W request
 // stream (kPF k-blocks ahead) runs straight across chunk boundaries.  d = nchunks * KH * 128.
-template <int KH, int MT, bool FUSE>
+template <int KH, int MT>
 __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny_kc(int M, int V, int n, int NT, int num_tiles,
                                                                      int nchunks,
                                                                      const uint16_t* __restrict__ W,
                                                                      const uint16_t* __restrict__ H,
                                                                      const float* __restrict__ temperature,
-                                                                     float* L, float* __restrict__ pm,
-                                                                     float* __restrict__ ps, TailArgs tail) {
+                                                                     float* __restrict__ L, float* __restrict__ pm,
+                                                                     float* __restrict__ ps) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ float s_invt[64];
     __shared__ __attribute__((aligned(16))) float s_pstage[2 * 64 * 4];   // softmax partials of the group's 4 tiles
@@ -760,7 +485,7 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny_kc(int M, int 
         }
         lds_barrier();
         if ((MT == 2 || khalf == 0) && this_tile < num_tiles)
-            store_tile_32x32_t<FUSE>(fin, (MT == 2) ? khalf * 32 : 0, this_tile * 32, M, V, NT, s_invt, L, pm, ps, patch, s_pstage, pair);
+            store_tile_32x32_t(fin, (MT == 2) ? khalf * 32 : 0, this_tile * 32, M, V, NT, s_invt, L, pm, ps, patch, s_pstage, pair);
         // the four tiles of this group sit side by side in a row of the partial tables: 16 bytes per row
         lds_barrier();
         if (tid < 128 && (tid & 63) < M) {
@@ -770,18 +495,9 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny_kc(int M, int 
             if ((NT & 3) == 0 && t0 + 3 < NT) *reinterpret_cast<float4*>(dst) = *reinterpret_cast<const float4*>(srcp);
             else for (int q = 0; q < 4; ++q) if (t0 + q < NT) dst[q] = srcp[q];
         }
-        if (FUSE && tid >= 128 && tid < 192) publish_group_summary(tail, s_pstage, tid - 128, M, g, NT);
         if (!more) break;
 #pragma unroll
         for (int i = 0; i < 4; ++i) src[i] = nsrc[i];
-    }
-    if (FUSE) {
-        // every store of this workgroup (logits, group summaries) is acknowledged before its arrival counts
-        __shared__ int s_last;
-        publish_barrier();
-        if (tid == 0) s_last = arrive(tail.ticket, gridDim.x) ? 1 : 0;
-        __syncthreads();
-        if (s_last) sampler_tail<MT * 32>(tail, M, V, n, temperature, L, lds);
     }
 }
 
@@ -978,67 +694,32 @@ static hipError_t raise_lds_limit(K kernel, size_t lds, std::once_flag& once, hi
     return rc;
 }
 
-static size_t skinny_lds_bytes(int KH, int MT) { return (size_t)MT * 32 * (KH * 256 + 16) + (size_t)kSkinnyWaves * kPatchBytes; }
-
-// The fused sampler applies when the group summaries of every row fit the kernel's dynamic LDS, and the logits
-// rows are 16-byte aligned (V % 4 == 0: the write-through stores are whole 16-byte pieces).
-static bool tail_fits(const tabed_cfg& c, const WsLayout& Lay, int KH, int MT) {
-    return c.V % 4 == 0 && (long long)Lay.M * c.V * 4 < (1ll << 31) &&
-           tail_lds_bytes(Lay.NG, MT * 32) <= skinny_lds_bytes(KH, MT);
-}
-
-template <int KH, int MT, bool FUSE>
+template <int KH, int MT>
 static hipError_t launch_skinny_kc_t(const ProfScope* prof, const tabed_cfg& c, const WsLayout& Lay, int M, const void* W,
-                                     const void* H, const float* temperature, float* logits, float* pm, float* ps,
-                                     const TailArgs& tail, hipStream_t s) {
-    const size_t lds = skinny_lds_bytes(KH, MT);
+                               const void* H, const float* temperature, float* logits, float* pm, float* ps,
+                               hipStream_t s) {
+    const size_t lds = (size_t)MT * 32 * (KH * 256 + 16) + (size_t)kSkinnyWaves * kPatchBytes;
     static std::once_flag attr_once;
     static hipError_t attr_rc = hipSuccess;
-    if (raise_lds_limit(&k_lmhead_skinny_kc<KH, MT, FUSE>, lds, attr_once, attr_rc) != hipSuccess) return attr_rc;
+    if (raise_lds_limit(&k_lmhead_skinny_kc<KH, MT>, lds, attr_once, attr_rc) != hipSuccess) return attr_rc;
     const int num_tiles = Lay.NT, groups = (num_tiles + 3) / 4;
     const dim3 grid(groups < 256 ? groups : 256);
-    launch(prof, k_lmhead_skinny_kc<KH, MT, FUSE>, grid, dim3(kSkinnyThreads), lds, s, M, c.V, c.n, Lay.NT, num_tiles,
-           c.d / (KH * 128), static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), temperature, logits, pm, ps,
-           tail);
+    launch(prof, k_lmhead_skinny_kc<KH, MT>, grid, dim3(kSkinnyThreads), lds, s, M, c.V, c.n, Lay.NT, num_tiles,
+           c.d / (KH * 128), static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), temperature, logits, pm, ps);
     return hipSuccess;
 }
 
-template <int KH, int MT, bool FUSE>
-static hipError_t launch_skinny_t(const ProfScope* prof, const tabed_cfg& c, const WsLayout& Lay, int M, const void* W,
-                                  const void* H, const float* temperature, float* logits, float* pm, float* ps,
-                                  const TailArgs& tail, hipStream_t s) {
-    const size_t lds = skinny_lds_bytes(KH, MT);
-    static std::once_flag attr_once;                   // raise the dynamic-LDS limit of this instantiation once
-    static hipError_t attr_rc = hipSuccess;
-    if (raise_lds_limit(&k_lmhead_skinny<KH, MT, FUSE>, lds, attr_once, attr_rc) != hipSuccess) return attr_rc;
-    const int num_tiles = Lay.NT;
-    const int groups = (num_tiles + 3) / 4;
-    const dim3 grid(groups < 256 ? groups : 256);      // one workgroup per compute unit
-    launch(prof, k_lmhead_skinny<KH, MT, FUSE>, grid, dim3(kSkinnyThreads), lds, s, M, c.V, c.n, Lay.NT, num_tiles,
-           static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), temperature, logits, pm, ps, tail);
-    return hipSuccess;
-}
-
-// Dispatch over (k-blocks per wave, row blocks, fused sampler or not); chunked = the K-chunked kernel.
-static hipError_t launch_skinny_any(bool chunked, int KH, const ProfScope* prof, const tabed_cfg& c, const WsLayout& Lay,
-                                    int M, const void* W, const void* H, const float* temperature, float* logits,
-                                    float* pm, float* ps, const TailArgs& tail, hipStream_t s) {
+static hipError_t launch_skinny_kc(const ProfScope* prof, int KH, const tabed_cfg& c, const WsLayout& Lay, int M,
+                             const void* W, const void* H, const float* temperature, float* logits, float* pm,
+                             float* ps, hipStream_t s) {
     const int MT = (M + 31) / 32;
-    const bool fuse = tail.ticket != nullptr;
-#define TABED_SKINNY_CASE(FN_, KH_)                                                                               \
-    if (KH == KH_) {                                                                                              \
-        if (MT == 1) return fuse ? FN_<KH_, 1, true>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, tail, s) \
-                                 : FN_<KH_, 1, false>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, tail, s); \
-        return fuse ? FN_<KH_, 2, true>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, tail, s)              \
-                    : FN_<KH_, 2, false>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, tail, s);            \
+#define TABED_SKINNY_KC(KH_)                                                                              \
+    if (KH == KH_) {                                                                                      \
+        if (MT == 1) return launch_skinny_kc_t<KH_, 1>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);   \
+        else         return launch_skinny_kc_t<KH_, 2>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);   \
     }
-    if (chunked) {
-        TABED_SKINNY_CASE(launch_skinny_kc_t, 4) TABED_SKINNY_CASE(launch_skinny_kc_t, 6) TABED_SKINNY_CASE(launch_skinny_kc_t, 7)
-    } else {
-        TABED_SKINNY_CASE(launch_skinny_t, 4) TABED_SKINNY_CASE(launch_skinny_t, 6) TABED_SKINNY_CASE(launch_skinny_t, 7)
-        TABED_SKINNY_CASE(launch_skinny_t, 8)
-    }
-#undef TABED_SKINNY_CASE
+    TABED_SKINNY_KC(4) TABED_SKINNY_KC(6) TABED_SKINNY_KC(7)
+#undef TABED_SKINNY_KC
     return hipErrorInvalidValue;
 }
 
@@ -1046,37 +727,54 @@ static bool skinny_applies(const tabed_cfg& c, int M) {
     if (c.w_dtype != 1 || M > 64 || c.d % 128 != 0) return false;
     const int KH = c.d / 128, MT = (M + 31) / 32;
     if (KH != 4 && KH != 6 && KH != 7 && KH != 8) return false;
-    return skinny_lds_bytes(KH, MT) <= 160 * 1024;
+    const size_t lds = (size_t)MT * 32 * (c.d * 2 + 16) + (size_t)kSkinnyWaves * kPatchBytes;
+    return lds <= 160 * 1024;
+}
+
+template <int KH, int MT>
+static hipError_t launch_skinny_t(const ProfScope* prof, const tabed_cfg& c, const WsLayout& Lay, int M, const void* W, const void* H,
+                            const float* temperature, float* logits, float* pm, float* ps, hipStream_t s) {
+    const size_t lds = (size_t)MT * 32 * (KH * 256 + 16) + (size_t)kSkinnyWaves * kPatchBytes;
+    static std::once_flag attr_once;                   // raise the dynamic-LDS limit of this instantiation once
+    static hipError_t attr_rc = hipSuccess;
+    if (raise_lds_limit(&k_lmhead_skinny<KH, MT>, lds, attr_once, attr_rc) != hipSuccess) return attr_rc;
+    const int num_tiles = Lay.NT;
+    int cus = 256;
+    const int groups = (num_tiles + 3) / 4;
+    const dim3 grid(groups < cus ? groups : cus);
+    launch(prof, k_lmhead_skinny<KH, MT>, grid, dim3(kSkinnyThreads), lds, s, M, c.V, c.n, Lay.NT, num_tiles,
+                       static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), temperature, logits, pm, ps);
+    return hipSuccess;
+}
+
+static hipError_t launch_skinny(const ProfScope* prof, const tabed_cfg& c, const WsLayout& Lay, int M, const void* W, const void* H,
+                          const float* temperature, float* logits, float* pm, float* ps, hipStream_t s) {
+    const int KH = c.d / 128, MT = (M + 31) / 32;
+#define TABED_SKINNY(KH_)                                                                              \
+    if (KH == KH_) {                                                                                   \
+        if (MT == 1) return launch_skinny_t<KH_, 1>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);  \
+        else         return launch_skinny_t<KH_, 2>(prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);  \
+    }
+    TABED_SKINNY(4) TABED_SKINNY(6) TABED_SKINNY(7) TABED_SKINNY(8)
+#undef TABED_SKINNY
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& Lay, char* ws, const void* W, const void* H,
-                         const float* temperature, float* logits, const SamplerIo* io, bool* fused, hipStream_t s) {
+                         const float* temperature, float* logits, hipStream_t s) {
     ProfScope prof(TABED_K_LMHEAD, s);
     float* pm = reinterpret_cast<float*>(ws + Lay.off_pm);
     float* ps = reinterpret_cast<float*>(ws + Lay.off_ps);
     const int M = Lay.M;
-    if (fused != nullptr) *fused = false;
-    const bool plain_skinny = skinny_applies(c, M);
-    const int kc = plain_skinny ? 0 : skinny_kc_kh(c, M);
     if (c.w_dtype == 0) {
         const dim3 grid(Lay.NT, (M + 7) / 8);
         launch(&prof, k_lmhead_f32, grid, dim3(kBlock), 0, s, M, c.d, c.V, c.n, Lay.NT,
                            static_cast<const float*>(W), static_cast<const float*>(H), temperature, logits, pm, ps);
-    } else if (plain_skinny || kc != 0) {
-        const int KH = plain_skinny ? c.d / 128 : kc, MT = (M + 31) / 32;
-        TailArgs tail{};
-        if (io != nullptr && fused != nullptr && tail_fits(c, Lay, KH, MT)) {
-            tail.B = c.B; tail.gamma = c.gamma; tail.pos = io->pos; tail.NG = Lay.NG;
-            tail.greedy_here = c.sampling_only ? 1 : 0;
-            tail.seed = c.seed; tail.round = io->round;
-            tail.weights = io->weights; tail.u_draft = io->u_draft;
-            tail.draft_lse = io->draft_lse; tail.draft_tokens = io->draft_tokens; tail.draft_q = io->draft_q;
-            tail.flags = io->flags;
-            tail.gsum = reinterpret_cast<unsigned long long*>(ws + Lay.off_gsum);
-            tail.ticket = reinterpret_cast<uint32_t*>(ws + Lay.off_tickets) + 1 * c.B;
-            *fused = true;
-        }
-        const hipError_t e = launch_skinny_any(!plain_skinny, KH, &prof, c, Lay, M, W, H, temperature, logits, pm, ps, tail, s);
+    } else if (skinny_applies(c, M)) {
+        const hipError_t e = launch_skinny(&prof, c, Lay, M, W, H, temperature, logits, pm, ps, s);
+        if (e != hipSuccess) return e;
+    } else if (skinny_kc_kh(c, M) != 0) {
+        const hipError_t e = launch_skinny_kc(&prof, skinny_kc_kh(c, M), c, Lay, M, W, H, temperature, logits, pm, ps, s);
         if (e != hipSuccess) return e;
     } else if (M > 64 && c.d % 64 == 0) {
         static std::once_flag attr_once;                   // raise the dynamic-LDS limit once

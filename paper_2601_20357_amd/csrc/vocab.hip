@@ -196,7 +196,6 @@ hipError_t launch_weights(const tabed_cfg& c, uint64_t round, const float* dev, 
 // =====================================================================================================
 struct SampleArgs {
     int V, n, B, gamma, pos, NT, C2;
-    int greedy_only;      // 1: sampling rows were decided inside the LM-head kernel, only greedy rows are left
     uint64_t seed, round;
     const float* logits;  // [B,n,V] of this position
     const float* pm;      // [B*n,NT]
@@ -223,7 +222,7 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
     // Workgroup 0 of a sequence always has work, so its temperature load overlaps the loads below; the
     // other workgroups only exist for greedy rows and leave at once otherwise.
     const float T = a.temperature[b];
-    if ((c != 0 || a.greedy_only) && T > 0.f) return;
+    if (c != 0 && T > 0.f) return;
 
     __shared__ float s_m[TABED_MAX_N];    // row maximum of scaled logits
     __shared__ double s_S[TABED_MAX_N];   // sum_v exp(scaled - max)
@@ -541,11 +540,10 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
 hipError_t launch_sample(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round, int pos,
                          const float* logits, const float* weights, const float* temperature,
                          const float* u_draft, double* draft_lse, int32_t* draft_tokens, float* draft_q,
-                         uint8_t* flags, bool greedy_only, hipStream_t s) {
+                         uint8_t* flags, hipStream_t s) {
     ProfScope prof(TABED_K_SAMPLE, s);
     SampleArgs a;
     a.V = c.V; a.n = c.n; a.B = c.B; a.gamma = c.gamma; a.pos = pos; a.NT = L.NT; a.C2 = L.C2;
-    a.greedy_only = greedy_only ? 1 : 0;
     a.seed = c.seed; a.round = round;
     a.logits = logits;
     a.pm = reinterpret_cast<const float*>(ws + L.off_pm);

@@ -28,10 +28,9 @@ def to_dev_store(x: np.ndarray, w_dtype: int) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).to(DEV).view(torch.bfloat16)
 
 
-def cfg_of(wl: synth.Workload, seed=0, policy=0, tau_w=1.0, eps=1e-6, distance=0, sampling_only=0):
+def cfg_of(wl: synth.Workload, seed=0, policy=0, tau_w=1.0, eps=1e-6, distance=0):
     return binding.make_cfg(V=wl.V, d=wl.d, n=wl.n, B=wl.B, gamma=wl.gamma, h=wl.h, w_dtype=wl.w_dtype,
-                            policy=policy, tau_w=tau_w, eps=eps, seed=seed, distance=distance,
-                            sampling_only=sampling_only)
+                            policy=policy, tau_w=tau_w, eps=eps, seed=seed, distance=distance)
 
 
 class OracleSide:
@@ -69,9 +68,9 @@ class OracleSide:
 
 
 class GpuSide:
-    def __init__(self, wl, seed=0, policy=0, tau_w=1.0, eps=1e-6, distance=0, fused=False, sampling_only=0):
+    def __init__(self, wl, seed=0, policy=0, tau_w=1.0, eps=1e-6, distance=0, fused=False):
         self.wl = wl
-        self.cfg = cfg_of(wl, seed, policy, tau_w, eps, distance, sampling_only)
+        self.cfg = cfg_of(wl, seed, policy, tau_w, eps, distance)
         self.buf = binding.RoundBuffers(self.cfg, DEV)
         self.first = True
         self.fused = fused          # tabed_verify also opens the next round (window push + next weights)
@@ -272,7 +271,7 @@ def compare_round(g, o, wl, tally: Tally, check_logits=True, hard=False, margins
 
 
 def run_rounds(oracle, wl, rounds, temp, seed=0, policy=0, check_logits=True, uniforms=None, W=None, distance=0,
-               fused=False, start_round=0, rows=None, on_round=None, max_gpu_flags=None, sampling_only=0):
+               fused=False, start_round=0, rows=None, on_round=None, max_gpu_flags=None):
     """Drive both sides for `rounds` rounds with state carried over; returns the tally.
 
     rows: the GPU runs all wl.B sequences, the oracle only these (sequences are independent: each has its own
@@ -289,7 +288,7 @@ def run_rounds(oracle, wl, rounds, temp, seed=0, policy=0, check_logits=True, un
     wl_o = wl if rows is None else synth.scaled(wl, B=len(b_index))
     assert rows is None or (policy != 3 and not fused), "a subset run needs per-sequence state only"
     orc = OracleSide(oracle, wl_o, seed, policy, distance=distance)
-    gpu = GpuSide(wl, seed, policy, distance=distance, fused=fused, sampling_only=sampling_only)
+    gpu = GpuSide(wl, seed, policy, distance=distance, fused=fused)
     tally = Tally()
     for rnd in range(start_round, start_round + rounds):
         H, target = synth.make_round(wl, W, rnd)

@@ -98,50 +98,6 @@ def test_shapes_and_edges(oracle, shape):
     assert tally.flagged_divergences <= max(2, tally.decisions // 50)
 
 
-# ------------------------------------------------------------------ one-kernel draft step (sampler in the LM head's tail)
-FUSED_SHAPES = [
-    # V,     d,   n, B, gamma, h, temperature     -- bf16, n*B <= 64, V % 4 == 0, group summaries fit the kernel's LDS
-    (32000,  768, 4, 16, 3,    8, "one"),          # the serving shape: every row sampled by the LM head's last workgroup
-    (32000,  768, 4, 16, 2,    8, "mixed07"),      # greedy rows with the hint set: decided by one wave of that workgroup
-    (32000,  768, 4, 1,  3,    8, "greedy"),       # one row block, a single greedy sequence
-    (40000,  768, 3, 11, 2,    3, "mixed07"),      # persistent loop runs twice, 33 rows, ragged group count
-    (5004,   512, 2, 3,  2,    4, "one"),          # last group holds one ragged tile
-    (2100,  1024, 4, 16, 2,    3, "mixed07"),      # K-chunked kernel, two row blocks
-    (4100,  1536, 16, 2, 2,    3, "one"),          # K-chunked kernel, the maximum number of drafts
-]
-
-
-@pytest.mark.parametrize("shape", FUSED_SHAPES, ids=lambda s: f"V{s[0]}d{s[1]}n{s[2]}B{s[3]}{s[6]}")
-def test_one_kernel_draft_step_with_sampling_only_hint(oracle, shape):
-    """cfg.sampling_only = 1: tabed_draft_step enqueues the LM-head kernel alone.  The hint must not change any
-    result: sampling rows and (unexpected) greedy rows match the oracle as before."""
-    V, d, n, B, gamma, h, mode = shape
-    _say(f"one-kernel draft step {shape}")
-    wl = synth.scaled(SERVING, V=V, d=d, n=n, B=B, gamma=gamma, h=h, cfg_id=60 + V % 7)
-    tally = harness.run_rounds(oracle, wl, 5, synth.make_temperature(wl, mode), sampling_only=1)
-    _say(tally)
-    assert tally.flagged_divergences <= max(2, tally.decisions // 50)
-
-
-def test_sampling_only_hint_does_not_change_results(oracle):
-    """Same inputs with and without the hint: identical tokens, flags, logits and verification results; the
-    per-draft log-sum-exp, and with it q(y), agree to the last bits (with the hint a greedy row's normaliser is
-    combined from 128-wide group summaries, without it from 32-wide tiles)."""
-    wl = synth.scaled(SERVING, V=32000, B=6, gamma=2, cfg_id=67)
-    W = synth.make_lm_head(wl)
-    W_t = harness.to_dev_store(W, wl.w_dtype)
-    temp = synth.make_temperature(wl, "mixed07")
-    H, target = synth.make_round(wl, W, 0)
-    outs = [harness.GpuSide(wl, sampling_only=hint).round(0, W_t, H, target, temp) for hint in (0, 1)]
-    for key in outs[0]:
-        if key == "draft_lse":
-            np.testing.assert_allclose(outs[0][key], outs[1][key], rtol=0, atol=1e-6)
-        elif key in ("draft_q", "dev"):
-            np.testing.assert_allclose(outs[0][key], outs[1][key], rtol=2e-6, atol=1e-7)
-        else:
-            assert np.array_equal(outs[0][key], outs[1][key]), key
-
-
 def test_static_policy_and_other_tau(oracle):
     wl = synth.scaled(SERVING, V=2048, d=64, B=4, cfg_id=51)
     t = harness.run_rounds(oracle, wl, 4, synth.make_temperature(wl, "one"), policy=1)
