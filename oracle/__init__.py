@@ -217,3 +217,58 @@ def update_weights(*, n, B, gamma, h, policy, tau_w, eps, dev, n_valid, ring, ri
                                 C.c_uint64(seed), C.c_uint64(rnd),
                                 _p(d_), _p(nv), _p(ring), _p(ring_head), _p(ring_count), _p(w))
     return w
+
+
+# ---------------------------------------------------------------- token tree (Sec. 6.1)
+SIB_STRIDE = 65536
+
+
+def draft_siblings(*, V, n, B, gamma, width, seed, rnd, pos, draft_logits, draft_tokens, weights, temperature,
+                   sib_tokens, sib_q, sib_flags, u_sib=None):
+    """The width-1 sibling candidates of position `pos`, from the ensembled distribution of that position
+    (draft_logits slot pos as written by draft_step); writes entries (b, pos, :) of the sib_* arrays in place."""
+    S = width - 1
+    assert draft_logits.dtype == np.float32 and draft_logits.shape == (gamma, B, n, V)
+    assert sib_tokens.dtype == np.int32 and sib_tokens.shape == (B, gamma, S)
+    assert sib_q.dtype == np.float32 and sib_q.shape == (B, gamma, S)
+    assert sib_flags.dtype == np.uint8 and sib_flags.shape == (B, gamma, S)
+    draft_tokens = np.ascontiguousarray(draft_tokens, dtype=np.int32)
+    weights, temperature = _f32(weights), _f32(temperature)
+    u = None if u_sib is None else _f32(u_sib)
+    lib().oracle_draft_siblings(V, n, B, gamma, width, C.c_uint64(seed), C.c_uint64(rnd), pos,
+                                _p(draft_logits), _p(draft_tokens), _p(weights), _p(temperature), _p(u),
+                                _p(sib_tokens), _p(sib_q), _p(sib_flags))
+
+
+def verify_tree(*, V, n, B, gamma, width, distance, seed, rnd, target_logits, leaf_logits, draft_logits, draft_tokens,
+                draft_q, sib_tokens, sib_q, weights, temperature, u_acc=None, u_res=None, u_acc_sib=None):
+    """Verification of a width-`width` token tree; returns a dict of fresh output arrays (those of verify plus
+    leaf [B] and n_out [B])."""
+    S = width - 1
+    assert distance in (0, 1), "hard labels are defined for the chain only"
+    target_logits, draft_logits = _f32(target_logits), _f32(draft_logits)
+    leaf_logits = _f32(leaf_logits)
+    assert target_logits.shape == (B, gamma + 1, V) and draft_logits.shape == (gamma, B, n, V)
+    assert leaf_logits.shape == (B, gamma, S, V)
+    draft_tokens = np.ascontiguousarray(draft_tokens, dtype=np.int32)
+    sib_tokens = np.ascontiguousarray(sib_tokens, dtype=np.int32)
+    draft_q, sib_q, weights, temperature = _f32(draft_q), _f32(sib_q), _f32(weights), _f32(temperature)
+    assert sib_tokens.shape == (B, gamma, S) and sib_q.shape == (B, gamma, S)
+    ua = None if u_acc is None else _f32(u_acc)
+    ur = None if u_res is None else _f32(u_res)
+    us = None if u_acc_sib is None else _f32(u_acc_sib)
+    out = dict(
+        accept_len=np.zeros(B, dtype=np.int32),
+        out_tokens=np.full((B, gamma + 1), -1, dtype=np.int32),
+        dev=np.zeros((B, gamma, n), dtype=np.float32),
+        n_valid=np.zeros(B, dtype=np.int32),
+        flags=np.zeros((B, gamma + 1), dtype=np.uint8),
+        leaf=np.zeros(B, dtype=np.int32),
+        n_out=np.zeros(B, dtype=np.int32),
+    )
+    lib().oracle_verify_tree(V, n, B, gamma, width, distance, C.c_uint64(seed), C.c_uint64(rnd),
+                             _p(target_logits), _p(leaf_logits), _p(draft_logits), _p(draft_tokens), _p(draft_q),
+                             _p(sib_tokens), _p(sib_q), _p(weights), _p(temperature), _p(ua), _p(ur), _p(us),
+                             _p(out["accept_len"]), _p(out["out_tokens"]), _p(out["dev"]), _p(out["n_valid"]),
+                             _p(out["flags"]), _p(out["leaf"]), _p(out["n_out"]))
+    return out

@@ -23,6 +23,10 @@
  *     Sec. 5.1 last paragraph: TVD as the alternative distance; Sec. 5.1:
  *     selection by hard labels (token matches) instead of soft labels.
  *   - Eq. 1: speedup = block_eff / (gamma * Tq/Tp + 1).
+ *   - Sec. 6.1, "Verification: Integrating Token Tree" (+ App. D): the drafts
+ *     form a token tree of width 2 or 3 that the target verifies in one pass.
+ *     The paper gives no construction; the one taken here is stated at
+ *     oracle_draft_siblings / oracle_verify_tree.
  *
  * Notation: n = number of drafting methods (the paper's m), B independent
  * sequences, V vocabulary, d draft hidden size, gamma block length, h window.
@@ -513,5 +517,195 @@ void oracle_update_weights(int n, int B, int gamma, int h, int policy,
         double Z = 0.0;
         for (int j = 0; j < n; ++j) Z += exp(x[j] - xmax);
         for (int j = 0; j < n; ++j) w[j] = (float)(exp(x[j] - xmax) / Z);
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* Token tree (Sec. 6.1 "Verification: Integrating Token Tree").        */
+/* ------------------------------------------------------------------ */
+/*
+ * reading (the paper names the tree width, 2 or 3, and nothing else): at every
+ * in-block position i the draft proposes `width` sibling candidates for the
+ * same prefix, all taken from the ensembled distribution q_i of that position:
+ * candidate 0 is the token Alg. 1 line 7 samples (the "trunk": the only one
+ * the draft model extends to position i+1), candidates 1..width-1 are leaves.
+ * A sampling row draws the siblings independently from q_i (inverse CDF, own
+ * uniform each); a greedy row takes the next-largest entries of q_i (lowest
+ * index on ties), so its candidates are the top `width` tokens in order.
+ * Width 1 is the plain chain.
+ *
+ * Sibling s (1-based) of position pos uses the Philox block of counter
+ * (round, b, pos + s * 65536): word 0 draws the sibling, word 1 is its accept
+ * uniform.
+ *
+ * Layouts: draft_logits [gamma,B,n,V] (slot pos already written by
+ * oracle_draft_step), draft_tokens [B,gamma] (trunk tokens, column pos
+ * written), u_sib [B,gamma,width-1] or NULL; outputs sib_tokens, sib_q,
+ * sib_flags [B,gamma,width-1], entries (b,pos,.) written.
+ */
+#define ORACLE_SIB_STRIDE 65536u
+
+void oracle_draft_siblings(int V, int n, int B, int gamma, int width,
+                           uint64_t seed, uint64_t round, int pos,
+                           const float* draft_logits, const int32_t* draft_tokens,
+                           const float* weights, const float* temperature, const float* u_sib,
+                           int32_t* sib_tokens, float* sib_q, uint8_t* sib_flags)
+{
+    const int S = width - 1;
+    if (S <= 0) return;
+    const float* L = draft_logits + (size_t)pos * B * n * V;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        double T = (double)temperature[b];
+        double T_eff = T > 0.0 ? T : 1.0;
+        double* q = (double*)malloc((size_t)n * V * sizeof(double));
+        double* q_ens = (double*)malloc((size_t)V * sizeof(double));
+        double* rest = (double*)malloc((size_t)V * sizeof(double));
+        for (int j = 0; j < n; ++j) oracle_softmax(L + ((size_t)b * n + j) * V, V, T_eff, q + (size_t)j * V, NULL);
+        oracle_ensemble(n, V, q, weights + (size_t)b * n, q_ens);
+        for (int v = 0; v < V; ++v) rest[v] = q_ens[v];
+        int trunk = draft_tokens[(size_t)b * gamma + pos];
+        if (trunk >= 0 && trunk < V) rest[trunk] = -1.0; /* greedy rows: already taken */
+        for (int s = 1; s <= S; ++s) {
+            size_t o = ((size_t)b * gamma + pos) * S + (s - 1);
+            uint32_t flag = 0;
+            int y;
+            if (T > 0.0) {
+                float u = u_sib ? u_sib[o] : oracle_uniform(seed, round, (uint32_t)b, (uint32_t)pos + (uint32_t)s * ORACLE_SIB_STRIDE, 0);
+                y = oracle_sample_cdf(q_ens, V, (double)u, &flag);
+            } else {
+                y = oracle_argmax(rest, V, &flag);  /* next-largest entry; -1 marks the ones already taken */
+                rest[y] = -1.0;
+            }
+            sib_tokens[o] = y;
+            sib_q[o] = (float)q_ens[y];
+            sib_flags[o] = (uint8_t)flag;
+        }
+        free(q); free(q_ens); free(rest);
+    }
+}
+
+/*
+ * Verification of the tree (reading, continued).  The walk goes down the trunk
+ * exactly as the chain does (same test, same uniforms) until the trunk token of
+ * some position k is rejected, or all gamma are accepted (bonus token from
+ * p_gamma, as in the chain).  At position k the siblings are tried in order by
+ * multi-round rejection sampling, the lossless rule for several candidates
+ * drawn from one proposal: with f_0 = p_k, Z_0 = 1 and, after each rejection,
+ *     f_c(v) = max(0, f_{c-1}(v) / Z_{c-1} - q_k(v)),   Z_c = sum_v f_c(v),
+ * candidate c (c >= 1) is accepted iff  u_c * q_k(y_c) * Z_c < f_c(y_c)
+ * (probability min(1, r_c(y)/q(y)) with r_c = f_c / Z_c; c = 0 is the chain's
+ * own test u * q < p).  An accepted sibling is emitted and, being a leaf, is
+ * followed by one bonus token from the target's distribution AFTER it
+ * (leaf_logits); if every candidate is rejected the corrected token comes from
+ * r_width = f_width / Z_width.  The one final draw of a round (corrected token,
+ * bonus after a leaf, or bonus after gamma accepts) uses the chain's u_res.
+ * Greedy rows: a candidate is accepted iff it equals arg-max p_k; the bonus
+ * after a leaf is the arg-max of its leaf row; otherwise arg-max p_k is emitted.
+ * The decision of a sibling test is taken in fp64 on the fp32 interface value
+ * q(y); it is flagged when |lhs - rhs| < 1e-6 * max(f_{c-1}(y)/Z_{c-1}, q(y)).
+ * An empty residual (Z_c = 0) ends the levels: the token is drawn from p_k,
+ * flagged degenerate.
+ * The distances and n_valid = min(k+1, gamma) are those of the chain: the
+ * position where the walk ends is verified either way.
+ *
+ * Extra inputs: leaf_logits [B,gamma,width-1,V] (target logits after sibling
+ * s of position i), sib_tokens / sib_q [B,gamma,width-1], u_acc_sib
+ * [B,gamma,width-1] or NULL.  Extra outputs: leaf [B] = 0 or the 1-based index
+ * of the accepted sibling; n_out [B] = emitted tokens (k+1, or k+2 after a
+ * leaf); out_tokens [B,gamma+1] as in oracle_verify with the leaf and its bonus
+ * token at columns k and k+1; flags [B,gamma+1]: column k also carries the
+ * sibling tests' margin bits, column k+1 the bonus draw after a leaf.
+ */
+void oracle_verify_tree(int V, int n, int B, int gamma, int width, int distance,
+                        uint64_t seed, uint64_t round,
+                        const float* target_logits, const float* leaf_logits,
+                        const float* draft_logits,
+                        const int32_t* draft_tokens, const float* draft_q,
+                        const int32_t* sib_tokens, const float* sib_q,
+                        const float* weights, const float* temperature,
+                        const float* u_acc, const float* u_res, const float* u_acc_sib,
+                        int32_t* accept_len, int32_t* out_tokens, float* dev,
+                        int32_t* n_valid, uint8_t* flags, int32_t* leaf, int32_t* n_out)
+{
+    /* the trunk: everything the chain computes */
+    oracle_verify(V, n, B, gamma, distance, 0, seed, round, target_logits, draft_logits, draft_tokens, draft_q,
+                  weights, temperature, u_acc, u_res, accept_len, out_tokens, dev, n_valid, flags);
+    const int S = width - 1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        const int k = accept_len[b];
+        leaf[b] = 0;
+        n_out[b] = k + 1;
+        if (S <= 0 || k >= gamma) continue;
+        double T = (double)temperature[b];
+        int greedy = !(T > 0.0);
+        double T_eff = greedy ? 1.0 : T;
+        const float* Lt = target_logits + ((size_t)b * (gamma + 1) + k) * V;
+        uint8_t* fl = flags + (size_t)b * (gamma + 1);
+        int32_t* out = out_tokens + (size_t)b * (gamma + 1);
+        double* f = (double*)malloc((size_t)V * sizeof(double));
+        double* q = (double*)malloc((size_t)n * V * sizeof(double));
+        double* q_ens = (double*)malloc((size_t)V * sizeof(double));
+        double* p = (double*)malloc((size_t)V * sizeof(double));
+        int accepted = 0;
+        if (greedy) {
+            int top = argmax_logits(Lt, V);
+            for (int s = 1; s <= S && !accepted; ++s)
+                if (sib_tokens[((size_t)b * gamma + k) * S + (s - 1)] == top) accepted = s;
+            if (accepted) {
+                out[k] = top;
+                out[k + 1] = argmax_logits(leaf_logits + (((size_t)b * gamma + k) * S + (accepted - 1)) * V, V);
+            }
+        } else {
+            oracle_softmax(Lt, V, T_eff, p, NULL);
+            for (int j = 0; j < n; ++j)
+                oracle_softmax(draft_logits + (((size_t)k * B + b) * n + j) * V, V, T_eff, q + (size_t)j * V, NULL);
+            oracle_ensemble(n, V, q, weights + (size_t)b * n, q_ens);
+            for (int v = 0; v < V; ++v) f[v] = p[v];
+            double Zprev = 1.0;
+            uint32_t flag = 0;
+            int degenerate = 0;
+            for (int c = 1; c <= width; ++c) {
+                /* candidate c-1 was rejected: f_c = max(0, f_{c-1}/Z_{c-1} - q); sibling c, if there is one, is
+                 * tested against it, otherwise (c = width) the corrected token is drawn from it */
+                int y = -1;
+                double qy = 0.0, minuend_y = 0.0;
+                if (c <= S) {
+                    y = sib_tokens[((size_t)b * gamma + k) * S + (c - 1)];
+                    qy = (double)sib_q[((size_t)b * gamma + k) * S + (c - 1)];
+                    minuend_y = (y >= 0 && y < V) ? f[y] / Zprev : 0.0;   /* f_{c-1}(y) / Z_{c-1}, kept for the margin */
+                }
+                double Z = 0.0;
+                for (int v = 0; v < V; ++v) { f[v] = fmax(0.0, f[v] / Zprev - q_ens[v]); Z += f[v]; }
+                if (!(Z > 0.0)) { degenerate = 1; break; }
+                Zprev = Z;
+                if (c > S) break;                            /* every candidate rejected: f = f_width */
+                if (y < 0 || y >= V) { flag |= ORACLE_FLAG_DEGENERATE; continue; }
+                float u = u_acc_sib ? u_acc_sib[((size_t)b * gamma + k) * S + (c - 1)]
+                                    : oracle_uniform(seed, round, (uint32_t)b, (uint32_t)k + (uint32_t)c * ORACLE_SIB_STRIDE, 1);
+                double fy = fmax(0.0, minuend_y - qy);      /* f_c(y) on the interface value q(y) */
+                double lhs = (double)u * qy * Z;
+                if (fabs(lhs - fy) < MARGIN * fmax(minuend_y, qy)) flag |= ORACLE_FLAG_ACCEPT_MARGIN;
+                if (lhs < fy) { accepted = c; break; }
+            }
+            float u = u_res ? u_res[b] : oracle_uniform(seed, round, (uint32_t)b, (uint32_t)gamma, 0);
+            fl[k] &= (uint8_t)~(ORACLE_FLAG_SAMPLE_MARGIN | ORACLE_FLAG_DEGENERATE);   /* the chain's draw is replaced */
+            if (accepted) {
+                out[k] = sib_tokens[((size_t)b * gamma + k) * S + (accepted - 1)];
+                uint32_t bflag = 0;
+                oracle_softmax(leaf_logits + (((size_t)b * gamma + k) * S + (accepted - 1)) * V, V, T_eff, p, NULL);
+                out[k + 1] = oracle_sample_cdf(p, V, (double)u, &bflag);
+                fl[k + 1] = (uint8_t)bflag;
+            } else if (degenerate) {
+                flag |= ORACLE_FLAG_DEGENERATE;
+                out[k] = oracle_sample_cdf(p, V, (double)u, &flag);
+            } else {
+                out[k] = oracle_sample_cdf(f, V, (double)u, &flag);   /* f = f_width */
+            }
+            fl[k] |= (uint8_t)flag;
+        }
+        if (accepted) { leaf[b] = accepted; n_out[b] = k + 2; }
+        free(f); free(q); free(q_ens); free(p);
     }
 }

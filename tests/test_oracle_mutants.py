@@ -45,6 +45,18 @@ MUTANTS = [
      "out[0] = c1; out[1] = c2; out[2] = c3; out[3] = c0;", False),
     ("23-bit uniforms", "(float)(out[word & 3] >> 8) * (1.0f / 16777216.0f)",
      "(float)(out[word & 3] >> 9) * (1.0f / 8388608.0f)", False),
+    ("tree: residual level without the renormalisation", "f[v] = fmax(0.0, f[v] / Zprev - q_ens[v]); Z += f[v];",
+     "f[v] = fmax(0.0, f[v] - q_ens[v]); Z += f[v];", False),
+    ("tree: sibling test without the level's mass", "double lhs = (double)u * qy * Z;", "double lhs = (double)u * qy;", False),
+    ("tree: the last sibling is never tried", "if (c > S) break;                            /* every candidate rejected: f = f_width */",
+     "if (c >= S) break;", False),
+    ("tree: last level skipped", "for (int c = 1; c <= width; ++c) {", "for (int c = 1; c <= S; ++c) {", False),
+    ("tree: bonus after a leaf from the trunk's next row",
+     "oracle_softmax(leaf_logits + (((size_t)b * gamma + k) * S + (accepted - 1)) * V, V, T_eff, p, NULL);",
+     "oracle_softmax(target_logits + ((size_t)b * (gamma + 1) + k + 1) * V, V, T_eff, p, NULL);", False),
+    ("tree: siblings reuse the trunk's uniform",
+     "(uint32_t)pos + (uint32_t)s * ORACLE_SIB_STRIDE, 0);", "(uint32_t)pos, 0);", False),
+    ("tree: greedy siblings may repeat the trunk", "if (trunk >= 0 && trunk < V) rest[trunk] = -1.0;", "", False),
     ("Eq. 1 without the +1", "return block_eff / (gamma * tq_over_tp + 1.0);", "return block_eff / (gamma * tq_over_tp);", False),
 ]
 
