@@ -56,6 +56,7 @@ extern "C" {
 #endif
 
 #define TABED_MAX_N 16     /* drafting methods                      */
+#define TABED_MAX_TREE_WIDTH 3 /* candidates per position of a token tree (1 = chain) */
 #define TABED_MAX_GAMMA 32 /* block length                          */
 
 #define TABED_OK 0
@@ -188,6 +189,55 @@ int tabed_verify(const tabed_cfg* cfg, void* ws, uint64_t round,
                  void* stream);
 
 /*
+ * Token tree (Sec. 6.1, paragraph "Verification: Integrating Token Tree"; results in App. D for widths 2 and 3).
+ * The paper names the tree width and nothing else; the construction taken here: at every in-block position the
+ * draft proposes tree_width sibling candidates for the same prefix, all from that position's ensembled
+ * distribution q_i.  Candidate 0 is the token tabed_draft_step samples (the trunk: the only candidate the draft
+ * model extends), candidates 1..tree_width-1 are leaves: a sampling row draws them independently from q_i, a
+ * greedy row takes the next-largest entries of q_i.  tree_width = 1 is the chain.
+ *
+ * tabed_draft_siblings draws the siblings of position pos.  Call it after tabed_draft_step(pos) and before
+ * tabed_draft_step(pos + 1): it works from the softmax partials that call left in `ws`.
+ *   draft_logits [gamma,B,n,V], draft_tokens [B,gamma]: as written by tabed_draft_step (slot / column pos)
+ *   u_sib        [B,gamma,tree_width-1] fp32 in   optional explicit uniforms; NULL => Philox block of counter
+ *                (round, b, pos + s * 65536) for sibling s >= 1: word 0 draws it, word 1 is its accept uniform
+ *   sib_tokens, sib_q, sib_flags [B,gamma,tree_width-1] out  entries (b, pos, :) are written: token, q_i(token), flags
+ */
+int tabed_draft_siblings(const tabed_cfg* cfg, void* ws, uint64_t round, int32_t pos, int32_t tree_width,
+                         const float* draft_logits, const int32_t* draft_tokens, const float* weights,
+                         const float* temperature, const float* u_sib,
+                         int32_t* sib_tokens, float* sib_q, uint8_t* sib_flags, void* stream);
+
+/*
+ * Verification of the token tree.  The trunk is verified exactly as tabed_verify does (same arguments, same
+ * results for accept_len = k, dev, n_valid, the window update).  At the position k where the trunk token is
+ * rejected the siblings are tried in order by multi-round rejection sampling, the lossless rule for several
+ * candidates from one proposal: with f_0 = p_k, Z_0 = 1 and f_c = max(0, f_{c-1} / Z_{c-1} - q_k), Z_c = sum f_c,
+ * sibling c is accepted iff u_c q_k(y_c) Z_c < f_c(y_c).  An accepted sibling is emitted and followed by one
+ * bonus token from the target's distribution after it (leaf_logits); if every candidate is rejected the
+ * corrected token is drawn from f_width / Z_width.  Greedy rows: a candidate is accepted iff it equals
+ * arg-max p_k.  The round's one final draw uses u_res, as in the chain.
+ *   leaf_logits  [B,gamma,tree_width-1,V] fp32 in  target logits after sibling s of position i
+ *   sib_tokens, sib_q [B,gamma,tree_width-1]   in  as written by tabed_draft_siblings
+ *   u_acc_sib    [B,gamma,tree_width-1] fp32   in  optional explicit accept uniforms of the siblings
+ *   out_tokens   [B,gamma+1]  k trunk tokens, then the accepted sibling and its bonus token, or the corrected /
+ *                bonus token of the chain, then -1
+ *   leaf         [B] int32 out  0, or the index s of the accepted sibling
+ *   n_out        [B] int32 out  tokens emitted: k + 1, or k + 2 after a leaf
+ *   flags        [B,gamma+1]    column k also carries the sibling tests' margin bits, column k + 1 the draw after a leaf
+ * next_weights must not alias weights here (the tree passes read this block's weights after the window update).
+ * cfg->distance = 2 (hard labels) is not defined for trees: TABED_EUNSUPPORTED.
+ */
+int tabed_verify_tree(const tabed_cfg* cfg, void* ws, uint64_t round, int32_t tree_width,
+                      const float* target_logits, const float* leaf_logits, const float* draft_logits,
+                      const double* draft_lse, const int32_t* draft_tokens, const float* draft_q,
+                      const int32_t* sib_tokens, const float* sib_q, const float* weights, const float* temperature,
+                      const float* u_acc, const float* u_res, const float* u_acc_sib,
+                      int32_t* accept_len, int32_t* out_tokens, float* dev, int32_t* n_valid, uint8_t* flags,
+                      int32_t* leaf, int32_t* n_out,
+                      float* ring, int32_t* ring_head, int32_t* ring_count, float* next_weights, void* stream);
+
+/*
  * Alg. 1 lines 2-3 with the policy of App. B.2: push the distances of the
  * n_valid[b] verified positions of the finished block into the window, then
  * w = softmax((1 / max(e_j, eps)) / tau_w) with e_j the window sum (policy 0), or the candidate
@@ -228,8 +278,9 @@ int tabed_philox_uniforms(const tabed_cfg* cfg, uint64_t round, float* out, void
 #define TABED_K_RESID 3   /* corrected / bonus token            */
 #define TABED_K_WEIGHTS 4 /* window + weights                   */
 #define TABED_K_DIST 5    /* second-pass distances (total variation, hard labels, grid mixtures) */
-#define TABED_K_NULL 6    /* empty kernel, see tabed_prof_null  */
-#define TABED_K_COUNT 7
+#define TABED_K_TREE 6    /* token tree: sibling 1's test (the later tree passes are not timed) */
+#define TABED_K_NULL 7    /* empty kernel, see tabed_prof_null  */
+#define TABED_K_COUNT 8
 int tabed_prof_enable(int on);
 int tabed_prof_read(int id, double* total_ms, int64_t* launches);
 int tabed_prof_reset(void);

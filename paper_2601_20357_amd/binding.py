@@ -14,12 +14,12 @@ LIB_PATH = os.path.join(_HERE, "libtabed.so")
 
 EXPORTS = [
     "tabed_workspace_bytes", "tabed_workspace_init", "tabed_strerror", "tabed_last_hip_error", "tabed_dev_width",
-    "tabed_draft_step", "tabed_draft_step_static", "tabed_verify", "tabed_update_weights", "tabed_philox_uniforms",
+    "tabed_draft_step", "tabed_draft_step_static", "tabed_verify", "tabed_draft_siblings", "tabed_verify_tree", "tabed_update_weights", "tabed_philox_uniforms",
     "tabed_prof_enable", "tabed_prof_read", "tabed_prof_reset", "tabed_kernel_name", "tabed_prof_null",
 ]
 
 FLAG_ACCEPT_MARGIN, FLAG_SAMPLE_MARGIN, FLAG_DEGENERATE = 1, 2, 4
-K_LMHEAD, K_SAMPLE, K_STATS, K_RESID, K_WEIGHTS, K_DIST, K_NULL, K_COUNT = 0, 1, 2, 3, 4, 5, 6, 7
+K_LMHEAD, K_SAMPLE, K_STATS, K_RESID, K_WEIGHTS, K_DIST, K_TREE, K_NULL, K_COUNT = 0, 1, 2, 3, 4, 5, 6, 7, 8
 
 
 class TabedCfg(C.Structure):
@@ -62,6 +62,10 @@ def load():
     lib.tabed_draft_step_static.argtypes = [cfgp, u64, i32] + [vp] * 11
     lib.tabed_verify.restype = C.c_int
     lib.tabed_verify.argtypes = [cfgp, vp, u64] + [vp] * 19
+    lib.tabed_draft_siblings.restype = C.c_int
+    lib.tabed_draft_siblings.argtypes = [cfgp, vp, u64, i32, i32] + [vp] * 9
+    lib.tabed_verify_tree.restype = C.c_int
+    lib.tabed_verify_tree.argtypes = [cfgp, vp, u64, i32] + [vp] * 25
     lib.tabed_update_weights.restype = C.c_int
     lib.tabed_update_weights.argtypes = [cfgp, vp, u64] + [vp] * 7
     lib.tabed_philox_uniforms.restype = C.c_int
@@ -202,6 +206,56 @@ def tabed_verify(cfg, ws, rnd, target_logits, draft_logits, draft_lse, draft_tok
         _ptr(ring_head, torch.int32, B, "ring_head"), _ptr(ring_count, torch.int32, B, "ring_count"),
         _ptr(next_weights, torch.float32, B * n, "next_weights"), _stream(stream))
     _check(rc, "tabed_verify")
+
+
+MAX_TREE_WIDTH = 3
+SIBLING_STRIDE = 65536
+
+
+def tabed_draft_siblings(cfg, ws, rnd, pos, tree_width, draft_logits, draft_tokens, weights, temperature, sib_tokens,
+                         sib_q, sib_flags, u_sib=None, stream=None):
+    import torch
+    V, n, B, g = cfg.V, cfg.n, cfg.B, cfg.gamma
+    S = tree_width - 1
+    rc = load().tabed_draft_siblings(
+        C.byref(cfg), _ptr(ws, torch.uint8, name="ws"), rnd, pos, tree_width,
+        _ptr(draft_logits, torch.float32, g * B * n * V, "draft_logits"),
+        _ptr(draft_tokens, torch.int32, B * g, "draft_tokens"),
+        _ptr(weights, torch.float32, B * n, "weights"), _ptr(temperature, torch.float32, B, "temperature"),
+        _ptr(u_sib, torch.float32, B * g * S, "u_sib"),
+        _ptr(sib_tokens, torch.int32, B * g * S, "sib_tokens"), _ptr(sib_q, torch.float32, B * g * S, "sib_q"),
+        _ptr(sib_flags, torch.uint8, B * g * S, "sib_flags"), _stream(stream))
+    _check(rc, "tabed_draft_siblings")
+
+
+def tabed_verify_tree(cfg, ws, rnd, tree_width, target_logits, leaf_logits, draft_logits, draft_lse, draft_tokens,
+                      draft_q, sib_tokens, sib_q, weights, temperature, accept_len, out_tokens, dev, n_valid, flags,
+                      leaf, n_out, u_acc=None, u_res=None, u_acc_sib=None, ring=None, ring_head=None, ring_count=None,
+                      next_weights=None, stream=None):
+    import torch
+    V, n, B, g = cfg.V, cfg.n, cfg.B, cfg.gamma
+    S = tree_width - 1
+    dw = tabed_dev_width(cfg)
+    rc = load().tabed_verify_tree(
+        C.byref(cfg), _ptr(ws, torch.uint8, name="ws"), rnd, tree_width,
+        _ptr(target_logits, torch.float32, B * (g + 1) * V, "target_logits"),
+        _ptr(leaf_logits, torch.float32, B * g * S * V, "leaf_logits") if S else None,
+        _ptr(draft_logits, torch.float32, g * B * n * V, "draft_logits"),
+        _ptr(draft_lse, torch.float64, g * B * n, "draft_lse"),
+        _ptr(draft_tokens, torch.int32, B * g, "draft_tokens"), _ptr(draft_q, torch.float32, B * g, "draft_q"),
+        _ptr(sib_tokens, torch.int32, B * g * S, "sib_tokens") if S else None,
+        _ptr(sib_q, torch.float32, B * g * S, "sib_q") if S else None,
+        _ptr(weights, torch.float32, B * n, "weights"), _ptr(temperature, torch.float32, B, "temperature"),
+        _ptr(u_acc, torch.float32, B * g, "u_acc"), _ptr(u_res, torch.float32, B, "u_res"),
+        _ptr(u_acc_sib, torch.float32, B * g * S, "u_acc_sib") if S else None,
+        _ptr(accept_len, torch.int32, B, "accept_len"), _ptr(out_tokens, torch.int32, B * (g + 1), "out_tokens"),
+        _ptr(dev, torch.float32, B * g * dw, "dev"), _ptr(n_valid, torch.int32, B, "n_valid"),
+        _ptr(flags, torch.uint8, B * (g + 1), "flags"), _ptr(leaf, torch.int32, B, "leaf"),
+        _ptr(n_out, torch.int32, B, "n_out"),
+        _ptr(ring, torch.float32, B * max(cfg.h, 1) * dw, "ring"),
+        _ptr(ring_head, torch.int32, B, "ring_head"), _ptr(ring_count, torch.int32, B, "ring_count"),
+        _ptr(next_weights, torch.float32, B * n, "next_weights"), _stream(stream))
+    _check(rc, "tabed_verify_tree")
 
 
 def tabed_update_weights(cfg, ws, rnd, dev, n_valid, ring, ring_head, ring_count, weights, stream=None):

@@ -41,7 +41,7 @@ WsLayout ws_layout(const tabed_cfg& c) {
     L.DW = (c.policy == 2) ? TABED_GRID_CANDIDATES : c.n;
     L.Cd = (c.V + kChunkV - 1) / kChunkV;
     size_t off = 0;
-    L.off_tickets = off; off = align_up(off + sizeof(uint32_t) * 3 * (size_t)c.B);
+    L.off_tickets = off; off = align_up(off + sizeof(uint32_t) * 5 * (size_t)c.B);
     L.off_pm = off;      off = align_up(off + sizeof(float) * (size_t)L.M * L.NT);
     L.off_ps = off;      off = align_up(off + sizeof(float) * (size_t)L.M * L.NT);
     L.off_cand = off;    off = align_up(off + sizeof(Top2Rec) * (size_t)c.B * L.C2);
@@ -49,6 +49,8 @@ WsLayout ws_layout(const tabed_cfg& c) {
     L.off_seg = off;     off = align_up(off + sizeof(double) * 2 * (size_t)c.B * L.NSEG);
     L.off_wstage = off;  off = align_up(off + sizeof(float) * (size_t)c.B * c.n);
     L.off_dist = off;    off = align_up(off + sizeof(double) * 2 * (size_t)c.B * c.gamma * L.DW * L.Cd);
+    L.off_tstate = off;  off = align_up(off + sizeof(double) * kTsSlots * (size_t)c.B);
+    L.off_tseg = off;    off = align_up(off + sizeof(double) * 2 * (size_t)c.B * L.NSEG);
     L.total = off;
     return L;
 }
@@ -221,7 +223,60 @@ int tabed_verify(const tabed_cfg* cfg, void* ws, uint64_t round, const float* ta
     hipStream_t s = static_cast<hipStream_t>(stream);
     const hipError_t e = launch_verify(*cfg, L, static_cast<char*>(ws), round, target_logits, draft_logits, draft_lse,
                                        draft_tokens, draft_q, weights, temperature, u_acc, u_res, accept_len,
-                                       out_tokens, dev, n_valid, flags, ring, ring_head, ring_count, next_weights, s);
+                                       out_tokens, dev, n_valid, flags, ring, ring_head, ring_count, next_weights,
+                                       /*tree=*/false, s);
+    return e == hipSuccess ? TABED_OK : fail_hip(e);
+}
+
+int tabed_draft_siblings(const tabed_cfg* cfg, void* ws, uint64_t round, int32_t pos, int32_t tree_width,
+                         const float* draft_logits, const int32_t* draft_tokens, const float* weights,
+                         const float* temperature, const float* u_sib, int32_t* sib_tokens, float* sib_q,
+                         uint8_t* sib_flags, void* stream) {
+    const int rc = validate_cfg(cfg);
+    if (rc != TABED_OK) return rc;
+    if (tree_width < 1 || tree_width > TABED_MAX_TREE_WIDTH) return TABED_ERANGE;
+    if (pos < 0 || pos >= cfg->gamma) return TABED_ERANGE;
+    if (tree_width == 1) return TABED_OK;                   // a chain has no siblings
+    if (!ws || !draft_logits || !draft_tokens || !weights || !temperature || !sib_tokens || !sib_q || !sib_flags)
+        return TABED_ENULL;
+    if (misaligned(ws) || misaligned(draft_logits)) return TABED_EALIGN;
+    const WsLayout L = ws_layout(*cfg);
+    const float* slot = draft_logits + (size_t)pos * L.M * cfg->V;
+    const hipError_t e = launch_siblings(*cfg, L, static_cast<char*>(ws), round, pos, tree_width, slot, draft_tokens, weights,
+                                         temperature, u_sib, sib_tokens, sib_q, sib_flags, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? TABED_OK : fail_hip(e);
+}
+
+int tabed_verify_tree(const tabed_cfg* cfg, void* ws, uint64_t round, int32_t tree_width, const float* target_logits,
+                      const float* leaf_logits, const float* draft_logits, const double* draft_lse,
+                      const int32_t* draft_tokens, const float* draft_q, const int32_t* sib_tokens, const float* sib_q,
+                      const float* weights, const float* temperature, const float* u_acc, const float* u_res,
+                      const float* u_acc_sib, int32_t* accept_len, int32_t* out_tokens, float* dev, int32_t* n_valid,
+                      uint8_t* flags, int32_t* leaf, int32_t* n_out, float* ring, int32_t* ring_head,
+                      int32_t* ring_count, float* next_weights, void* stream) {
+    const int rc = validate_cfg(cfg);
+    if (rc != TABED_OK) return rc;
+    if (tree_width < 1 || tree_width > TABED_MAX_TREE_WIDTH) return TABED_ERANGE;
+    if (cfg->distance == 2) return TABED_EUNSUPPORTED;      // hard labels are defined for the chain only
+    if (!ws || !target_logits || !draft_logits || !draft_lse || !draft_tokens || !draft_q || !weights ||
+        !temperature || !accept_len || !out_tokens || !dev || !n_valid || !flags || !leaf || !n_out)
+        return TABED_ENULL;
+    if (tree_width > 1 && (!leaf_logits || !sib_tokens || !sib_q)) return TABED_ENULL;
+    if (misaligned(ws) || misaligned(target_logits) || misaligned(draft_logits) || misaligned(draft_lse) ||
+        (tree_width > 1 && misaligned(leaf_logits)))
+        return TABED_EALIGN;
+    const int nwin = (ring != nullptr) + (ring_head != nullptr) + (ring_count != nullptr) + (next_weights != nullptr);
+    if (nwin != 0 && nwin != 4) return TABED_ENULL;
+    if (next_weights == weights) return TABED_EINVAL;       // the tree passes still read this block's weights
+    const WsLayout L = ws_layout(*cfg);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_verify(*cfg, L, static_cast<char*>(ws), round, target_logits, draft_logits, draft_lse,
+                                 draft_tokens, draft_q, weights, temperature, u_acc, u_res, accept_len, out_tokens, dev,
+                                 n_valid, flags, ring, ring_head, ring_count, next_weights, /*tree=*/true, s);
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_verify_tree(*cfg, L, static_cast<char*>(ws), round, tree_width, target_logits, leaf_logits, draft_logits,
+                           draft_lse, sib_tokens, sib_q, weights, temperature, u_res, u_acc_sib, out_tokens, flags, leaf,
+                           n_out, s);
     return e == hipSuccess ? TABED_OK : fail_hip(e);
 }
 
@@ -280,6 +335,7 @@ const char* tabed_kernel_name(int id) {
         case TABED_K_RESID: return "resid";
         case TABED_K_WEIGHTS: return "weights";
         case TABED_K_DIST: return "dist";
+        case TABED_K_TREE: return "tree";
         case TABED_K_NULL: return "null";
         default: return "?";
     }

@@ -31,7 +31,8 @@ struct WsLayout {
     int M, NT, C2, C3max, NSEG, C5, RS;
     int DW;              // width of one distance vector: n, or 11 candidate mixtures (policy 2)
     int Cd;              // vocabulary chunks of the second-pass distance kernel
-    size_t off_tickets;  // uint32 [3][B]: arrival counters (0: greedy draft arg-max, 2: corrected/bonus sampler)
+    size_t off_tickets;  // uint32 [5][B]: arrival counters (0: greedy draft arg-max, 2: corrected/bonus sampler,
+                         // 3: token-tree residual level, 4: token-tree bonus after a leaf)
     size_t off_pm;       // float  [M][NT] tile maxima of scaled logits
     size_t off_ps;       // float  [M][NT] tile sums of exp(scaled logit - tile max)
     size_t off_cand;     // Top2Rec [B][C2]
@@ -39,6 +40,8 @@ struct WsLayout {
     size_t off_seg;      // double [B][2][NSEG] segment masses: residual, target
     size_t off_wstage;   // float [B][n] next weights staged by the fused window update
     size_t off_dist;     // double [B][gamma][DW][Cd][2] chunk sums, or chunk arg-maxes (value, index), of the second pass
+    size_t off_tstate;   // double [B][8] token-tree walk of every sequence (see TreeState)
+    size_t off_tseg;     // double [B][2][NSEG] token-tree passes: segment masses, segment maxima
     size_t total;
 };
 WsLayout ws_layout(const tabed_cfg& c);
@@ -55,12 +58,29 @@ hipError_t launch_sample(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
                          const float* u_draft, double* draft_lse, int32_t* draft_tokens, float* draft_q,
                          uint8_t* flags, hipStream_t s);
 
+// Token tree.  Slots of a sequence's record in the workspace (doubles):
+enum TreeState { kTsStatus = 0, kTsIndex = 1, kTsK = 2, kTsRowMax = 3, kTsRowZ = 4, kTsZ1 = 5, kTsZ2 = 6, kTsArgmax = 7, kTsSlots = 8 };
+constexpr int kTreeDone = 0, kTreePending = 1, kTreeLeaf = 2;   // kTsStatus; kTsIndex = next level / accepted sibling
+constexpr uint32_t kSiblingStride = 65536u;                     // Philox counter word 3 of sibling s: pos + s * 65536
+
+hipError_t launch_siblings(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round, int pos, int width,
+                           const float* logits /* slot pos */, const int32_t* draft_tokens, const float* weights,
+                           const float* temperature, const float* u_sib, int32_t* sib_tokens, float* sib_q,
+                           uint8_t* sib_flags, hipStream_t s);
+
+hipError_t launch_verify_tree(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round, int width,
+                              const float* target_logits, const float* leaf_logits, const float* draft_logits,
+                              const double* draft_lse, const int32_t* sib_tokens, const float* sib_q,
+                              const float* weights, const float* temperature, const float* u_res,
+                              const float* u_acc_sib, int32_t* out_tokens, uint8_t* flags, int32_t* leaf,
+                              int32_t* n_out, hipStream_t s);
+
 hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round,
                          const float* target_logits, const float* draft_logits, const double* draft_lse,
                          const int32_t* draft_tokens, const float* draft_q, const float* weights,
                          const float* temperature, const float* u_acc, const float* u_res, int32_t* accept_len,
                          int32_t* out_tokens, float* dev, int32_t* n_valid, uint8_t* flags, float* ring,
-                         int32_t* ring_head, int32_t* ring_count, float* next_weights, hipStream_t s);
+                         int32_t* ring_head, int32_t* ring_count, float* next_weights, bool tree, hipStream_t s);
 
 hipError_t launch_weights(const tabed_cfg& c, uint64_t round, const float* dev, const int32_t* n_valid, float* ring,
                           int32_t* ring_head, int32_t* ring_count, float* weights, hipStream_t s);

@@ -18,7 +18,7 @@ __global__ void k_fill_u32(uint32_t* p, int count) {
 }
 
 hipError_t launch_ws_init(const tabed_cfg& c, const WsLayout& L, char* ws, hipStream_t s) {
-    const int count = 3 * c.B;
+    const int count = 5 * c.B;
     launch(nullptr, k_fill_u32, dim3((count + 255) / 256), dim3(256), 0, s,
                        reinterpret_cast<uint32_t*>(ws + L.off_tickets), count);
     return hipGetLastError();
@@ -196,6 +196,8 @@ hipError_t launch_weights(const tabed_cfg& c, uint64_t round, const float* dev, 
 // =====================================================================================================
 struct SampleArgs {
     int V, n, B, gamma, pos, NT, C2;
+    int sib, S;           // token tree: sibling index of this launch (0 = the trunk token) and siblings per position
+    const int32_t* trunk; // token tree, sib > 0: trunk tokens [B,gamma] (a greedy row's siblings skip taken tokens)
     uint64_t seed, round;
     const float* logits;  // [B,n,V] of this position
     const float* pm;      // [B*n,NT]
@@ -238,9 +240,21 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
 
     const float* pmb = a.pm + (size_t)b * n * NT;      // partials of this sequence: [n][NT]
     const float* psb = a.ps + (size_t)b * n * NT;
-    const size_t out_idx = (size_t)b * a.gamma + a.pos;
+    // the trunk token goes to [B,gamma]; sibling s of a token tree to [B,gamma,S] and has a Philox block of its own
+    const size_t out_idx = (a.sib == 0) ? (size_t)b * a.gamma + a.pos
+                                        : ((size_t)b * a.gamma + a.pos) * a.S + (a.sib - 1);
     const float wj = (tid < n) ? a.weights[(size_t)b * n + tid] : 0.f;
-    const float u = a.u_draft ? a.u_draft[out_idx] : tabed_uniform(a.seed, a.round, (uint32_t)b, (uint32_t)a.pos, 0);
+    const float u = a.u_draft ? a.u_draft[out_idx]
+                              : tabed_uniform(a.seed, a.round, (uint32_t)b, (uint32_t)a.pos + (uint32_t)a.sib * kSiblingStride, 0);
+    int taken[TABED_MAX_TREE_WIDTH - 1];               // greedy siblings: tokens already in the candidate list
+#pragma unroll
+    for (int t = 0; t < TABED_MAX_TREE_WIDTH - 1; ++t) taken[t] = -1;
+    if (a.sib > 0) {
+        taken[0] = a.trunk[(size_t)b * a.gamma + a.pos];
+#pragma unroll
+        for (int t = 1; t < TABED_MAX_TREE_WIDTH - 1; ++t)
+            if (t < a.sib) taken[t] = a.draft_tokens[((size_t)b * a.gamma + a.pos) * a.S + (t - 1)];
+    }
 
     // Which tiles a thread owns.  Two-pass kernels and TI = 1: the contiguous run [tid*TI, tid*TI + TI).
     // Single-pass kernels: TI/4 chunks of 4 consecutive tiles, chunk q*256 + tid for q < TI/4 (for TI = 4 that
@@ -332,7 +346,7 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
             if (lane == 0) {
                 s_m[j] = M;
                 s_S[j] = S;
-                if (c == 0) a.draft_lse[((size_t)a.pos * a.B + b) * n + j] = (double)M + log(S);
+                if (c == 0 && a.sib == 0) a.draft_lse[((size_t)a.pos * a.B + b) * n + j] = (double)M + log(S);
             }
         }
     }
@@ -340,7 +354,7 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
     const float invT = greedy ? 1.f : 1.f / T;
     __syncthreads();
     if (N > 0) {
-        if (tid < N && c == 0) a.draft_lse[((size_t)a.pos * a.B + b) * n + tid] = lse_mine;
+        if (tid < N && c == 0 && a.sib == 0) a.draft_lse[((size_t)a.pos * a.B + b) * n + tid] = lse_mine;
     } else {
         if (tid < n) {
             s_c[tid] = (double)wj / s_S[tid];
@@ -501,8 +515,12 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
         for (int u = 0; u < 4; ++u) {
             const int v = cb + (u * kBlock + tid) * 4;
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (v + e < V) best = top2_push(best, q[u][e], v + e);
+            for (int e = 0; e < 4; ++e) {
+                bool free_tok = (v + e < V);
+#pragma unroll
+                for (int t = 0; t < TABED_MAX_TREE_WIDTH - 1; ++t) free_tok = free_tok && (v + e != taken[t]);
+                if (free_tok) best = top2_push(best, q[u][e], v + e);
+            }
         }
     }
     best = wave_top2(best);
@@ -531,19 +549,22 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
     double f = 0.0;
     for (int j = 0; j < n; ++j) f += s_c[j] * (double)__expf(rows[(size_t)j * V + y] * invT - s_m[j]);
     uint32_t flag = 0;
-    if (V > 1 && (t.v1 - t.v2) < kMargin * fabsf(t.v1)) flag |= TABED_FLAG_SAMPLE_MARGIN;
+    if (V > 1 + a.sib && (t.v1 - t.v2) < kMargin * fabsf(t.v1)) flag |= TABED_FLAG_SAMPLE_MARGIN;
     a.draft_tokens[out_idx] = y;
     a.draft_q[out_idx] = (float)f;
     a.flags[out_idx] = (uint8_t)flag;
 }
 
-hipError_t launch_sample(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round, int pos,
-                         const float* logits, const float* weights, const float* temperature,
-                         const float* u_draft, double* draft_lse, int32_t* draft_tokens, float* draft_q,
-                         uint8_t* flags, hipStream_t s) {
+// sib = 0: the trunk token of Alg. 1 line 7.  sib >= 1 (token tree of `width`): sibling `sib` of the position, from
+// the same softmax partials; the output arrays are then the [B,gamma,width-1] sibling arrays.
+static hipError_t launch_sample_any(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round, int pos,
+                                    const float* logits, const float* weights, const float* temperature,
+                                    const float* u_draft, double* draft_lse, int32_t* draft_tokens, float* draft_q,
+                                    uint8_t* flags, int sib, int width, const int32_t* trunk, hipStream_t s) {
     ProfScope prof(TABED_K_SAMPLE, s);
     SampleArgs a;
     a.V = c.V; a.n = c.n; a.B = c.B; a.gamma = c.gamma; a.pos = pos; a.NT = L.NT; a.C2 = L.C2;
+    a.sib = sib; a.S = width - 1; a.trunk = trunk;
     a.seed = c.seed; a.round = round;
     a.logits = logits;
     a.pm = reinterpret_cast<const float*>(ws + L.off_pm);
@@ -577,6 +598,28 @@ hipError_t launch_sample(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
 #undef TABED_LAUNCH_SAMPLE_N
 #undef TABED_LAUNCH_SAMPLE
     return hipGetLastError();
+}
+
+hipError_t launch_sample(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round, int pos,
+                         const float* logits, const float* weights, const float* temperature,
+                         const float* u_draft, double* draft_lse, int32_t* draft_tokens, float* draft_q,
+                         uint8_t* flags, hipStream_t s) {
+    return launch_sample_any(c, L, ws, round, pos, logits, weights, temperature, u_draft, draft_lse, draft_tokens,
+                             draft_q, flags, 0, 1, nullptr, s);
+}
+
+// Token tree: the width-1 siblings of position pos, one sampler launch each (a greedy row's sibling s needs
+// siblings 1..s-1 to skip them).  Uses the softmax partials the LM head of this position left in the workspace.
+hipError_t launch_siblings(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round, int pos, int width,
+                           const float* logits, const int32_t* draft_tokens, const float* weights,
+                           const float* temperature, const float* u_sib, int32_t* sib_tokens, float* sib_q,
+                           uint8_t* sib_flags, hipStream_t s) {
+    for (int sib = 1; sib < width; ++sib) {
+        const hipError_t e = launch_sample_any(c, L, ws, round, pos, logits, weights, temperature, u_sib, nullptr,
+                                               sib_tokens, sib_q, sib_flags, sib, width, draft_tokens, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // =====================================================================================================
@@ -949,6 +992,7 @@ struct FinishArgs {
     int hard;             // 1: dist holds chunk arg-maxes and the distance is the token-mismatch indicator
     int fuse;             // 1: the call also advances every sequence's window and writes the next weights
     WindowArgs win;
+    double* tstate;       // token tree: [B][kTsSlots] record of every sequence's walk, or nullptr (chain)
     float* wstage;        // [B][n] next weights, staged until every workgroup of the sequence has arrived
     double* seg;          // [B][2][NSEG]
     uint32_t* tickets;
@@ -977,11 +1021,11 @@ struct ResidRow {
 // (0 = run time, one batch of S loads per draft).
 template <bool VEC, int N, int S>
 __device__ __forceinline__ void resid_eval(const ResidRow& r, int n, int V, const int (&v)[S], const float* s_hi,
-                                           const float* s_lo, const float* s_w, float (&f)[S][4], float (&p)[S][4]) {
+                                           const float* s_lo, const float* s_w, float (&f)[S][4], float (&p)[S][4],
+                                           float (&q)[S][4]) {
     float4 tx[S];
 #pragma unroll
     for (int s = 0; s < S; ++s) tx[s] = load4<VEC>(r.trow, v[s], V);
-    float q[S][4];
 #pragma unroll
     for (int s = 0; s < S; ++s)
 #pragma unroll
@@ -1177,12 +1221,12 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
     const float* lo_k = s_lo[r.bonus ? 0 : k];
     constexpr int kSegPerChunk = kResidChunkV / kSegV;            // 8
     constexpr int kSegPerWave = kSegPerChunk / kWavesPerBlock;    // 2
-    float f[kSegPerWave][4], p[kSegPerWave][4];
+    float f[kSegPerWave][4], p[kSegPerWave][4], qmix[kSegPerWave][4];
     int vs[kSegPerWave];
     if (!greedy && !book) {
 #pragma unroll
         for (int s = 0; s < kSegPerWave; ++s) vs[s] = (c * kSegPerChunk + wave + s * kWavesPerBlock) * kSegV + lane * 4;
-        resid_eval<VEC, N, kSegPerWave>(r, n, V, vs, hi_k, lo_k, s_w, f, p);
+        resid_eval<VEC, N, kSegPerWave>(r, n, V, vs, hi_k, lo_k, s_w, f, p, qmix);
     }
 
     if (book) {
@@ -1230,6 +1274,12 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
         if (tid == 0) {
             a.accept_len[b] = k;
             a.n_valid[b] = k + 1 < gamma ? k + 1 : gamma;
+            if (a.tstate != nullptr && greedy) {           // token tree: where the trunk stopped and what the target wants there
+                double* ts = a.tstate + (size_t)b * kTsSlots;
+                ts[kTsK] = (double)k;
+                ts[kTsArgmax] = (double)s_rowam[k];
+                ts[kTsZ1] = 0.0;
+            }
         }
     }
     const int nv_k = k + 1 < gamma ? k + 1 : gamma;
@@ -1289,10 +1339,19 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
     for (int g = g0; g < g1; ++g) { runR += published_load(&segR[g]); runP += published_load(&segP[g]); }
     double run = runP;
     const double* mass = segP;
+    double Z1 = 0.0;
     if (!r.bonus) {
         const double Zr = block_sum(runR, s_redd);
-        if (Zr > 0.0) { run = runR; mass = segR; }
+        if (Zr > 0.0) { run = runR; mass = segR; Z1 = Zr; }
         else { r.bonus = true; flag |= TABED_FLAG_DEGENERATE; }   // empty residual: draw from p_k
+    }
+    if (a.tstate != nullptr && tid == 0) {                 // token tree: the first residual level is known here
+        double* ts = a.tstate + (size_t)b * kTsSlots;
+        ts[kTsK] = (double)k;
+        ts[kTsRowMax] = s_rowm[k];
+        ts[kTsRowZ] = s_rowZ[k];
+        ts[kTsZ1] = Z1;                                    // 0: all gamma accepted, or an empty residual
+        ts[kTsArgmax] = (double)s_rowam[k];
     }
     double Z;
     const double excl = block_exclusive_scan(run, s_redd, &Z);
@@ -1323,8 +1382,8 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
     __syncthreads();
     if (tid >= kWave) return;
     const int v1[1] = {s_seg * kSegV + lane * 4};
-    float f1[1][4], p1[1][4];
-    resid_eval<VEC, N, 1>(r, n, V, v1, hi_k, lo_k, s_w, f1, p1);
+    float f1[1][4], p1[1][4], q1[1][4];
+    resid_eval<VEC, N, 1>(r, n, V, v1, hi_k, lo_k, s_w, f1, p1, q1);
     const int v = v1[0];
     const double l1 = (double)f1[0][0], l2 = l1 + (double)f1[0][1], l3 = l2 + (double)f1[0][2], l4 = l3 + (double)f1[0][3];
     const double base = s_prefix + (wave_inclusive_scan(l4) - l4);
@@ -1364,7 +1423,7 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
                          const int32_t* draft_tokens, const float* draft_q, const float* weights,
                          const float* temperature, const float* u_acc, const float* u_res, int32_t* accept_len,
                          int32_t* out_tokens, float* dev, int32_t* n_valid, uint8_t* flags, float* ring,
-                         int32_t* ring_head, int32_t* ring_count, float* next_weights, hipStream_t s) {
+                         int32_t* ring_head, int32_t* ring_count, float* next_weights, bool tree, hipStream_t s) {
     const bool vec = (c.V % 4 == 0);
     const bool second_pass = (c.distance != 0 || c.policy == 2);   // distances that take a pass of their own
     const int ncomp = (vec && (c.n == 2 || c.n == 4 || c.n == 8)) ? c.n : 0;   // compile-time draft counts
@@ -1423,6 +1482,7 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
     a.fuse = (ring != nullptr) ? 1 : 0;
     a.win = window_args(c, round + 1, ring, ring_head, ring_count, next_weights);   // the weights of the NEXT round
     a.wstage = reinterpret_cast<float*>(ws + L.off_wstage);
+    a.tstate = tree ? reinterpret_cast<double*>(ws + L.off_tstate) : nullptr;
     a.seg = reinterpret_cast<double*>(ws + L.off_seg);
     a.tickets = reinterpret_cast<uint32_t*>(ws + L.off_tickets) + 2 * c.B;
     a.accept_len = accept_len; a.out_tokens = out_tokens; a.dev = dev; a.n_valid = n_valid; a.flags = flags;
@@ -1433,6 +1493,460 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
     else if (ncomp == 4) launch(&prof, k_finish<true, 4>, grid, dim3(kBlock), lds, s, a);
     else if (ncomp == 8) launch(&prof, k_finish<true, 8>, grid, dim3(kBlock), lds, s, a);
     else launch(&prof, k_finish<true, 0>, grid, dim3(kBlock), lds, s, a);
+    return hipGetLastError();
+}
+
+// =====================================================================================================
+// Token tree (Sec. 6.1, "Verification: Integrating Token Tree"): width sibling candidates per position, all
+// from the position's ensembled distribution; candidate 0 is the trunk token the chain verifies, candidates
+// 1..width-1 are leaves.  tabed_verify's kernels walk the trunk and leave, per sequence, where it stopped (k),
+// the target row's normaliser there and the mass Z_1 of the first residual.  The passes below finish the walk
+// at position k by multi-round rejection sampling: with f_0 = p_k, Z_0 = 1 and
+//     f_c(v) = max(0, f_{c-1}(v) / Z_{c-1} - q_k(v)),   Z_c = sum_v f_c(v),
+// sibling c is accepted iff u_c q_k(y_c) Z_c < f_c(y_c); an accepted sibling is emitted and followed by a
+// bonus token from the target's distribution after it (its leaf row); if all are rejected the corrected
+// token comes from f_width.  k_tree_begin decides sibling 1 (Z_1 is known), k_tree_level<L> computes level
+// L >= 2 for the sequences still undecided and either decides sibling L or (L = width) draws the corrected
+// token, k_tree_bonus draws the token after an accepted leaf.  Sequences whose walk is over skip every pass.
+// =====================================================================================================
+struct TreeArgs {
+    int V, n, B, gamma, S, NSEG, C5;       // S = width - 1 siblings per position
+    uint64_t seed, round;
+    const float* target;                   // [B,gamma+1,V]
+    const float* leaf_logits;              // [B,gamma,S,V]
+    const float* dlogits;                  // [gamma,B,n,V]
+    const double* dlse;                    // [gamma,B,n]
+    const int32_t* sib_tokens;             // [B,gamma,S]
+    const float* sib_q;                    // [B,gamma,S]
+    const float* weights;
+    const float* temperature;
+    const float* u_res;
+    const float* u_acc_sib;                // [B,gamma,S] or nullptr
+    double* tstate;                        // [B][kTsSlots]
+    const double* segP;                    // [B][2][NSEG] of tabed_verify's residual pass: slot 1 = masses of p_k
+    double* tseg;                          // [B][2][NSEG]
+    uint32_t* tickets;                     // [B] of this pass
+    int32_t* out_tokens;
+    uint8_t* flags;
+    int32_t* leaf;
+    int32_t* n_out;
+};
+
+// f_L(y) / Z_L's numerator chain at one token, in fp64, on the interface value q(y):
+// returns f_{L-1}(y) / Z_{L-1} (the minuend of level L) given p(y), q(y) and the masses of the lower levels.
+__device__ __forceinline__ double tree_minuend(int L, double py, double qy, double Z1, double Z2) {
+    double m = py;                                          // level 1: f_0 / Z_0 = p
+    if (L >= 2) m = fmax(0.0, m - qy) / Z1;
+    if (L >= 3) m = fmax(0.0, m - qy) / Z2;
+    return m;
+}
+
+// Sibling L's accept test (Z = Z_L).  Returns true if accepted; *flag gets the margin bit.
+__device__ __forceinline__ bool tree_test(int L, double py, double qy, double Z1, double Z2, double Z, float u, uint32_t* flag) {
+    const double minuend = tree_minuend(L, py, qy, Z1, Z2);
+    const double fy = fmax(0.0, minuend - qy), lhs = (double)u * qy * Z;
+    if (fabs(lhs - fy) < (double)kMargin * fmax(minuend, qy)) *flag |= TABED_FLAG_ACCEPT_MARGIN;
+    return lhs < fy;
+}
+
+__global__ __launch_bounds__(64) void k_tree_begin(TreeArgs a) {
+    const int b = blockIdx.x;
+    if (threadIdx.x != 0) return;
+    double* ts = a.tstate + (size_t)b * kTsSlots;
+    const int gamma = a.gamma, S = a.S, V = a.V;
+    const int k = (int)ts[kTsK];
+    const float T = a.temperature[b];
+    const bool greedy = !(T > 0.f);
+    int status = kTreeDone, index = 0;
+    a.leaf[b] = 0;
+    a.n_out[b] = k + 1;
+    if (k < gamma && S > 0) {
+        const size_t so = ((size_t)b * gamma + k) * S;
+        if (greedy) {
+            const int top = (int)ts[kTsArgmax];
+            for (int sidx = 1; sidx <= S && status == kTreeDone; ++sidx)
+                if (a.sib_tokens[so + sidx - 1] == top) { status = kTreeLeaf; index = sidx; }
+        } else if (ts[kTsZ1] > 0.0) {
+            // the chain's corrected token (drawn from level 1) is replaced: by a leaf, or by a draw from level width
+            uint32_t flag = a.flags[(size_t)b * (gamma + 1) + k] & ~(uint32_t)(TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE);
+            const int y = a.sib_tokens[so];
+            status = kTreePending; index = 2;
+            if (y >= 0 && y < V) {
+                const double lse = ts[kTsRowMax] + log(ts[kTsRowZ]);
+                const double py = exp((double)(a.target[((size_t)b * (gamma + 1) + k) * V + y] * (1.f / T)) - lse);
+                const float u = a.u_acc_sib ? a.u_acc_sib[so]
+                                            : tabed_uniform(a.seed, a.round, (uint32_t)b, (uint32_t)k + kSiblingStride, 1);
+                if (tree_test(1, py, (double)a.sib_q[so], 0.0, 0.0, ts[kTsZ1], u, &flag)) { status = kTreeLeaf; index = 1; }
+            } else {
+                flag |= TABED_FLAG_DEGENERATE;
+            }
+            a.flags[(size_t)b * (gamma + 1) + k] = (uint8_t)flag;
+        }
+    }
+    ts[kTsStatus] = (double)status;
+    ts[kTsIndex] = (double)index;
+}
+
+// Locates, in the workgroup that finishes a sequence, the 256-wide segment whose prefix of masses crosses
+// target = u * Z; thread `tid` owns segments [g0, g1).  Returns false if every mass is zero.
+__device__ __forceinline__ bool tree_pick_segment(const double* mass, int g0, int g1, double excl, double run, double target,
+                                                  int* s_first, int* s_lastw, int* s_seg, double* s_prefix) {
+    const int owner = block_find_owner(excl, run, target, s_first, s_lastw);
+    if (owner < 0) return false;
+    if ((int)threadIdx.x == owner) {
+        double P = excl, Plast = excl;
+        int gstar = -1, glast = g0;
+        for (int g = g0; g < g1; ++g) {
+            const double mg = published_load(&mass[g]);
+            if (mg > 0.0) { glast = g; Plast = P; }
+            if (P + mg > target) { gstar = g; break; }
+            P += mg;
+        }
+        if (gstar < 0) { gstar = glast; P = Plast; }
+        *s_seg = gstar;
+        *s_prefix = P;
+    }
+    __syncthreads();
+    return true;
+}
+
+// One wave: given the four values of every lane's group inside the chosen segment, the token where the prefix
+// crosses target, with the margin flags of the sampler.  Returns the token on every lane.
+__device__ __forceinline__ int tree_pick_token(const float (&f)[4], int v, int V, double prefix, double target, double Z,
+                                               uint32_t* flag) {
+    const int lane = threadIdx.x & 63;
+    const double l1 = (double)f[0], l2 = l1 + (double)f[1], l3 = l2 + (double)f[2], l4 = l3 + (double)f[3];
+    const double base = prefix + (wave_inclusive_scan(l4) - l4);
+    const double cdf[4] = {base + l1, base + l2, base + l3, base + l4};
+    int hit = -1, lastlive = -1;
+#pragma unroll
+    for (int e = 3; e >= 0; --e) {
+        if (f[e] > 0.f && cdf[e] > target) hit = e;
+        if (lastlive < 0 && f[e] > 0.f) lastlive = e;
+    }
+    const unsigned long long cross = __ballot(hit >= 0);
+    const unsigned long long live = __ballot(lastlive >= 0);
+    int pick;
+    if (cross) pick = __ffsll((long long)cross) - 1;
+    else if (live) { pick = 63 - __clzll((long long)live); *flag |= TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE; }
+    else { pick = 0; *flag |= TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE; }
+    const int e = cross ? hit : (live ? lastlive : 0);
+    int tok = v + e;
+    uint32_t mine = 0;
+    if (lane == pick) {
+        const double tol = (double)kMargin * Z;
+        const double fe = (double)(e == 0 ? f[0] : e == 1 ? f[1] : e == 2 ? f[2] : f[3]);
+        const double hi_edge = e == 0 ? cdf[0] : e == 1 ? cdf[1] : e == 2 ? cdf[2] : cdf[3];
+        if (fabs(hi_edge - target) < tol && tok + 1 < V) mine |= TABED_FLAG_SAMPLE_MARGIN;
+        if (tok > 0 && fabs((hi_edge - fe) - target) < tol) mine |= TABED_FLAG_SAMPLE_MARGIN;
+    }
+    tok = tok < V ? tok : V - 1;
+    *flag |= (uint32_t)__builtin_amdgcn_readlane((int)mine, pick);
+    return __builtin_amdgcn_readlane(tok, pick);
+}
+
+template <bool VEC, int N>
+__global__ __launch_bounds__(kBlock) void k_tree_level(TreeArgs a, int L) {
+    const int c = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    double* ts = a.tstate + (size_t)b * kTsSlots;
+    if ((int)ts[kTsStatus] != kTreePending || (int)ts[kTsIndex] != L) return;      // uniform over the grid row
+    const int V = a.V, n = (N > 0) ? N : a.n, gamma = a.gamma, S = a.S, NSEG = a.NSEG;
+    const int k = (int)ts[kTsK];
+    const float T = a.temperature[b];
+    const double Z1 = ts[kTsZ1], Z2 = ts[kTsZ2];
+    const float invZ1 = (float)(1.0 / Z1), invZ2 = (L >= 3) ? (float)(1.0 / Z2) : 0.f;
+
+    __shared__ float s_hi[TABED_MAX_N], s_lo[TABED_MAX_N], s_w[TABED_MAX_N];
+    __shared__ double s_redd[kWavesPerBlock];
+    __shared__ int s_last, s_first[kWavesPerBlock], s_lastw[kWavesPerBlock], s_seg;
+    __shared__ double s_prefix;
+    if (tid < n) {
+        const double l = a.dlse[((size_t)k * a.B + b) * n + tid];
+        const float hi = (float)l;
+        s_hi[tid] = hi;
+        s_lo[tid] = (float)(1.0 - (l - (double)hi));
+        s_w[tid] = a.weights[(size_t)b * n + tid];
+    }
+    __syncthreads();
+    ResidRow r;
+    r.bonus = false;
+    r.invT = 1.f / T;
+    r.trow = a.target + ((size_t)b * (gamma + 1) + k) * V;
+    r.pmax = (float)ts[kTsRowMax];
+    r.pinvZ = (float)(1.0 / ts[kTsRowZ]);
+    r.qrows = a.dlogits + ((size_t)k * a.B + b) * n * V;
+    // level L from the elementwise values: f_1 = max(0, p - q), f_2 = max(0, f_1 / Z_1 - q), f_3 = max(0, f_2 / Z_2 - q)
+    auto level = [&](float f1, float q) {
+        float f = fmaxf(0.f, f1 * invZ1 - q);
+        if (L >= 3) f = fmaxf(0.f, f * invZ2 - q);
+        return f;
+    };
+    constexpr int kSegPerChunk = kResidChunkV / kSegV, kSegPerWave = kSegPerChunk / kWavesPerBlock;
+    {
+        float f[kSegPerWave][4], p[kSegPerWave][4], q[kSegPerWave][4];
+        int vs[kSegPerWave];
+#pragma unroll
+        for (int sg = 0; sg < kSegPerWave; ++sg) vs[sg] = (c * kSegPerChunk + wave + sg * kWavesPerBlock) * kSegV + lane * 4;
+        resid_eval<VEC, N, kSegPerWave>(r, n, V, vs, s_hi, s_lo, s_w, f, p, q);
+#pragma unroll
+        for (int sg = 0; sg < kSegPerWave; ++sg) {
+            const int seg = c * kSegPerChunk + wave + sg * kWavesPerBlock;
+            float acc = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc += level(f[sg][e], q[sg][e]);
+            const double m = (double)wave_sum(acc);
+            if (lane == 0 && seg < NSEG) publish_store(&a.tseg[((size_t)b * 2 + 0) * NSEG + seg], m);
+        }
+    }
+    publish_barrier();
+    if (tid == 0) s_last = arrive(&a.tickets[b], (uint32_t)a.C5) ? 1 : 0;
+    __syncthreads();
+    if (!s_last) return;
+
+    // ---- last workgroup of the sequence: the level's mass, then sibling L's test or the corrected token
+    const double* massL = a.tseg + ((size_t)b * 2 + 0) * NSEG;
+    const double* massP = a.segP + ((size_t)b * 2 + 1) * NSEG;
+    const int SPT = (NSEG + kBlock - 1) / kBlock;
+    const int g0 = min(NSEG, tid * SPT), g1 = min(NSEG, g0 + SPT);
+    double run = 0.0;
+    for (int g = g0; g < g1; ++g) run += published_load(&massL[g]);
+    double Z;
+    double excl = block_exclusive_scan(run, s_redd, &Z);
+    const size_t fidx = (size_t)b * (gamma + 1) + k;
+    uint32_t flag = a.flags[fidx];
+    const bool degenerate = !(Z > 0.0);
+    const double* mass = massL;
+    if (degenerate) {
+        // empty residual (the lower level equals q): the token is drawn from p_k, whose segment masses the
+        // chain's residual pass left behind
+        flag |= TABED_FLAG_DEGENERATE;
+        run = 0.0;
+        for (int g = g0; g < g1; ++g) run += massP[g];
+        excl = block_exclusive_scan(run, s_redd, &Z);
+        mass = massP;
+        r.bonus = true;
+    } else if (L <= S) {
+        if (tid == 0) {
+            const size_t so = ((size_t)b * gamma + k) * S + (L - 1);
+            const int y = a.sib_tokens[so];
+            int decided = 0;
+            if (y >= 0 && y < V) {
+                const double lse = ts[kTsRowMax] + log(ts[kTsRowZ]);
+                const double py = exp((double)(r.trow[y] * r.invT) - lse);
+                const float u = a.u_acc_sib ? a.u_acc_sib[so]
+                                            : tabed_uniform(a.seed, a.round, (uint32_t)b, (uint32_t)k + (uint32_t)L * kSiblingStride, 1);
+                if (tree_test(L, py, (double)a.sib_q[so], Z1, Z2, Z, u, &flag)) decided = 1;
+            } else {
+                flag |= TABED_FLAG_DEGENERATE;
+            }
+            a.flags[fidx] = (uint8_t)flag;
+            if (decided) { ts[kTsStatus] = (double)kTreeLeaf; ts[kTsIndex] = (double)L; }
+            else { ts[kTsIndex] = (double)(L + 1); ts[kTsZ2] = Z; }   // L = 2: widths above 3 would need a Z_3
+        }
+        return;                                            // the next pass continues (or the leaf's bonus pass)
+    }
+    const float u = a.u_res ? a.u_res[b] : tabed_uniform(a.seed, a.round, (uint32_t)b, (uint32_t)gamma, 0);
+    const double target = (double)u * Z;
+    if (!tree_pick_segment(mass, g0, g1, excl, run, target, s_first, s_lastw, &s_seg, &s_prefix)) {
+        if (tid == 0) {
+            a.out_tokens[fidx] = 0;
+            a.flags[fidx] = (uint8_t)(flag | TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE);
+            ts[kTsStatus] = (double)kTreeDone;
+        }
+        return;
+    }
+    if (tid >= kWave) return;
+    const int v1[1] = {s_seg * kSegV + lane * 4};
+    float f1[1][4], p1[1][4], q1[1][4], fl[4];
+    resid_eval<VEC, N, 1>(r, n, V, v1, s_hi, s_lo, s_w, f1, p1, q1);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) fl[e] = degenerate ? p1[0][e] : level(f1[0][e], q1[0][e]);
+    const int tok = tree_pick_token(fl, v1[0], V, s_prefix, target, Z, &flag);
+    if (lane == 0) {
+        a.out_tokens[fidx] = tok;
+        a.flags[fidx] = (uint8_t)flag;
+        ts[kTsStatus] = (double)kTreeDone;
+    }
+}
+
+// Bonus token after an accepted leaf: a draw from softmax(leaf row / T) with the round's u_res (arg-max for a
+// greedy row).  Every wave leaves, per 256-wide segment, the maximum of the scaled logits and the sum of
+// exp(. - that maximum); the last workgroup combines them (fp64, segment order), finds the segment the uniform
+// falls into and re-evaluates it.  Greedy: per-segment (value, index) arg-max records, merged lowest index first.
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_tree_bonus(TreeArgs a) {
+    const int c = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    double* ts = a.tstate + (size_t)b * kTsSlots;
+    if ((int)ts[kTsStatus] != kTreeLeaf) return;
+    const int V = a.V, gamma = a.gamma, S = a.S, NSEG = a.NSEG;
+    const int k = (int)ts[kTsK], sidx = (int)ts[kTsIndex];
+    const float T = a.temperature[b];
+    const bool greedy = !(T > 0.f);
+    const float invT = greedy ? 1.f : 1.f / T;
+    const size_t so = ((size_t)b * gamma + k) * S + (sidx - 1);
+    const float* row = a.leaf_logits + so * V;
+    double* rec0 = a.tseg + ((size_t)b * 2 + 0) * NSEG;    // sampling: segment sum;  greedy: arg-max value
+    double* rec1 = a.tseg + ((size_t)b * 2 + 1) * NSEG;    // sampling: segment max;  greedy: arg-max index
+
+    __shared__ double s_redd[kWavesPerBlock];
+    __shared__ float s_redf[kWavesPerBlock];
+    __shared__ ArgMax s_am[kWavesPerBlock];
+    __shared__ int s_last, s_first[kWavesPerBlock], s_lastw[kWavesPerBlock], s_seg;
+    __shared__ double s_prefix;
+
+    constexpr int kSegPerChunk = kResidChunkV / kSegV, kSegPerWave = kSegPerChunk / kWavesPerBlock;
+    float4 x[kSegPerWave];
+#pragma unroll
+    for (int sg = 0; sg < kSegPerWave; ++sg)
+        x[sg] = load4<VEC>(row, (c * kSegPerChunk + wave + sg * kWavesPerBlock) * kSegV + lane * 4, V);
+#pragma unroll
+    for (int sg = 0; sg < kSegPerWave; ++sg) {
+        const int seg = c * kSegPerChunk + wave + sg * kWavesPerBlock;
+        const int v = seg * kSegV + lane * 4;
+        if (greedy) {
+            ArgMax am{-INFINITY, 0x7fffffff};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (v + e < V) am = argmax_merge(am, ArgMax{f4get(x[sg], e), v + e});
+            am = wave_argmax(am);
+            if (lane == 0 && seg < NSEG) { publish_store(&rec0[seg], (double)am.v); publish_store(&rec1[seg], (double)am.i); }
+        } else {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mx = fmaxf(mx, f4get(x[sg], e) * invT);
+            mx = wave_max(mx);
+            float acc = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float st = f4get(x[sg], e) * invT;
+                if (st > -INFINITY) acc += __expf(st - mx);
+            }
+            const double sum = (double)wave_sum(acc);
+            if (lane == 0 && seg < NSEG) { publish_store(&rec0[seg], sum); publish_store(&rec1[seg], (double)mx); }
+        }
+    }
+    publish_barrier();
+    if (tid == 0) s_last = arrive(&a.tickets[b], (uint32_t)a.C5) ? 1 : 0;
+    __syncthreads();
+    if (!s_last) return;
+
+    const size_t fidx = (size_t)b * (gamma + 1) + k;
+    const int SPT = (NSEG + kBlock - 1) / kBlock;
+    const int g0 = min(NSEG, tid * SPT), g1 = min(NSEG, g0 + SPT);
+    const int leaf_tok = a.sib_tokens[so];
+    if (greedy) {
+        ArgMax am{-INFINITY, 0x7fffffff};
+        for (int g = g0; g < g1; ++g) am = argmax_merge(am, ArgMax{(float)published_load(&rec0[g]), (int)published_load(&rec1[g])});
+        am = wave_argmax(am);
+        if (lane == 0) s_am[wave] = am;
+        __syncthreads();
+        if (tid == 0) {
+            ArgMax t = s_am[0];
+            for (int w = 1; w < kWavesPerBlock; ++w) t = argmax_merge(t, s_am[w]);
+            a.out_tokens[fidx] = leaf_tok;
+            a.out_tokens[fidx + 1] = (t.i >= 0 && t.i < V) ? t.i : 0;
+            a.flags[fidx + 1] = 0;
+            a.leaf[b] = sidx;
+            a.n_out[b] = k + 2;
+            ts[kTsStatus] = (double)kTreeDone;
+        }
+        return;
+    }
+    float ml = -INFINITY;
+    for (int g = g0; g < g1; ++g) ml = fmaxf(ml, (float)published_load(&rec1[g]));
+    const float M = block_max(ml, s_redf);
+    double run = 0.0;
+    for (int g = g0; g < g1; ++g) {
+        const double sg = published_load(&rec0[g]);
+        if (sg > 0.0) run += sg * exp(published_load(&rec1[g]) - (double)M);
+    }
+    // rescaled masses go back to slot 0 so that the owner can walk its own run (only this workgroup is left)
+    double Z;
+    const double excl = block_exclusive_scan(run, s_redd, &Z);
+    const float u = a.u_res ? a.u_res[b] : tabed_uniform(a.seed, a.round, (uint32_t)b, (uint32_t)gamma, 0);
+    const double target = (double)u * Z;
+    uint32_t flag = 0;
+    const int owner = block_find_owner(excl, run, target, s_first, s_lastw);
+    if (owner < 0) {
+        if (tid == 0) {
+            a.out_tokens[fidx] = leaf_tok; a.out_tokens[fidx + 1] = 0;
+            a.flags[fidx + 1] = (uint8_t)(TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE);
+            a.leaf[b] = sidx; a.n_out[b] = k + 2; ts[kTsStatus] = (double)kTreeDone;
+        }
+        return;
+    }
+    if (tid == owner) {
+        double P = excl, Plast = excl;
+        int gstar = -1, glast = g0;
+        for (int g = g0; g < g1; ++g) {
+            const double sg = published_load(&rec0[g]);
+            const double mg = (sg > 0.0) ? sg * exp(published_load(&rec1[g]) - (double)M) : 0.0;
+            if (mg > 0.0) { glast = g; Plast = P; }
+            if (P + mg > target) { gstar = g; break; }
+            P += mg;
+        }
+        if (gstar < 0) { gstar = glast; P = Plast; }
+        s_seg = gstar;
+        s_prefix = P;
+    }
+    __syncthreads();
+    if (tid >= kWave) return;
+    const int v = s_seg * kSegV + lane * 4;
+    const float4 xx = load4<VEC>(row, v, V);
+    float f[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float st = f4get(xx, e) * invT;
+        f[e] = (st > -INFINITY) ? __expf(st - M) : 0.f;
+    }
+    const int tok = tree_pick_token(f, v, V, s_prefix, target, Z, &flag);
+    if (lane == 0) {
+        a.out_tokens[fidx] = leaf_tok;
+        a.out_tokens[fidx + 1] = tok;
+        a.flags[fidx + 1] = (uint8_t)flag;
+        a.leaf[b] = sidx;
+        a.n_out[b] = k + 2;
+        ts[kTsStatus] = (double)kTreeDone;
+    }
+}
+
+hipError_t launch_verify_tree(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round, int width,
+                              const float* target_logits, const float* leaf_logits, const float* draft_logits,
+                              const double* draft_lse, const int32_t* sib_tokens, const float* sib_q,
+                              const float* weights, const float* temperature, const float* u_res,
+                              const float* u_acc_sib, int32_t* out_tokens, uint8_t* flags, int32_t* leaf,
+                              int32_t* n_out, hipStream_t s) {
+    ProfScope prof(TABED_K_TREE, s);
+    TreeArgs a;
+    a.V = c.V; a.n = c.n; a.B = c.B; a.gamma = c.gamma; a.S = width - 1; a.NSEG = L.NSEG; a.C5 = L.C5;
+    a.seed = c.seed; a.round = round;
+    a.target = target_logits; a.leaf_logits = leaf_logits; a.dlogits = draft_logits; a.dlse = draft_lse;
+    a.sib_tokens = sib_tokens; a.sib_q = sib_q; a.weights = weights; a.temperature = temperature;
+    a.u_res = u_res; a.u_acc_sib = u_acc_sib;
+    a.tstate = reinterpret_cast<double*>(ws + L.off_tstate);
+    a.segP = reinterpret_cast<const double*>(ws + L.off_seg);
+    a.tseg = reinterpret_cast<double*>(ws + L.off_tseg);
+    a.out_tokens = out_tokens; a.flags = flags; a.leaf = leaf; a.n_out = n_out;
+    a.tickets = reinterpret_cast<uint32_t*>(ws + L.off_tickets) + 3 * c.B;
+    // sibling 1 against the first residual (its mass is known from tabed_verify's pass); width 1: leaf = 0, n_out = k + 1
+    launch(&prof, k_tree_begin, dim3(c.B), dim3(64), 0, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || width == 1) return e;
+    const bool vec = (c.V % 4 == 0);
+    const int ncomp = (vec && (c.n == 2 || c.n == 4 || c.n == 8)) ? c.n : 0;
+    const dim3 grid(L.C5, c.B);
+    for (int lvl = 2; lvl <= width; ++lvl) {
+        if (!vec) launch(nullptr, k_tree_level<false, 0>, grid, dim3(kBlock), 0, s, a, lvl);
+        else if (ncomp == 2) launch(nullptr, k_tree_level<true, 2>, grid, dim3(kBlock), 0, s, a, lvl);
+        else if (ncomp == 4) launch(nullptr, k_tree_level<true, 4>, grid, dim3(kBlock), 0, s, a, lvl);
+        else if (ncomp == 8) launch(nullptr, k_tree_level<true, 8>, grid, dim3(kBlock), 0, s, a, lvl);
+        else launch(nullptr, k_tree_level<true, 0>, grid, dim3(kBlock), 0, s, a, lvl);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    a.tickets = reinterpret_cast<uint32_t*>(ws + L.off_tickets) + 4 * c.B;
+    if (vec) launch(nullptr, k_tree_bonus<true>, grid, dim3(kBlock), 0, s, a);
+    else launch(nullptr, k_tree_bonus<false>, grid, dim3(kBlock), 0, s, a);
     return hipGetLastError();
 }
 

@@ -143,3 +143,26 @@ def make_round(wl: Workload, W: np.ndarray, rnd: int):
         else:
             noise *= np.float32(wl.sigma)
     return H, np.ascontiguousarray(base + noise, dtype=np.float32)
+
+
+def make_tree_leaves(wl: Workload, W: np.ndarray, H: np.ndarray, rnd: int, width: int) -> np.ndarray:
+    """Target logits after the leaves of a width-`width` token tree: [B, gamma, width-1, V] fp32.
+
+    No model exists to condition on a leaf token, so the row after sibling s of position i follows the recipe of
+    the next position's target row (the matching draft's logits at hidden state H[i+1]) with a noise draw of its own.
+    """
+    S = width - 1
+    g = _rng(wl, 500000 + rnd)
+    shape = (wl.B, wl.gamma, S, wl.V)
+    if wl.target == "independent":
+        return g.standard_normal(shape, dtype=np.float32) * np.float32(wl.sigma)
+    jstar = matching_draft(wl, rnd)
+    Wf = as_f32(W, wl.w_dtype)
+    Hj = as_f32(H, wl.w_dtype)[1:, :, jstar, :]                       # [gamma, B, d]: positions 1..gamma
+    base = np.einsum("ibk,vk->biv", Hj, Wf, optimize=True).astype(np.float32)     # [B, gamma, V]
+    if wl.target == "student_t":
+        noise = g.standard_t(3.0, size=shape).astype(np.float32) * np.float32(wl.sigma)
+    else:
+        noise = g.standard_normal(shape, dtype=np.float32)
+        noise *= make_seq_sigma(wl)[:, None, None, None] if wl.target == "per_seq_sigma" else np.float32(wl.sigma)
+    return np.ascontiguousarray(base[:, :, None, :] + noise, dtype=np.float32)

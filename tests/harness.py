@@ -314,3 +314,140 @@ def run_rounds(oracle, wl, rounds, temp, seed=0, policy=0, check_logits=True, un
     limit = max(2, tally.decisions // 100) if max_gpu_flags is None else max_gpu_flags
     assert tally.gpu_only_flags <= limit, f"the GPU alone flagged {tally.gpu_only_flags} of {tally.decisions} decisions"
     return tally
+
+
+# ---------------------------------------------------------------- token tree (Sec. 6.1)
+def run_rounds_tree(oracle, wl, rounds, temp, width, seed=0, distance=0, fused=False, explicit_uniforms=False, policy=0):
+    """Both sides draft a width-`width` token tree (trunk + siblings per position) and verify it, state carried
+    over `rounds` rounds.  The trunk is compared by compare_round; on top of it the siblings (token, q, flags),
+    the accepted leaf, the number of emitted tokens and the tokens at and after the stopping position."""
+    S = width - 1
+    B, n, g, V, h = wl.B, wl.n, wl.gamma, wl.V, wl.h
+    W = synth.make_lm_head(wl)
+    W_t = to_dev_store(W, wl.w_dtype)
+    orc = OracleSide(oracle, wl, seed, policy, distance=distance)
+    cfg = cfg_of(wl, seed, policy=policy, distance=distance)
+    buf = binding.RoundBuffers(cfg, DEV)
+    zi = lambda shape, dt: torch.zeros(shape, dtype=dt, device=DEV)
+    sib_tok, sib_q, sib_fl = zi((B, g, max(S, 1)), torch.int32), zi((B, g, max(S, 1)), torch.float32), zi((B, g, max(S, 1)), torch.uint8)
+    leaf_t, nout_t = zi((B,), torch.int32), zi((B,), torch.int32)
+    next_w = zi((B, n), torch.float32)
+    tally = Tally()
+    SM, AM = binding.FLAG_SAMPLE_MARGIN, binding.FLAG_ACCEPT_MARGIN
+    first, need_update = True, True
+    rng = np.random.default_rng(777 + seed)
+    for rnd in range(rounds):
+        H, target = synth.make_round(wl, W, rnd)
+        leaves = synth.make_tree_leaves(wl, W, H, rnd, width) if S else np.zeros((B, g, 0, V), np.float32)
+        u = {}
+        if explicit_uniforms:
+            u = dict(u_draft=rng.random((B, g), dtype=np.float32), u_acc=rng.random((B, g), dtype=np.float32),
+                     u_res=rng.random(B, dtype=np.float32), u_sib=rng.random((B, g, S), dtype=np.float32),
+                     u_acc_sib=rng.random((B, g, S), dtype=np.float32))
+        # ---- oracle
+        w_o = oracle.update_weights(n=n, B=B, gamma=g, h=h, policy=policy, tau_w=1.0, eps=1e-6, dev=orc.dev, n_valid=orc.n_valid,
+                                    ring=orc.ring, ring_head=orc.head, ring_count=orc.count, seed=seed, rnd=rnd)
+        dl = np.zeros((g, B, n, V), np.float32); lse = np.zeros((g, B, n)); tok = np.zeros((B, g), np.int32)
+        dq = np.zeros((B, g), np.float32); fl = np.zeros((B, g), np.uint8)
+        o_st = np.zeros((B, g, S), np.int32); o_sq = np.zeros((B, g, S), np.float32); o_sf = np.zeros((B, g, S), np.uint8)
+        for pos in range(g):
+            oracle.draft_step(V=V, d=wl.d, n=n, B=B, gamma=g, w_dtype=wl.w_dtype, seed=seed, rnd=rnd, pos=pos, W=W, H=H[pos],
+                              weights=w_o, temperature=temp, draft_logits=dl, draft_lse=lse, draft_tokens=tok, draft_q=dq,
+                              flags=fl, u_draft=u.get("u_draft"))
+            if S:
+                oracle.draft_siblings(V=V, n=n, B=B, gamma=g, width=width, seed=seed, rnd=rnd, pos=pos, draft_logits=dl,
+                                      draft_tokens=tok, weights=w_o, temperature=temp, sib_tokens=o_st, sib_q=o_sq,
+                                      sib_flags=o_sf, u_sib=u.get("u_sib"))
+        o = oracle.verify_tree(V=V, n=n, B=B, gamma=g, width=width, distance=distance, seed=seed, rnd=rnd, target_logits=target,
+                               leaf_logits=leaves, draft_logits=dl, draft_tokens=tok, draft_q=dq, sib_tokens=o_st, sib_q=o_sq,
+                               weights=w_o, temperature=temp, u_acc=u.get("u_acc"), u_res=u.get("u_res"),
+                               u_acc_sib=u.get("u_acc_sib"))
+        orc.dev, orc.n_valid = o["dev"], o["n_valid"]
+        o.update(weights=w_o, draft_logits=dl, draft_lse=lse, draft_tokens=tok, draft_q=dq, draft_flags=fl)
+        # ---- GPU
+        t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV)
+        temp_t, tgt_t, leaves_t = t(temp), t(target), t(leaves)
+        ug = {k: t(v) for k, v in u.items()}
+        if need_update:
+            buf.update_weights(first, rnd=rnd)
+        first, need_update = False, not fused
+        w_used = buf.weights.clone()
+        for pos in range(g):
+            buf.draft_step(rnd, pos, W_t, to_dev_store(H[pos], wl.w_dtype), temp_t, ug.get("u_draft"))
+            if S:
+                binding.tabed_draft_siblings(cfg, buf.ws, rnd, pos, width, buf.draft_logits, buf.draft_tokens, buf.weights,
+                                             temp_t, sib_tok, sib_q, sib_fl, u_sib=ug.get("u_sib"))
+        win = dict(ring=buf.ring, ring_head=buf.ring_head, ring_count=buf.ring_count, next_weights=next_w) if fused else {}
+        binding.tabed_verify_tree(cfg, buf.ws, rnd, width, tgt_t, leaves_t if S else None, buf.draft_logits, buf.draft_lse,
+                                  buf.draft_tokens, buf.draft_q, sib_tok if S else None, sib_q if S else None, buf.weights,
+                                  temp_t, buf.accept_len, buf.out_tokens, buf.dev, buf.n_valid, buf.verify_flags, leaf_t,
+                                  nout_t, u_acc=ug.get("u_acc"), u_res=ug.get("u_res"), u_acc_sib=ug.get("u_acc_sib"), **win)
+        torch.cuda.synchronize()
+        if fused:
+            buf.weights.copy_(next_w)
+        c = lambda x: x.cpu().numpy()
+        gd = dict(weights=c(w_used), draft_logits=c(buf.draft_logits), draft_lse=c(buf.draft_lse), draft_tokens=c(buf.draft_tokens),
+                  draft_q=c(buf.draft_q), draft_flags=c(buf.draft_flags), accept_len=c(buf.accept_len), out_tokens=c(buf.out_tokens),
+                  dev=c(buf.dev), n_valid=c(buf.n_valid), flags=c(buf.verify_flags))
+        g_st, g_sq, g_sf, g_leaf, g_nout = c(sib_tok)[:, :, :S], c(sib_q)[:, :, :S], c(sib_fl)[:, :, :S], c(leaf_t), c(nout_t)
+        # ---- the walk beyond the trunk, sequence by sequence
+        lock = True
+        np.testing.assert_allclose(gd["weights"], o["weights"], rtol=1e-5, atol=1e-6)
+        err = float(np.max(np.abs(gd["draft_logits"] - o["draft_logits"])))
+        assert err <= 1e-5 * max(float(np.max(np.abs(o["draft_logits"]))), 1.0)
+        tally.max_logit_err = max(tally.max_logit_err, err)
+        np.testing.assert_allclose(gd["draft_lse"], o["draft_lse"], rtol=0, atol=2e-6)
+        derr = np.abs(gd["dev"] - o["dev"])
+        assert np.all(derr <= 1e-5 * np.abs(o["dev"]) + 1e-6)
+        tally.max_dev_err = max(tally.max_dev_err, float(derr.max()))
+        for b in range(B):
+            ok = True
+            for pos in range(g):                      # candidates: trunk, then siblings
+                cands = [(gd["draft_tokens"][b, pos], o["draft_tokens"][b, pos], gd["draft_q"][b, pos], o["draft_q"][b, pos],
+                          gd["draft_flags"][b, pos] | o["draft_flags"][b, pos])]
+                cands += [(g_st[b, pos, s], o_st[b, pos, s], g_sq[b, pos, s], o_sq[b, pos, s], g_sf[b, pos, s] | o_sf[b, pos, s])
+                          for s in range(S)]
+                for tg, to, qg, qo, fboth in cands:
+                    tally.decisions += 1
+                    if tg != to:
+                        assert fboth & SM, f"unflagged candidate mismatch b={b} pos={pos}: {tg} vs {to}"
+                        tally.flagged_divergences += 1
+                        ok = False
+                        break
+                    assert abs(float(qg) - float(qo)) <= 1e-5 * float(qo), (b, pos, qg, qo)
+                if not ok:
+                    break
+            if not ok:
+                lock = False
+                continue
+            tally.decisions += 1
+            kg, ko = int(gd["accept_len"][b]), int(o["accept_len"][b])
+            if kg != ko:
+                assert (gd["flags"][b, min(kg, ko)] | o["flags"][b, min(kg, ko)]) & AM, f"unflagged accept-length mismatch b={b}: {kg} vs {ko}"
+                tally.flagged_divergences += 1
+                lock = False
+                continue
+            assert gd["n_valid"][b] == o["n_valid"][b] == min(ko + 1, g)
+            assert np.array_equal(gd["out_tokens"][b, :ko], o["out_tokens"][b, :ko])
+            fk = int(gd["flags"][b, min(ko, g)] | o["flags"][b, min(ko, g)])
+            if g_leaf[b] != o["leaf"][b]:
+                assert fk & AM, f"unflagged sibling decision mismatch b={b} k={ko}: leaf {g_leaf[b]} vs {o['leaf'][b]}"
+                tally.flagged_divergences += 1
+                continue
+            assert g_nout[b] == o["n_out"][b] == ko + 1 + (1 if o["leaf"][b] else 0)
+            m = int(o["n_out"][b])
+            assert np.all(gd["out_tokens"][b, m:] == -1) and np.all(o["out_tokens"][b, m:] == -1)
+            for col in range(ko, m):
+                tally.decisions += 1
+                if gd["out_tokens"][b, col] != o["out_tokens"][b, col]:
+                    fcol = int(gd["flags"][b, col] | o["flags"][b, col])
+                    assert fcol & SM, f"unflagged emitted-token mismatch b={b} col={col}: {gd['out_tokens'][b]} vs {o['out_tokens'][b]}"
+                    tally.flagged_divergences += 1
+        tally.leaves = getattr(tally, "leaves", 0) + int((o["leaf"] > 0).sum())
+        tally.emitted = getattr(tally, "emitted", 0) + int(o["n_out"].sum())
+        if not lock:
+            buf.ring.copy_(torch.from_numpy(orc.ring).to(DEV)); buf.ring_head.copy_(torch.from_numpy(orc.head).to(DEV))
+            buf.ring_count.copy_(torch.from_numpy(orc.count).to(DEV)); buf.dev.copy_(torch.from_numpy(orc.dev).to(DEV))
+            buf.n_valid.copy_(torch.from_numpy(orc.n_valid).to(DEV))
+            need_update = True
+    return tally

@@ -317,6 +317,57 @@ def test_lvlm_recipe_70_rounds_reduced_vocabulary(oracle):
     assert np.all(last[71][0] == 1) and np.all(last[71][1] == 1)
 
 
+# ------------------------------------------------------------------ token tree (Sec. 6.1)
+TREE_CASES = [
+    # V,     d,   n, B, gamma, h, w_dtype, temperature, width, fused window update, explicit uniforms
+    (1000,   64,  2, 3, 3,     4, 0, "one",     2, False, False),
+    (4099,   72,  3, 5, 4,     5, 1, "mixed07", 3, False, False),    # V % 4 != 0, greedy and sampling rows
+    (8200,   128, 4, 6, 2,     3, 1, "greedy",  3, False, False),
+    (40,     16,  2, 24, 3,    3, 1, "greedy",  3, False, False),    # tiny vocabulary: greedy siblings do get accepted
+    (5000,   64,  5, 9, 2,     3, 1, "mixed07", 2, True,  True),
+    (32000,  768, 4, 16, 5,    8, 1, "one",     2, False, False),    # the serving shape
+    (32000,  768, 4, 16, 5,    8, 1, "one",     3, True,  False),
+    (152064, 896, 4, 2, 2,     16, 1, "mixed07", 3, False, False),   # large vocabulary: several segments per thread
+]
+
+
+@pytest.mark.parametrize("case", TREE_CASES, ids=lambda c: f"V{c[0]}n{c[2]}B{c[3]}w{c[8]}{c[7]}")
+def test_token_tree_matches_oracle(oracle, case):
+    V, d, n, B, gamma, h, w_dtype, mode, width, fused, explicit = case
+    _say(f"token tree {case}")
+    wl = synth.scaled(SERVING, V=V, d=d, n=n, B=B, gamma=gamma, h=h, w_dtype=w_dtype, cfg_id=130 + V % 11)
+    # the 40-token case runs with static weights: its distances are tiny, and 1/e would amplify their rounding
+    tally = harness.run_rounds_tree(oracle, wl, 5, synth.make_temperature(wl, mode), width, fused=fused,
+                                    explicit_uniforms=explicit, policy=1 if V < 100 else 0)
+    _say(f"{tally} leaves={tally.leaves} emitted={tally.emitted}")
+    assert tally.flagged_divergences <= max(2, tally.decisions // 50)
+    assert tally.leaves > 0 or mode == "greedy" or B * 5 < 20      # sibling acceptances are exercised
+
+
+def test_token_tree_of_width_one_is_the_chain(oracle):
+    """tabed_verify_tree with tree_width = 1 leaves exactly what tabed_verify leaves, plus leaf = 0 and n_out = k + 1."""
+    wl = synth.scaled(SERVING, V=8200, d=128, B=6, gamma=3, cfg_id=141)
+    W = synth.make_lm_head(wl)
+    temp = synth.make_temperature(wl, "mixed07")
+    H, target = synth.make_round(wl, W, 0)
+    gpu = harness.GpuSide(wl)
+    ref = gpu.round(0, harness.to_dev_store(W, wl.w_dtype), H, target, temp)
+    buf = gpu.buf
+    leaf = torch.full((wl.B,), -7, dtype=torch.int32, device=DEV)
+    n_out = torch.full((wl.B,), -7, dtype=torch.int32, device=DEV)
+    for t in (buf.accept_len, buf.out_tokens, buf.n_valid):
+        t.fill_(-9)
+    buf.dev.fill_(-1.0)
+    binding.tabed_verify_tree(gpu.cfg, buf.ws, 0, 1, torch.from_numpy(target).to(DEV), None, buf.draft_logits, buf.draft_lse,
+                              buf.draft_tokens, buf.draft_q, None, None, buf.weights, torch.from_numpy(temp).to(DEV),
+                              buf.accept_len, buf.out_tokens, buf.dev, buf.n_valid, buf.verify_flags, leaf, n_out)
+    torch.cuda.synchronize()
+    for key, tens in (("accept_len", buf.accept_len), ("out_tokens", buf.out_tokens), ("dev", buf.dev),
+                      ("n_valid", buf.n_valid), ("flags", buf.verify_flags)):
+        assert np.array_equal(tens.cpu().numpy(), ref[key]), key
+    assert np.all(leaf.cpu().numpy() == 0) and np.array_equal(n_out.cpu().numpy(), ref["accept_len"] + 1)
+
+
 def test_hip_graph_replay_matches_eager_bitwise(oracle):
     """bench.py replays captured rounds: a captured sequence of the C-ABI calls must give, on every replay,
     exactly what the same calls give when issued eagerly from the same state."""
