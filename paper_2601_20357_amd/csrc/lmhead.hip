@@ -6,7 +6,6 @@
 // correctness configuration) use plain FMAs.
 #include <hip/hip_bf16.h>
 
-#include <cstdlib>
 #include <mutex>
 #include <type_traits>
 
@@ -645,142 +644,6 @@ __global__ __launch_bounds__(NW * 64) void k_lmhead_large(int M, int d, int V, i
                                tpatch);
 }
 
-// ---------------------------------------------------------------- bf16, many rows, hidden size a multiple of 32:
-// the same 256 x 256 workgroup tile with FOUR waves of 128 x 128 (16 accumulator tiles = 256 registers per lane, one
-// wave per SIMD) and no register staging at all: k-blocks of 32 travel from global memory straight into LDS
-// (global_load_lds_dwordx4: every lane names its own 16 global bytes, the wave's 64 pieces land contiguously at
-// M0 + lane * 16), four stages deep, so three k-blocks (~1.3 us of MFMA work) are in flight while one is multiplied.
-// Against the eight-wave kernel above this halves the LDS bytes read per flop (each operand fragment feeds four MFMAs
-// instead of two or four), which is what bounded that kernel, and frees the registers its staging sets took.
-//   * LDS rows are 64 bytes, unpadded (a wave's 1 KB lands contiguously); bank conflicts are avoided by a swizzle
-//     instead: slot s of row r holds k-chunk s ^ ((r >> 2) & 3), chosen by which global chunk a lane asks for, so the
-//     16 lanes that read one chunk of 16 consecutive rows touch 16 distinct 16-byte bank groups.
-//   * one barrier per k-block: a wave waits for its own loads of the block (vmcnt), the barrier makes everybody's
-//     visible and retires the stage the previous block was read from, which the loads issued next overwrite.
-constexpr int kBigThreads = 256;
-constexpr int kBigLds = 128 * 1024;                                       // all stages together
-
-__device__ __forceinline__ void load_to_lds_16(const uint16_t* src, unsigned char* lds_wave_base) {
-    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
-                                     (void __attribute__((address_space(3)))*)lds_wave_base, 16, 0, 0);
-}
-
-// BK = k per block: 32 (64-byte rows, four stages) or 64 (128-byte rows = whole cache lines, two stages).
-template <int BK>
-__global__ __launch_bounds__(kBigThreads) void k_lmhead_big(int M, int d, int V, int n, int NT, int mblocks,
-                                                            const uint16_t* __restrict__ W,
-                                                            const uint16_t* __restrict__ H,
-                                                            const float* __restrict__ temperature,
-                                                            float* __restrict__ L, float* __restrict__ pm,
-                                                            float* __restrict__ ps, int dry) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    __shared__ float s_invt[kLBM];
-    constexpr int ROWB = BK * 2;                       // bytes per LDS row
-    constexpr int CH = BK / 8;                         // 16-byte slots per row
-    constexpr int STAGE = (kLBM + kLBN) * ROWB;        // W rows, then H rows
-    constexpr int STAGES = kBigLds / STAGE;
-    constexpr int RPI = 64 / CH;                       // rows one wave-instruction covers (1 KB)
-    constexpr int IPO = kLBN / 4 / RPI;                // instructions per operand, wave and k-block
-    static_assert(STAGES >= 2 && (kLBN / 4) % RPI == 0, "stage split");
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nn = lane & 31, half = lane >> 5;
-    const int w = blockIdx.x, xcd = w & 7, slot = w >> 3;                 // XCD-aware numbering, as in k_lmhead_large
-    const int mb = slot % mblocks, nb = (slot / mblocks) * 8 + xcd;
-    const int m0 = mb * kLBM;
-    int v0 = nb * kLBN;
-    if (v0 >= V) return;
-    if (dry == 2) v0 = 0;                                  // TEMP: every workgroup reads the same W tile
-    const int wm = wave >> 1, wn = wave & 1;
-    if (tid < kLBM && m0 + tid < M) s_invt[tid] = row_inv_temperature(temperature, m0 + tid, n);
-
-    // swizzle: slot s of row r holds k-chunk s ^ swz(r); the 16 lanes that read one chunk of 16 consecutive rows
-    // then touch 16 distinct 16-byte bank groups
-    auto swz = [](int row) { return CH == 4 ? (row >> 2) & 3 : (row >> 1) & 7; };
-    // ---- who loads what: instruction t of a wave covers rows (wave * IPO + t) * RPI + lane / CH of the W part and
-    //      of the H part of a stage; the lane's slot lane % CH receives k-chunk slot ^ swz(row)
-    const uint16_t* wsrc[IPO];
-    const uint16_t* hsrc[IPO];
-#pragma unroll
-    for (int t = 0; t < IPO; ++t) {
-        const int row = (wave * IPO + t) * RPI + lane / CH;
-        const int chunk = (lane % CH) ^ swz(row);
-        wsrc[t] = W + (size_t)min(v0 + row, V - 1) * d + chunk * 8;       // clamped rows are masked in the epilogue
-        hsrc[t] = H + (size_t)min(m0 + row, M - 1) * d + chunk * 8;
-    }
-    const int KB = d / BK;
-    auto issue = [&](int kb) {
-        unsigned char* st = lds + (kb % STAGES) * STAGE + wave * (IPO * 1024);
-#pragma unroll
-        for (int t = 0; t < IPO; ++t) load_to_lds_16(wsrc[t] + kb * BK, st + t * 1024);
-#pragma unroll
-        for (int t = 0; t < IPO; ++t) load_to_lds_16(hsrc[t] + kb * BK, st + kLBN * ROWB + t * 1024);
-    };
-
-    f32x16 acc[4][4];                                                     // [vocabulary tile][row tile]
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-
-    const int sw = swz(nn);                                               // rows 32 apart share it
-#pragma unroll
-    for (int j = 0; j < STAGES - 1; ++j)
-        if (j < KB) issue(j);
-    for (int kb = 0; kb < KB; ++kb) {
-        // this wave's loads of k-block kb have landed (the blocks issued after it may still be in flight) ...
-        const int newer = min(STAGES - 2, KB - 1 - kb);                   // k-blocks issued after kb
-        if (newer >= 2) asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");       // 2 x 8 (BK = 32 only)
-        else if (newer == 1) asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-        // ... and so have everybody's; the stage k-block kb - 1 was read from is free again
-        if (kb + STAGES - 1 < KB) issue(kb + STAGES - 1);
-        const unsigned char* sW = lds + (kb % STAGES) * STAGE;
-        const unsigned char* sH = sW + kLBN * ROWB;
-        bf16x8 wf[2][4], hf[2][4];
-        auto read_frags = [&](int ks, int set) {
-            const int sl = ((2 * ks + half) ^ sw) * 16;
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-                wf[set][a] = *reinterpret_cast<const bf16x8*>(sW + (wn * 128 + a * 32 + nn) * ROWB + sl);
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-                hf[set][b] = *reinterpret_cast<const bf16x8*>(sH + (wm * 128 + b * 32 + nn) * ROWB + sl);
-        };
-        read_frags(0, 0);
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            if (ks + 1 < BK / 16) read_frags(ks + 1, (ks + 1) & 1);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 4; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks & 1][a], hf[ks & 1][b], acc[a][b], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-    // ---- epilogue: every wave turns its sixteen 32x32 blocks through a private patch carved from stage 0
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // every wave is done with the last stage
-    unsigned char* tpatch = lds + wave * kPatchBytes;
-    if (dry) {                                             // TEMP timing experiment: one value per tile instead of the tile
-        float t = 0.f;
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) t += acc[a][b][0] + acc[a][b][7];
-        if (t == 123.456f) L[0] = t;
-        return;
-    }
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-            store_tile_32x32_t(acc[a][b], m0 + wm * 128 + b * 32, v0 + wn * 128 + a * 32, M, V, NT, s_invt - m0, L, pm, ps,
-                               tpatch);
-}
-
 // ---------------------------------------------------------------- fp32 operands: one output per thread
 // Workgroup = 8 rows x 32 vocabulary entries; a half-wave shares one row, so the tile partials are a
 // half-wave reduction.  Only the tiny correctness configuration stores fp32 weights.
@@ -913,22 +776,6 @@ hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& Lay, char* ws, cons
     } else if (skinny_kc_kh(c, M) != 0) {
         const hipError_t e = launch_skinny_kc(&prof, skinny_kc_kh(c, M), c, Lay, M, W, H, temperature, logits, pm, ps, s);
         if (e != hipSuccess) return e;
-    } else if (M > 64 && c.d % 64 == 0 && getenv("TABED_BIG") != nullptr) {
-        static std::once_flag attr_once, attr_once2;       // raise the dynamic-LDS limit once
-        static hipError_t attr_rc = hipSuccess, attr_rc2 = hipSuccess;
-        const size_t lds = (size_t)kBigLds;
-        const int mblocks = (M + kLBM - 1) / kLBM, nblocks = (c.V + kLBN - 1) / kLBN;
-        const int nrounds = (nblocks + 7) / 8;             // vocabulary blocks are dealt to the 8 XCDs in rounds
-        const dim3 grid(nrounds * mblocks * 8);
-        if (getenv("TABED_BIG")[0] == '6') {
-            if (raise_lds_limit(&k_lmhead_big<64>, lds, attr_once, attr_rc) != hipSuccess) return attr_rc;
-            launch(&prof, k_lmhead_big<64>, grid, dim3(kBigThreads), lds, s, M, c.d, c.V, c.n, Lay.NT, mblocks,
-                   static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), temperature, logits, pm, ps, getenv("TABED_DRY") != nullptr ? atoi(getenv("TABED_DRY")) : 0);
-        } else {
-            if (raise_lds_limit(&k_lmhead_big<32>, lds, attr_once2, attr_rc2) != hipSuccess) return attr_rc2;
-            launch(&prof, k_lmhead_big<32>, grid, dim3(kBigThreads), lds, s, M, c.d, c.V, c.n, Lay.NT, mblocks,
-                   static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), temperature, logits, pm, ps, getenv("TABED_DRY") != nullptr ? atoi(getenv("TABED_DRY")) : 0);
-        }
     } else if (M > 64 && c.d % 64 == 0) {
         static std::once_flag attr_once;                   // raise the dynamic-LDS limit once
         static hipError_t attr_rc = hipSuccess;
