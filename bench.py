@@ -77,6 +77,9 @@ def parse():
     ap.add_argument("--launch", default="graph", choices=["graph", "eager"],
                     help="graph: the pool's rounds are captured once into a HIP graph (stream capture of the same "
                          "C-ABI calls) and replayed; eager: every call is issued from Python each round")
+    ap.add_argument("--tree-width", type=int, default=1,
+                    help="token tree of this width (2 or 3) instead of the chain: every draft step also draws the "
+                         "siblings, tabed_verify_tree verifies; the window update is then a call of its own")
     ap.add_argument("--policy", type=int, default=0, help="weight policy (0 softmax of 1/e, 1 static, 2 two-draft grid, 3 random)")
     ap.add_argument("--distance", type=int, default=0, help="0 KL, 1 total variation")
     ap.add_argument("--drafts", type=int, default=0, help="override the workload's number of drafts n (2 for --policy 2)")
@@ -123,6 +126,21 @@ def gen_inputs(wl, pool, w_copies, device):
         Hs.append(H.contiguous())
         Ts.append(tgt.float().contiguous())
     return Ws, Hs, Ts, temp.float().contiguous()
+
+
+def gen_leaf_logits(wl, Ws, Hs, width, device):
+    """Target logits after the leaves of a token tree, [B,gamma,width-1,V] per pooled round: the recipe of the next
+    position's target row with a noise draw of its own (see synth.make_tree_leaves)."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(1000 * wl.cfg_id + 7)
+    out = []
+    for r, H in enumerate(Hs):
+        jstar = (r // wl.switch_every) % wl.n if wl.target == "switching" else 0
+        base = torch.einsum("ibk,vk->biv", H[1:, :, jstar, :].float(), Ws[0].float())      # [B,gamma,V]
+        noise = torch.randn((wl.B, wl.gamma, width - 1, wl.V), generator=g, device=device) * (wl.sigma or 0.8)
+        out.append((base[:, :, None, :] + noise).float().contiguous())
+    return out
 
 
 CPU_SAMPLE = {"tiny": (2000, None), "llava": (120, None), "serving": (60, None), "lvlm": (4, None), "stress": (1, 8)}
@@ -195,6 +213,11 @@ def main():
                            policy=args.policy, distance=args.distance)
     buf = binding.RoundBuffers(cfg, device)
 
+    tree = args.tree_width > 1
+    if tree:
+        args.separate_update = True
+        buf.enable_tree(args.tree_width)
+        Ls = gen_leaf_logits(wl, Ws, Hs, args.tree_width, device)
     upd_first = buf.prepare_update_weights(True)
     upd = buf.prepare_update_weights(False)
     def make_slots(per_step_rotation):
@@ -206,7 +229,11 @@ def main():
                 # as they would with a 68M-class draft body between them); per-step: every call a fresh copy
                 W = Ws[(r * wl.gamma + pos) % len(Ws)] if per_step_rotation else Ws[r % len(Ws)]
                 drafts.append(buf.prepare_draft_step(0, pos, W, Hs[r][pos], temp))
-            out.append((drafts, buf.prepare_verify(0, Ts[r], temp, fused_update=not args.separate_update)))
+                if tree:
+                    drafts.append(buf.prepare_draft_siblings(0, pos, temp))
+            ver = (buf.prepare_verify_tree(0, Ts[r], Ls[r], temp) if tree else
+                   buf.prepare_verify(0, Ts[r], temp, fused_update=not args.separate_update))
+            out.append((drafts, ver))
         return out
 
     slots = make_slots(False)
@@ -291,7 +318,7 @@ def main():
     else:
         dt = timed(args.steps)
     ms_per_step = dt / args.steps * 1e3
-    emitted = float(buf.accept_len.float().mean().item()) + 1.0
+    emitted = float(buf.n_out.float().mean().item()) if tree else float(buf.accept_len.float().mean().item()) + 1.0
 
     # ---- second, instrumented pass over the same steps: per-kernel HIP-event timing on the launch stream
     kernels = {}
@@ -366,7 +393,7 @@ def main():
         + (alg_bytes["dist"] if (args.distance != 0 or args.policy == 2) else 0)
     out = {
         "metric": ("ensemble-draft+verify steps/sec at V=32k,n=4,B=16; HBM GB/s & MFMA % of peak"
-                   if wl.name == "serving" else "ensemble-draft+verify steps/sec"),
+                   if wl.name == "serving" and not tree else "ensemble-draft+verify steps/sec"),
         "value": args.steps / dt, "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -374,8 +401,9 @@ def main():
         "config": {"workload": f"{wl.name}: V={wl.V} d={wl.d} n={wl.n} B={wl.B} gamma={wl.gamma} h={wl.h} "
                                f"temperature={wl.temperature} policy={args.policy} distance={args.distance}",
                    "pool_rounds": args.pool, "w_copies": args.w_copies,
-                   "calls_per_step": (2 if args.separate_update else 1) + wl.gamma, "launch": launch,
-                   "window_update": "separate call" if args.separate_update else "fused into tabed_verify"},
+                   "calls_per_step": (2 if args.separate_update else 1) + wl.gamma * (2 if tree else 1), "launch": launch,
+                   "window_update": "separate call" if args.separate_update else "fused into tabed_verify",
+                   "tree_width": args.tree_width},
         "roofline": roofline,
         "cpu_baseline": None,
         "detail": {"kernels": kernels, "mean_tokens_per_round": emitted,

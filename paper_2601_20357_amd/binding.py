@@ -345,6 +345,48 @@ class RoundBuffers:
         self.n_valid = z((B,), torch.int32)
         self.verify_flags = z((B, g + 1), torch.uint8)
 
+    # ---- token tree: sibling candidates and the walk's extra outputs
+    def enable_tree(self, width: int):
+        import torch
+        c = self.cfg
+        S = width - 1
+        dev = self.weights.device
+        self.tree_width = width
+        self.sib_tokens = torch.zeros((c.B, c.gamma, S), dtype=torch.int32, device=dev)
+        self.sib_q = torch.zeros((c.B, c.gamma, S), dtype=torch.float32, device=dev)
+        self.sib_flags = torch.zeros((c.B, c.gamma, S), dtype=torch.uint8, device=dev)
+        self.leaf = torch.zeros((c.B,), dtype=torch.int32, device=dev)
+        self.n_out = torch.zeros((c.B,), dtype=torch.int32, device=dev)
+
+    def prepare_draft_siblings(self, rnd, pos, temperature, stream=None) -> "PreparedCall":
+        import torch
+        c = self.cfg
+        vp = C.c_void_p
+        args = [C.byref(c), vp(self.ws.data_ptr()), C.c_uint64(rnd), C.c_int32(pos), C.c_int32(self.tree_width),
+                vp(self.draft_logits.data_ptr()), vp(self.draft_tokens.data_ptr()), vp(self.weights.data_ptr()),
+                vp(_ptr(temperature, torch.float32, c.B, "temperature")), vp(None),
+                vp(self.sib_tokens.data_ptr()), vp(self.sib_q.data_ptr()), vp(self.sib_flags.data_ptr()),
+                vp(_stream(stream))]
+        return PreparedCall(load().tabed_draft_siblings, args, "tabed_draft_siblings", args[2])
+
+    def prepare_verify_tree(self, rnd, target_logits, leaf_logits, temperature, stream=None) -> "PreparedCall":
+        """The window update stays a separate call here (next_weights may not alias weights in tabed_verify_tree)."""
+        import torch
+        c = self.cfg
+        vp = C.c_void_p
+        S = self.tree_width - 1
+        args = [C.byref(c), vp(self.ws.data_ptr()), C.c_uint64(rnd), C.c_int32(self.tree_width),
+                vp(_ptr(target_logits, torch.float32, c.B * (c.gamma + 1) * c.V, "target_logits")),
+                vp(_ptr(leaf_logits, torch.float32, c.B * c.gamma * S * c.V, "leaf_logits")),
+                vp(self.draft_logits.data_ptr()), vp(self.draft_lse.data_ptr()), vp(self.draft_tokens.data_ptr()),
+                vp(self.draft_q.data_ptr()), vp(self.sib_tokens.data_ptr()), vp(self.sib_q.data_ptr()),
+                vp(self.weights.data_ptr()), vp(_ptr(temperature, torch.float32, c.B, "temperature")),
+                vp(None), vp(None), vp(None),
+                vp(self.accept_len.data_ptr()), vp(self.out_tokens.data_ptr()), vp(self.dev.data_ptr()),
+                vp(self.n_valid.data_ptr()), vp(self.verify_flags.data_ptr()), vp(self.leaf.data_ptr()),
+                vp(self.n_out.data_ptr()), vp(None), vp(None), vp(None), vp(None), vp(_stream(stream))]
+        return PreparedCall(load().tabed_verify_tree, args, "tabed_verify_tree", args[2])
+
     # ---- the same three calls with arguments converted once (hot loops)
     def prepare_update_weights(self, first: bool, rnd=0, stream=None) -> PreparedCall:
         import torch
