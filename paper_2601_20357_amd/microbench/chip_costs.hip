@@ -36,6 +36,42 @@ __global__ void k_read(const float4* __restrict__ a, float* out, size_t n) {
     if (acc == 12345.678f) out[0] = acc;           // never true: keeps the loads alive
 }
 
+// Every workgroup streams the same small buffer `passes` times: what the L2s (one per XCD) deliver to the compute
+// units once the buffer is resident in each of them.
+__global__ void k_read_resident(const float4* __restrict__ a, float* out, size_t n, int passes) {
+    float acc = 0.f;
+    for (int p = 0; p < passes; ++p) {
+        // rotate the starting point per workgroup so that the compute units do not walk the channels in step
+        size_t i = ((size_t)blockIdx.x * 977 + threadIdx.x) % n;
+        for (size_t k = 0; k < n / blockDim.x; ++k) {
+            const float4 v = a[i];
+            acc += v.x + v.y + v.z + v.w;
+            i += blockDim.x;
+            if (i >= n) i -= n;
+        }
+    }
+    if (acc == 12345.678f) out[0] = acc;
+}
+
+// Back-to-back matrix instructions on independent accumulators, one wave per SIMD: the rate the matrix cores
+// sustain when nothing else is in the way.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+__global__ __launch_bounds__(256) void k_mfma_peak(int iters, float* out) {
+    bf16x8_t a, b;
+    for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(threadIdx.x * 0.001f + i); b[i] = (__bf16)(i * 0.5f); }
+    f32x16_t acc[8];
+    for (int j = 0; j < 8; ++j)
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+    }
+    float t = 0.f;
+    for (int j = 0; j < 8; ++j) t += acc[j][0] + acc[j][5];
+    if (t == 1234.5f) out[0] = t;
+}
+
 // Hand-over variants: every workgroup writes 256 floats, then one thread bumps a counter.
 __global__ void k_handover_fence_all(int* counter, float* buf) {
     buf[blockIdx.x * 256 + threadIdx.x] = 1.f;
@@ -105,6 +141,20 @@ int main() {
         char nm[96];
         snprintf(nm, sizeof nm, "read %zu MiB, same buffer every launch", mb);
         printf("%-58s %9.2f   %7.2f TB/s\n", nm, us, (double)mb * 1048576.0 / us * 1e-6);
+    }
+    for (size_t mb : {2, 4}) {
+        const size_t n = mb * (1u << 20) / 16;
+        const int passes = 16, wgs = 2048;
+        const double us = time_us([&] { hipLaunchKernelGGL(k_read_resident, dim3(wgs), dim3(256), 0, 0, a, (float*)out, n, passes); }, 10);
+        char nm[96];
+        snprintf(nm, sizeof nm, "%d workgroups each read the same %zu MiB %d times", wgs, mb, passes);
+        printf("%-58s %9.2f   %7.2f TB/s out of the L2s\n", nm, us, (double)wgs * passes * mb * 1048576.0 / us * 1e-6);
+    }
+    {
+        const int iters = 20000;
+        const double us = time_us([&] { hipLaunchKernelGGL(k_mfma_peak, dim3(256), dim3(256), 0, 0, iters, (float*)out); }, 3);
+        printf("%-58s %9.2f   %7.1f TFLOP/s\n", "v_mfma_f32_32x32x16_bf16 back to back, 1 wave per SIMD", us,
+               256.0 * 4 * iters * 8 * 32768.0 / us * 1e-6);
     }
     int start = 0;
     double cold1 = 0, cold17 = 0;
