@@ -515,12 +515,12 @@ constexpr int kLBM = 256, kLBN = 256, kLBK = 32, kLRow = (kLBK + 8) * 2;   // LD
 constexpr int kLCh = kLBK / 8;                                              // 16-byte chunks per row of a k-block
 constexpr int kLargeStage = (kLBM + kLBN) * kLRow;                          // bytes per buffer (40960)
 
-// NW = waves per workgroup: 8 (each wave 128 rows x 64 vocabulary entries, two waves per SIMD) or 4 (each wave
-// 128 x 128, one wave per SIMD with the accumulators in the upper half of the register file).
+// Eight waves per workgroup, each 128 rows x 64 vocabulary entries, two waves per SIMD.  (Four waves of 128 x 128 with
+// register staging spill ~300 registers; four waves fed by global_load_lds measured no faster: the loop is bound by
+// how fast a workgroup pulls its operand tiles, 1 byte per 128 flop at this tile size, through L1 from L2.)
 constexpr int kLargeWaves = 8;
 
-template <int NW>
-__global__ __launch_bounds__(NW * 64) void k_lmhead_large(int M, int d, int V, int n, int NT, int mblocks,
+__global__ __launch_bounds__(kLargeWaves * 64) void k_lmhead_large(int M, int d, int V, int n, int NT, int mblocks,
                                                                 const uint16_t* __restrict__ W,
                                                                 const uint16_t* __restrict__ H,
                                                                 const float* __restrict__ temperature,
@@ -528,6 +528,7 @@ __global__ __launch_bounds__(NW * 64) void k_lmhead_large(int M, int d, int V, i
                                                                 float* __restrict__ ps) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     __shared__ float s_invt[kLBM];
+    constexpr int NW = kLargeWaves;
     constexpr int kLargeThreads = NW * 64;
     constexpr int kLWPieces = kLBN * kLCh / kLargeThreads, kLHPieces = kLBM * kLCh / kLargeThreads;
     static_assert(kLBN * kLCh % kLargeThreads == 0 && kLBM * kLCh % kLargeThreads == 0, "staging split");
@@ -780,11 +781,11 @@ hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& Lay, char* ws, cons
         static std::once_flag attr_once;                   // raise the dynamic-LDS limit once
         static hipError_t attr_rc = hipSuccess;
         const size_t lds = 2 * (size_t)kLargeStage;
-        if (raise_lds_limit(&k_lmhead_large<kLargeWaves>, lds, attr_once, attr_rc) != hipSuccess) return attr_rc;
+        if (raise_lds_limit(&k_lmhead_large, lds, attr_once, attr_rc) != hipSuccess) return attr_rc;
         const int mblocks = (M + kLBM - 1) / kLBM, nblocks = (c.V + kLBN - 1) / kLBN;
         const int nrounds = (nblocks + 7) / 8;             // vocabulary blocks are dealt to the 8 XCDs in rounds
         const dim3 grid(nrounds * mblocks * 8);
-        launch(&prof, k_lmhead_large<kLargeWaves>, grid, dim3(kLargeWaves * 64), lds, s, M, c.d, c.V, c.n, Lay.NT, mblocks,
+        launch(&prof, k_lmhead_large, grid, dim3(kLargeWaves * 64), lds, s, M, c.d, c.V, c.n, Lay.NT, mblocks,
                static_cast<const uint16_t*>(W), static_cast<const uint16_t*>(H), temperature, logits, pm, ps);
     } else {
         const dim3 grid((c.V + kBN - 1) / kBN, (M + kBM - 1) / kBM);
