@@ -29,7 +29,7 @@ def source_digest():
     """Short digest of the kernel sources: a traffic figure measured on other sources is not reported."""
     import hashlib
     h = hashlib.sha256()
-    for name in ("device_utils.h", "internal.h", "lmhead.hip", "vocab.hip", "api.hip"):
+    for name in ("device_utils.h", "internal.h", "lmhead.hip", "vocab.hip"):
         with open(os.path.join(ROOT, "paper_2601_20357_amd", "csrc", name), "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]
@@ -318,7 +318,13 @@ def main():
     else:
         dt = timed(args.steps)
     ms_per_step = dt / args.steps * 1e3
-    emitted = float(buf.n_out.float().mean().item()) if tree else float(buf.accept_len.float().mean().item()) + 1.0
+    # tokens emitted per round and sequence, averaged over one more (untimed) pass over the pool
+    emitted_sum = 0.0
+    for _ in range(args.pool):
+        step()
+        torch.cuda.synchronize()
+        emitted_sum += float(buf.n_out.float().mean().item()) if tree else float(buf.accept_len.float().mean().item()) + 1.0
+    emitted = emitted_sum / args.pool
 
     # ---- second, instrumented pass over the same steps: per-kernel HIP-event timing on the launch stream
     kernels = {}

@@ -16,6 +16,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "tabed_oracle.c")
+_SRC_BODY = os.path.join(_HERE, "tabed_body_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 FLAG_ACCEPT_MARGIN = 1
@@ -25,8 +26,9 @@ FLAG_DEGENERATE = 4
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (no fast-math: summation order is part of the definition)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"]
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_BODY))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", _LIB, _SRC, _SRC_BODY, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -272,3 +274,36 @@ def verify_tree(*, V, n, B, gamma, width, distance, seed, rnd, target_logits, le
                              _p(out["accept_len"]), _p(out["out_tokens"]), _p(out["dev"]), _p(out["n_valid"]),
                              _p(out["flags"]), _p(out["leaf"]), _p(out["n_out"]))
     return out
+
+
+# ---------------------------------------------------------------- draft-model body (Sec. 5.1 / Sec. 4.1)
+def body_step(*, layers, d, heads, d_ff, V, max_ctx, rope_theta, rms_eps, tokens, ctx_len, weights, kcache, vcache):
+    """One decode step of the draft model for M rows; appends to the caches in place, returns H [M,d] (bf16 bits).
+
+    weights: dict with embed [V,d] uint16, g_final [d] float32 and per-layer lists g_attn, wqkv, wo, g_mlp, wgu, wdown
+    (bf16 bit patterns as uint16, gains float32).  kcache, vcache: uint16 [layers,M,max_ctx,d]."""
+    M = len(tokens)
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    ctx_len = np.ascontiguousarray(ctx_len, dtype=np.int32)
+    assert kcache.dtype == np.uint16 and kcache.shape == (layers, M, max_ctx, d) and vcache.shape == kcache.shape
+    assert weights["embed"].dtype == np.uint16 and weights["embed"].shape == (V, d)
+
+    def ptrs(key, dtype, shape):
+        arrs = [np.ascontiguousarray(a, dtype=dtype) for a in weights[key]]
+        assert len(arrs) == layers and all(a.shape == shape for a in arrs), key
+        return arrs, (C.c_void_p * layers)(*[a.ctypes.data for a in arrs])
+
+    keep = []
+    plist = []
+    for key, dt, shape in (("g_attn", np.float32, (d,)), ("wqkv", np.uint16, (3 * d, d)), ("wo", np.uint16, (d, d)),
+                           ("g_mlp", np.float32, (d,)), ("wgu", np.uint16, (2 * d_ff, d)), ("wdown", np.uint16, (d, d_ff))):
+        arrs, arr_p = ptrs(key, dt, shape)
+        keep.append(arrs)
+        plist.append(arr_p)
+    g_final = np.ascontiguousarray(weights["g_final"], dtype=np.float32)
+    embed = np.ascontiguousarray(weights["embed"])
+    H = np.zeros((M, d), dtype=np.uint16)
+    lib().oracle_body_step(layers, d, heads, d_ff, V, max_ctx, C.c_double(rope_theta), C.c_double(rms_eps), M,
+                           _p(tokens), _p(ctx_len), _p(embed), plist[0], plist[1], plist[2], plist[3], plist[4], plist[5],
+                           _p(g_final), _p(kcache), _p(vcache), _p(H))
+    return H

@@ -166,3 +166,34 @@ def make_tree_leaves(wl: Workload, W: np.ndarray, H: np.ndarray, rnd: int, width
         noise = g.standard_normal(shape, dtype=np.float32)
         noise *= make_seq_sigma(wl)[:, None, None, None] if wl.target == "per_seq_sigma" else np.float32(wl.sigma)
     return np.ascontiguousarray(base[:, :, None, :] + noise, dtype=np.float32)
+
+
+# ------------------------------------------------------------------ draft-model body (random weights: latency study)
+@dataclass(frozen=True)
+class BodyConfig:
+    """Shape of the LLaMA-style draft model in front of the LM head (the paper's drafts are 68M / 160M LLaMA models;
+    their trained weights are not used here)."""
+    layers: int = 2
+    d: int = 768
+    heads: int = 12
+    d_ff: int = 3072
+    V: int = 32000
+    max_ctx: int = 1024
+    rope_theta: float = 10000.0
+    rms_eps: float = 1e-5
+
+
+BODY_68M = BodyConfig()
+
+
+def make_body_weights(bc: BodyConfig, seed: int = 0) -> dict:
+    """Random weights of the body: matrices ~ N(0, 0.02) as bf16 bit patterns, norm gains 1 + N(0, 0.1) in fp32."""
+    g = np.random.default_rng(7000 + seed)
+    mat = lambda *shape: bf16_bits(g.standard_normal(shape, dtype=np.float32) * np.float32(0.02))
+    gain = lambda: (1.0 + 0.1 * g.standard_normal(bc.d)).astype(np.float32)
+    return dict(
+        embed=bf16_bits(g.standard_normal((bc.V, bc.d), dtype=np.float32)),
+        g_attn=[gain() for _ in range(bc.layers)], wqkv=[mat(3 * bc.d, bc.d) for _ in range(bc.layers)],
+        wo=[mat(bc.d, bc.d) for _ in range(bc.layers)], g_mlp=[gain() for _ in range(bc.layers)],
+        wgu=[mat(2 * bc.d_ff, bc.d) for _ in range(bc.layers)], wdown=[mat(bc.d, bc.d_ff) for _ in range(bc.layers)],
+        g_final=gain())

@@ -423,6 +423,50 @@ def test_hip_graph_replay_matches_eager_bitwise(oracle):
         del scratch
 
 
+def test_soak_two_thousand_rounds_twice_bitwise(oracle):
+    """The cross-workgroup hand-overs (greedy arg-max merge, corrected-token sampler, fused window update) under
+    sustained load: 2000 serving-shape rounds with greedy and sampling rows, window state carried, run twice from
+    the same state -- every round's tokens, accept lengths, distances and weights must be bit-identical.  A stale
+    partial result read by a finishing workgroup would show up as a difference; the comparison names the first
+    round that differs."""
+    wl = synth.scaled(SERVING, cfg_id=98)
+    rounds, pool = 2000, 6
+    W = synth.make_lm_head(wl)
+    W_t = harness.to_dev_store(W, wl.w_dtype)
+    temp_t = torch.from_numpy(synth.make_temperature(wl, "mixed07")).to(DEV)
+    inputs = [synth.make_round(wl, W, r) for r in range(pool)]
+    H_t = [[harness.to_dev_store(H[pos], wl.w_dtype) for pos in range(wl.gamma)] for H, _ in inputs]
+    T_t = [torch.from_numpy(t).to(DEV) for _, t in inputs]
+    cfg = harness.cfg_of(wl, seed=5)
+    logs = []
+    for run in range(2):
+        buf = binding.RoundBuffers(cfg, DEV)
+        log_tok = torch.zeros((rounds, wl.B, wl.gamma + 1), dtype=torch.int32, device=DEV)
+        log_dtok = torch.zeros((rounds, wl.B, wl.gamma), dtype=torch.int32, device=DEV)
+        log_dev = torch.zeros((rounds, wl.B, wl.gamma, wl.n), dtype=torch.float32, device=DEV)
+        log_w = torch.zeros((rounds, wl.B, wl.n), dtype=torch.float32, device=DEV)
+        buf.update_weights(True)
+        for r in range(rounds):
+            log_w[r].copy_(buf.weights)
+            for pos in range(wl.gamma):
+                buf.draft_step(r, pos, W_t, H_t[r % pool][pos], temp_t)
+            buf.verify(r, T_t[r % pool], temp_t, fused_update=True)
+            log_tok[r].copy_(buf.out_tokens)
+            log_dtok[r].copy_(buf.draft_tokens)
+            log_dev[r].copy_(buf.dev)
+            if r % 500 == 499:
+                torch.cuda.synchronize()
+                _say(f"  soak run {run}: {r + 1} rounds")
+        torch.cuda.synchronize()
+        logs.append((log_tok, log_dtok, log_dev, log_w))
+    for name, a, b in zip(("out_tokens", "draft_tokens", "dev", "weights"), logs[0], logs[1]):
+        same = (a.view(torch.int32) == b.view(torch.int32)).flatten(1).all(dim=1)
+        if not bool(same.all()):
+            first = int((~same).nonzero()[0])
+            raise AssertionError(f"{name} differs between the two runs from round {first} on")
+    assert int((logs[0][0][:, :, 0] >= 0).sum()) == rounds * wl.B          # every round emitted a token per sequence
+
+
 def test_seeded_sweep_of_small_shapes(oracle):
     """Twenty seeded random configurations (vocabulary, hidden size, drafts, sequences, block length, window,
     storage type, temperature mix, policy, distance, fused or separate window update)."""

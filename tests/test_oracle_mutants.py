@@ -11,7 +11,9 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "tabed_oracle.c")
+SRC_BODY = os.path.join(ROOT, "oracle", "tabed_body_oracle.c")
 PIN_FILES = ["tests/test_oracle_blocks.py", "tests/test_oracle_sd.py", "tests/test_oracle_tree.py"]
+BODY_PIN_FILES = ["tests/test_oracle_body.py"]
 
 # (name, text in the oracle, replacement, replace every occurrence?)
 MUTANTS = [
@@ -61,24 +63,43 @@ MUTANTS = [
 ]
 
 
+# mistakes planted in the draft-body oracle (tabed_body_oracle.c), caught by its library-operator pin
+BODY_MUTANTS = [
+    ("body: rotary pairs (i, i+1) instead of (i, i + head_dim/2)", "double q0 = q[i], q1 = q[i + hd / 2], k0 = k[i], k1 = k[i + hd / 2];",
+     "double q0 = q[i], q1 = q[(i + 1) % hd], k0 = k[i], k1 = k[i + hd / 2];", False),
+    ("body: scores not scaled by 1/sqrt(head_dim)", "sc[t] = acc / sqrt((double)hd);", "sc[t] = acc;", False),
+    ("body: gate and up halves swapped", "act[f] = round_bf16(gu[f] / (1.0 + exp(-gu[f])) * gu[d_ff + f]);",
+     "act[f] = round_bf16(gu[d_ff + f] / (1.0 + exp(-gu[d_ff + f])) * gu[f]);", False),
+    ("body: the new key is not part of its own attention", "for (int t = 0; t <= pos; ++t) { sc[t] = exp(sc[t] - mx); Z += sc[t]; }",
+     "sc[pos] = -INFINITY; for (int t = 0; t <= pos; ++t) { sc[t] = exp(sc[t] - mx); Z += sc[t]; }", False),
+    ("body: rotation angle with the wrong sign of the exponent", "pow(rope_theta, -2.0 * i / hd)", "pow(rope_theta, 2.0 * i / hd)", False),
+    ("body: second norm's gain taken from the first", "rmsnorm_bf16(x, g_mlp[l], d, rms_eps, h);", "rmsnorm_bf16(x, g_attn[l], d, rms_eps, h);", False),
+    ("body: residual of the MLP dropped", "linear(wdown[l], d, d_ff, act, proj);\n            for (int i = 0; i < d; ++i) x[i] = round_f32(x[i] + proj[i]);",
+     "linear(wdown[l], d, d_ff, act, proj);\n            for (int i = 0; i < d; ++i) x[i] = round_f32(proj[i]);", False),
+]
+
+
 def _run_mutant(args):
     name, old, new, every, tmp = args
-    src = open(SRC).read()
+    body = name.startswith("body:")
+    path = SRC_BODY if body else SRC
+    src = open(path).read()
     assert old in src, f"mutant '{name}' no longer matches the oracle's text"
     mutated = src.replace(old, new) if every else src.replace(old, new, 1)
     tag = "".join(ch if ch.isalnum() else "_" for ch in name)
     c_path, so_path = os.path.join(tmp, tag + ".c"), os.path.join(tmp, tag + ".so")
     open(c_path, "w").write(mutated)
-    subprocess.run(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", so_path, c_path, "-lm"], check=True)
+    sources = [SRC, c_path] if body else [c_path, SRC_BODY]
+    subprocess.run(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", so_path, *sources, "-lm"], check=True)
     env = dict(os.environ, TABED_ORACLE_LIB=so_path, OMP_NUM_THREADS="2")
-    files = [f for f in PIN_FILES if os.path.exists(os.path.join(ROOT, f))]
+    files = [f for f in (BODY_PIN_FILES if body else PIN_FILES) if os.path.exists(os.path.join(ROOT, f))]
     res = subprocess.run([sys.executable, "-m", "pytest", *files, "-x", "-q", "-p", "no:cacheprovider"],
                          cwd=ROOT, env=env, capture_output=True, text=True)
     return name, res.returncode
 
 
 def test_every_planted_mistake_is_caught_by_a_pin(tmp_path):
-    jobs = [(n, o, r, e, str(tmp_path)) for n, o, r, e in MUTANTS]
+    jobs = [(n, o, r, e, str(tmp_path)) for n, o, r, e in MUTANTS + BODY_MUTANTS]
     with ThreadPoolExecutor(max_workers=4) as pool:
         results = list(pool.map(_run_mutant, jobs))
     missed = [name for name, rc in results if rc == 0]
@@ -88,9 +109,9 @@ def test_every_planted_mistake_is_caught_by_a_pin(tmp_path):
 def test_the_unmodified_copy_passes(tmp_path):
     """The harness itself: an unmodified copy of the oracle, loaded the same way, passes the same pins."""
     so = str(tmp_path / "copy.so")
-    subprocess.run(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", so, SRC, "-lm"], check=True)
+    subprocess.run(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", so, SRC, SRC_BODY, "-lm"], check=True)
     env = dict(os.environ, TABED_ORACLE_LIB=so, OMP_NUM_THREADS="2")
-    files = [f for f in PIN_FILES if os.path.exists(os.path.join(ROOT, f))]
+    files = [f for f in PIN_FILES + BODY_PIN_FILES if os.path.exists(os.path.join(ROOT, f))]
     res = subprocess.run([sys.executable, "-m", "pytest", *files, "-x", "-q", "-p", "no:cacheprovider"],
                          cwd=ROOT, env=env, capture_output=True, text=True)
     assert res.returncode == 0, res.stdout[-2000:]
