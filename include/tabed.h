@@ -260,6 +260,64 @@ int tabed_update_weights(const tabed_cfg* cfg, void* ws, uint64_t round, const f
                          void* stream);
 
 /*
+ * Draft-model body in front of the LM head (Sec. 5.1, "Ensemble learning via Batched Inference": the m drafting
+ * methods share the parameters of the draft model and run as one batch; Sec. 4.1, "Target and Draft Models":
+ * LLaMA-style drafts of 68M / 160M parameters).  One decode step for `rows` = n * B rows, each with its own
+ * context: token embedding, then per layer RMSNorm, q/k/v projection, rotary position embedding (pairs
+ * (i, i + head_dim/2)), attention over the row's own key / value cache, output projection, RMSNorm, SwiGLU MLP;
+ * final RMSNorm.  The result H [rows,d] is what tabed_draft_step takes.  Weights, caches and every activation
+ * that feeds a projection are bf16; the residual stream and the projections' results are fp32.  No trained
+ * weights exist here: the body is exercised with random weights (parity with the oracle, and latency).
+ *
+ *   cfg, weights   HOST structs; the pointers inside `weights` are device pointers
+ *   rows           <= 65535; row r = b * n + j as everywhere
+ *   token_src, token_stride, rows_per_token: row r is fed token_src[(r / rows_per_token) * token_stride]
+ *                  (in-block position i > 0: token_src = draft_tokens + i - 1, stride gamma, rows_per_token n;
+ *                  a token outside [0,V) is clamped)
+ *   ctx_len        [rows] int32 in/out  tokens already in the row's cache = position of the token fed now;
+ *                  incremented by the call; must stay below cfg->max_ctx
+ *   kcache, vcache [layers,rows,max_ctx,d] bf16 in/out  entry ctx_len[r] of every row and layer is written
+ *   H              [rows,d] bf16 out
+ * `ws` is scratch of tabed_body_workspace_bytes(cfg, rows) bytes prepared once by tabed_body_workspace_init.
+ */
+#define TABED_BODY_MAX_LAYERS 16
+typedef struct tabed_body_cfg {
+    int32_t layers;   /* 1..TABED_BODY_MAX_LAYERS                                   */
+    int32_t d;        /* hidden size, multiple of 8                                 */
+    int32_t heads;    /* d / heads = head_dim, 8..128 and a multiple of 8           */
+    int32_t d_ff;     /* MLP width, multiple of 8                                   */
+    int32_t V;        /* vocabulary of the embedding table                          */
+    int32_t max_ctx;  /* cache length per row, 1..8192                              */
+    float rope_theta; /* rotary base (10000)                                        */
+    float rms_eps;    /* RMSNorm epsilon                                            */
+} tabed_body_cfg;
+
+typedef struct tabed_body_weights {
+    const void* embed;                          /* [V,d] bf16                        */
+    const float* g_final;                       /* [d]                               */
+    const float* g_attn[TABED_BODY_MAX_LAYERS]; /* [d]                               */
+    const void* wqkv[TABED_BODY_MAX_LAYERS];    /* [3d,d] bf16: q rows, k rows, v rows */
+    const void* wo[TABED_BODY_MAX_LAYERS];      /* [d,d] bf16                        */
+    const float* g_mlp[TABED_BODY_MAX_LAYERS];  /* [d]                               */
+    const void* wgu[TABED_BODY_MAX_LAYERS];     /* [2*d_ff,d] bf16: gate rows, up rows */
+    const void* wdown[TABED_BODY_MAX_LAYERS];   /* [d,d_ff] bf16                     */
+} tabed_body_weights;
+
+size_t tabed_body_workspace_bytes(const tabed_body_cfg* cfg, int32_t rows);   /* 0 if cfg is invalid */
+int tabed_body_workspace_init(const tabed_body_cfg* cfg, int32_t rows, void* ws, void* stream);
+int tabed_draft_body_step(const tabed_body_cfg* cfg, const tabed_body_weights* weights, void* ws, int32_t rows,
+                          const int32_t* token_src, int32_t token_stride, int32_t rows_per_token,
+                          int32_t* ctx_len, void* kcache, void* vcache, void* H, void* stream);
+/*
+ * After verification: the caches keep the fed tokens that were kept.  A round fed the round's first token and the
+ * drafted tokens y_0 .. y_{gamma-2}; with k accepted, min(k + 1, gamma) of them stay:
+ * ctx_len[r] = ctx_base[r] + min(accept_len[r / rows_per_seq] + 1, gamma).  (With k = gamma the last drafted
+ * token has not been fed yet; the caller feeds it with one more tabed_draft_body_step.)
+ */
+int tabed_draft_body_rollback(int32_t rows, int32_t rows_per_seq, int32_t gamma, const int32_t* ctx_base,
+                              const int32_t* accept_len, int32_t* ctx_len, void* stream);
+
+/*
  * The uniforms the two calls above would draw: out[b,pos,word] for b < B,
  * pos <= gamma, word in {0,1}.  out is [B,gamma+1,2] fp32.
  */
@@ -279,8 +337,9 @@ int tabed_philox_uniforms(const tabed_cfg* cfg, uint64_t round, float* out, void
 #define TABED_K_WEIGHTS 4 /* window + weights                   */
 #define TABED_K_DIST 5    /* second-pass distances (total variation, hard labels, grid mixtures) */
 #define TABED_K_TREE 6    /* token tree: sibling 1's test (the later tree passes are not timed) */
-#define TABED_K_NULL 7    /* empty kernel, see tabed_prof_null  */
-#define TABED_K_COUNT 8
+#define TABED_K_BODY 7    /* draft-model body: every kernel of tabed_draft_body_step */
+#define TABED_K_NULL 8    /* empty kernel, see tabed_prof_null  */
+#define TABED_K_COUNT 9
 int tabed_prof_enable(int on);
 int tabed_prof_read(int id, double* total_ms, int64_t* launches);
 int tabed_prof_reset(void);

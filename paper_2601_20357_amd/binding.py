@@ -15,11 +15,13 @@ LIB_PATH = os.path.join(_HERE, "libtabed.so")
 EXPORTS = [
     "tabed_workspace_bytes", "tabed_workspace_init", "tabed_strerror", "tabed_last_hip_error", "tabed_dev_width",
     "tabed_draft_step", "tabed_draft_step_static", "tabed_verify", "tabed_draft_siblings", "tabed_verify_tree", "tabed_update_weights", "tabed_philox_uniforms",
+    "tabed_body_workspace_bytes", "tabed_body_workspace_init", "tabed_draft_body_step", "tabed_draft_body_rollback",
     "tabed_prof_enable", "tabed_prof_read", "tabed_prof_reset", "tabed_kernel_name", "tabed_prof_null",
 ]
 
 FLAG_ACCEPT_MARGIN, FLAG_SAMPLE_MARGIN, FLAG_DEGENERATE = 1, 2, 4
-K_LMHEAD, K_SAMPLE, K_STATS, K_RESID, K_WEIGHTS, K_DIST, K_TREE, K_NULL, K_COUNT = 0, 1, 2, 3, 4, 5, 6, 7, 8
+K_LMHEAD, K_SAMPLE, K_STATS, K_RESID, K_WEIGHTS, K_DIST, K_TREE, K_BODY, K_NULL, K_COUNT = 0, 1, 2, 3, 4, 5, 6, 7, 8, 9
+BODY_MAX_LAYERS = 16
 
 
 class TabedCfg(C.Structure):
@@ -27,6 +29,18 @@ class TabedCfg(C.Structure):
     _fields_ = [("V", C.c_int32), ("d", C.c_int32), ("n", C.c_int32), ("B", C.c_int32),
                 ("gamma", C.c_int32), ("h", C.c_int32), ("w_dtype", C.c_int32), ("distance", C.c_int32),
                 ("policy", C.c_int32), ("tau_w", C.c_float), ("eps", C.c_float), ("seed", C.c_uint64)]
+
+
+class TabedBodyCfg(C.Structure):
+    """Mirror of `tabed_body_cfg`."""
+    _fields_ = [("layers", C.c_int32), ("d", C.c_int32), ("heads", C.c_int32), ("d_ff", C.c_int32), ("V", C.c_int32),
+                ("max_ctx", C.c_int32), ("rope_theta", C.c_float), ("rms_eps", C.c_float)]
+
+
+class TabedBodyWeights(C.Structure):
+    """Mirror of `tabed_body_weights` (device pointers)."""
+    _fields_ = [("embed", C.c_void_p), ("g_final", C.c_void_p)] + [
+        (name, C.c_void_p * BODY_MAX_LAYERS) for name in ("g_attn", "wqkv", "wo", "g_mlp", "wgu", "wdown")]
 
 
 class TabedError(RuntimeError):
@@ -70,6 +84,15 @@ def load():
     lib.tabed_update_weights.argtypes = [cfgp, vp, u64] + [vp] * 7
     lib.tabed_philox_uniforms.restype = C.c_int
     lib.tabed_philox_uniforms.argtypes = [cfgp, u64, vp, vp]
+    bcfgp = C.POINTER(TabedBodyCfg)
+    lib.tabed_body_workspace_bytes.restype = C.c_size_t
+    lib.tabed_body_workspace_bytes.argtypes = [bcfgp, i32]
+    lib.tabed_body_workspace_init.restype = C.c_int
+    lib.tabed_body_workspace_init.argtypes = [bcfgp, i32, vp, vp]
+    lib.tabed_draft_body_step.restype = C.c_int
+    lib.tabed_draft_body_step.argtypes = [bcfgp, C.POINTER(TabedBodyWeights), vp, i32, vp, i32, i32] + [vp] * 5
+    lib.tabed_draft_body_rollback.restype = C.c_int
+    lib.tabed_draft_body_rollback.argtypes = [i32, i32, i32, vp, vp, vp, vp]
     lib.tabed_prof_enable.restype = C.c_int
     lib.tabed_prof_enable.argtypes = [C.c_int]
     lib.tabed_prof_read.restype = C.c_int
@@ -269,6 +292,92 @@ def tabed_update_weights(cfg, ws, rnd, dev, n_valid, ring, ring_head, ring_count
         _ptr(ring_count, torch.int32, B, "ring_count"), _ptr(weights, torch.float32, B * n, "weights"),
         _stream(stream))
     _check(rc, "tabed_update_weights")
+
+
+def make_body_cfg(*, layers, d, heads, d_ff, V, max_ctx, rope_theta=1e4, rms_eps=1e-5) -> TabedBodyCfg:
+    return TabedBodyCfg(layers, d, heads, d_ff, V, max_ctx, rope_theta, rms_eps)
+
+
+def make_body_weights(bcfg: TabedBodyCfg, tensors: dict) -> TabedBodyWeights:
+    """Pointer table over device tensors: embed [V,d] and the per-layer lists wqkv [3d,d], wo [d,d], wgu [2 d_ff,d],
+    wdown [d,d_ff] as bf16 (or their bit patterns as int16 / uint16), gains g_attn, g_mlp (lists) and g_final as fp32.
+    The caller keeps `tensors` alive while the table is in use."""
+    import torch
+    two_byte = (torch.bfloat16, torch.int16, torch.uint16)
+    d, ff, L = bcfg.d, bcfg.d_ff, bcfg.layers
+
+    def mat(t, numel, name):
+        if t.dtype not in two_byte:
+            raise TabedError(f"{name} must hold bf16 values, got {t.dtype}")
+        return _ptr(t, None, numel, name)
+
+    w = TabedBodyWeights()
+    w.embed = mat(tensors["embed"], bcfg.V * d, "embed")
+    w.g_final = _ptr(tensors["g_final"], torch.float32, d, "g_final")
+    for key, numel in (("wqkv", 3 * d * d), ("wo", d * d), ("wgu", 2 * ff * d), ("wdown", d * ff)):
+        if len(tensors[key]) != L:
+            raise TabedError(f"{key} must list {L} layers")
+        for l in range(L):
+            getattr(w, key)[l] = mat(tensors[key][l], numel, f"{key}[{l}]")
+    for key in ("g_attn", "g_mlp"):
+        if len(tensors[key]) != L:
+            raise TabedError(f"{key} must list {L} layers")
+        for l in range(L):
+            getattr(w, key)[l] = _ptr(tensors[key][l], torch.float32, d, f"{key}[{l}]")
+    return w
+
+
+def tabed_body_workspace_bytes(bcfg: TabedBodyCfg, rows: int) -> int:
+    return int(load().tabed_body_workspace_bytes(C.byref(bcfg), rows))
+
+
+def tabed_body_workspace_init(bcfg, rows, ws, stream=None):
+    import torch
+    need = tabed_body_workspace_bytes(bcfg, rows)
+    if need == 0:
+        raise TabedError("tabed_body_workspace_init: invalid configuration")
+    if ws.numel() * ws.element_size() < need:
+        raise TabedError(f"body workspace holds {ws.numel() * ws.element_size()} bytes, {need} needed")
+    _check(load().tabed_body_workspace_init(C.byref(bcfg), rows, _ptr(ws, torch.uint8, name="ws"), _stream(stream)),
+           "tabed_body_workspace_init")
+
+
+def tabed_draft_body_step(bcfg, weights, ws, rows, token_src, token_stride, rows_per_token, ctx_len, kcache, vcache, H,
+                          stream=None):
+    """token_src: int32 tensor, or a (tensor, element offset) pair for a view into draft_tokens."""
+    import torch
+    if isinstance(token_src, tuple):
+        base, off = token_src
+        need = off + ((rows - 1) // rows_per_token) * token_stride + 1
+        if base.dtype != torch.int32 or not base.is_cuda or not base.is_contiguous() or base.numel() < need or off < 0:
+            raise TabedError("token_src must be a contiguous int32 GPU tensor covering every token read")
+        tok_ptr = base.data_ptr() + 4 * off
+    else:
+        need = ((rows - 1) // rows_per_token) * token_stride + 1
+        if token_src.numel() < need:
+            raise TabedError(f"token_src must hold {need} elements, got {token_src.numel()}")
+        tok_ptr = _ptr(token_src, torch.int32, None, "token_src")
+    if ws.numel() * ws.element_size() < tabed_body_workspace_bytes(bcfg, rows):
+        raise TabedError("body workspace too small")
+    two_byte = (torch.bfloat16, torch.int16, torch.uint16)
+    for t, name in ((kcache, "kcache"), (vcache, "vcache"), (H, "H")):
+        if t.dtype not in two_byte:
+            raise TabedError(f"{name} must hold bf16 values, got {t.dtype}")
+    cache_numel = bcfg.layers * rows * bcfg.max_ctx * bcfg.d
+    rc = load().tabed_draft_body_step(
+        C.byref(bcfg), C.byref(weights), _ptr(ws, torch.uint8, name="ws"), rows, tok_ptr, token_stride, rows_per_token,
+        _ptr(ctx_len, torch.int32, rows, "ctx_len"), _ptr(kcache, None, cache_numel, "kcache"),
+        _ptr(vcache, None, cache_numel, "vcache"), _ptr(H, None, rows * bcfg.d, "H"), _stream(stream))
+    _check(rc, "tabed_draft_body_step")
+
+
+def tabed_draft_body_rollback(rows, rows_per_seq, gamma, ctx_base, accept_len, ctx_len, stream=None):
+    import torch
+    nseq = (rows + rows_per_seq - 1) // rows_per_seq
+    rc = load().tabed_draft_body_rollback(
+        rows, rows_per_seq, gamma, _ptr(ctx_base, torch.int32, rows, "ctx_base"),
+        _ptr(accept_len, torch.int32, nseq, "accept_len"), _ptr(ctx_len, torch.int32, rows, "ctx_len"), _stream(stream))
+    _check(rc, "tabed_draft_body_rollback")
 
 
 def tabed_philox_uniforms(cfg, rnd, out, stream=None):

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtabed.so")
-SOURCES = ["api.hip", "lmhead.hip", "vocab.hip"]
+SOURCES = ["api.hip", "lmhead.hip", "vocab.hip", "body.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # keep the compiler from forming packed-fp32 instructions

@@ -292,6 +292,53 @@ int tabed_update_weights(const tabed_cfg* cfg, void* ws, uint64_t round, const f
     return e == hipSuccess ? TABED_OK : fail_hip(e);
 }
 
+size_t tabed_body_workspace_bytes(const tabed_body_cfg* cfg, int32_t rows) {
+    if (validate_body_cfg(cfg, rows) != TABED_OK) return 0;
+    return body_layout(*cfg, rows).total;
+}
+
+int tabed_body_workspace_init(const tabed_body_cfg* cfg, int32_t rows, void* ws, void* stream) {
+    const int rc = validate_body_cfg(cfg, rows);
+    if (rc != TABED_OK) return rc;
+    if (ws == nullptr) return TABED_ENULL;
+    if (misaligned(ws)) return TABED_EALIGN;
+    const hipError_t e = launch_body_init(*cfg, rows, static_cast<char*>(ws), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? TABED_OK : fail_hip(e);
+}
+
+int tabed_draft_body_step(const tabed_body_cfg* cfg, const tabed_body_weights* weights, void* ws, int32_t rows,
+                          const int32_t* token_src, int32_t token_stride, int32_t rows_per_token, int32_t* ctx_len,
+                          void* kcache, void* vcache, void* H, void* stream) {
+    const int rc = validate_body_cfg(cfg, rows);
+    if (rc != TABED_OK) return rc;
+    if (!weights || !ws || !token_src || !ctx_len || !kcache || !vcache || !H) return TABED_ENULL;
+    if (rows_per_token < 1 || token_stride < 0) return TABED_ERANGE;
+    if (!weights->embed || !weights->g_final) return TABED_ENULL;
+    for (int l = 0; l < cfg->layers; ++l) {
+        if (!weights->g_attn[l] || !weights->wqkv[l] || !weights->wo[l] || !weights->g_mlp[l] || !weights->wgu[l] ||
+            !weights->wdown[l])
+            return TABED_ENULL;
+        if (misaligned(weights->wqkv[l]) || misaligned(weights->wo[l]) || misaligned(weights->wgu[l]) ||
+            misaligned(weights->wdown[l]))
+            return TABED_EALIGN;
+    }
+    if (misaligned(ws) || misaligned(kcache) || misaligned(vcache) || misaligned(H) || misaligned(weights->embed))
+        return TABED_EALIGN;
+    const hipError_t e = launch_body_step(*cfg, *weights, static_cast<char*>(ws), rows, token_src, token_stride, rows_per_token,
+                                          ctx_len, static_cast<uint16_t*>(kcache), static_cast<uint16_t*>(vcache),
+                                          static_cast<uint16_t*>(H), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? TABED_OK : fail_hip(e);
+}
+
+int tabed_draft_body_rollback(int32_t rows, int32_t rows_per_seq, int32_t gamma, const int32_t* ctx_base,
+                              const int32_t* accept_len, int32_t* ctx_len, void* stream) {
+    if (!ctx_base || !accept_len || !ctx_len) return TABED_ENULL;
+    if (rows < 1 || rows_per_seq < 1 || gamma < 1) return TABED_ERANGE;
+    const hipError_t e = launch_body_rollback(rows, rows_per_seq, gamma, ctx_base, accept_len, ctx_len,
+                                              static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? TABED_OK : fail_hip(e);
+}
+
 int tabed_philox_uniforms(const tabed_cfg* cfg, uint64_t round, float* out, void* stream) {
     const int rc = validate_cfg(cfg);
     if (rc != TABED_OK) return rc;
@@ -336,6 +383,7 @@ const char* tabed_kernel_name(int id) {
         case TABED_K_WEIGHTS: return "weights";
         case TABED_K_DIST: return "dist";
         case TABED_K_TREE: return "tree";
+        case TABED_K_BODY: return "body";
         case TABED_K_NULL: return "null";
         default: return "?";
     }

@@ -50,8 +50,10 @@ int validate_cfg(const tabed_cfg* c);
 // ---------------------------------------------------------------- launchers (each enqueues on `s`)
 hipError_t launch_ws_init(const tabed_cfg& c, const WsLayout& L, char* ws, hipStream_t s);
 
+// prof_id: the timing bucket of the launch (the draft body runs its projections through the same kernels).
 hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& L, char* ws, const void* W, const void* H,
-                         const float* temperature, float* logits /* slot pos: [M,V] */, hipStream_t s);
+                         const float* temperature, float* logits /* slot pos: [M,V] */, hipStream_t s,
+                         int prof_id = TABED_K_LMHEAD);
 
 hipError_t launch_sample(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round, int pos,
                          const float* logits /* slot pos */, const float* weights, const float* temperature,
@@ -88,6 +90,24 @@ hipError_t launch_weights(const tabed_cfg& c, uint64_t round, const float* dev, 
 hipError_t launch_null(hipStream_t s);
 
 hipError_t launch_philox(const tabed_cfg& c, uint64_t round, float* out, hipStream_t s);
+
+// ---------------------------------------------------------------- draft-model body
+struct BodyLayout {
+    size_t off_ones;   // float [rows]: the "temperature" the projection launches divide by
+    size_t off_x;      // float [rows,d] residual stream
+    size_t off_y;      // float [rows, max(3d, 2 d_ff)] result of the current projection
+    size_t off_hb;     // bf16 [rows, max(d, d_ff)] input of the next projection
+    size_t off_gemm;   // scratch of the projection launches (softmax partials nobody reads)
+    size_t total;
+};
+BodyLayout body_layout(const tabed_body_cfg& c, int rows);
+int validate_body_cfg(const tabed_body_cfg* c, int rows);
+hipError_t launch_body_init(const tabed_body_cfg& c, int rows, char* ws, hipStream_t s);
+hipError_t launch_body_step(const tabed_body_cfg& c, const tabed_body_weights& w, char* ws, int rows,
+                            const int32_t* token_src, int token_stride, int rows_per_token, int32_t* ctx_len,
+                            uint16_t* kcache, uint16_t* vcache, uint16_t* H, hipStream_t s);
+hipError_t launch_body_rollback(int rows, int rows_per_seq, int gamma, const int32_t* ctx_base, const int32_t* accept_len,
+                                int32_t* ctx_len, hipStream_t s);
 
 // ---------------------------------------------------------------- event timing
 // While timing is enabled a launch goes through hipExtLaunchKernelGGL, which attaches a start and a stop

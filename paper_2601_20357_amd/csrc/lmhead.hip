@@ -762,8 +762,8 @@ static hipError_t launch_skinny(const ProfScope* prof, const tabed_cfg& c, const
 }
 
 hipError_t launch_lmhead(const tabed_cfg& c, const WsLayout& Lay, char* ws, const void* W, const void* H,
-                         const float* temperature, float* logits, hipStream_t s) {
-    ProfScope prof(TABED_K_LMHEAD, s);
+                         const float* temperature, float* logits, hipStream_t s, int prof_id) {
+    ProfScope prof(prof_id, s);
     float* pm = reinterpret_cast<float*>(ws + Lay.off_pm);
     float* ps = reinterpret_cast<float*>(ws + Lay.off_ps);
     const int M = Lay.M;

@@ -95,7 +95,7 @@ def test_error_codes_are_returned_before_any_launch(lib):
     for code in (0, -1, -2, -3, -4, -5, -6):
         assert lib.tabed_strerror(code).decode() not in ("", "unknown error code")
     assert lib.tabed_strerror(-99).decode() == "unknown error code"
-    assert [binding.tabed_kernel_name(i) for i in range(binding.K_COUNT)] == ["lmhead", "sample", "stats", "resid", "weights", "dist", "tree", "null"]
+    assert [binding.tabed_kernel_name(i) for i in range(binding.K_COUNT)] == ["lmhead", "sample", "stats", "resid", "weights", "dist", "tree", "body", "null"]
 
 
 def test_binding_refuses_host_tensors(lib):
