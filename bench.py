@@ -80,6 +80,9 @@ def parse():
     ap.add_argument("--tree-width", type=int, default=1,
                     help="token tree of this width (2 or 3) instead of the chain: every draft step also draws the "
                          "siblings, tabed_verify_tree verifies; the window update is then a call of its own")
+    ap.add_argument("--draft-body", default="none", choices=["none", "68m", "160m"],
+                    help="run the draft model's body (random weights) in front of every LM-head call instead of "
+                         "feeding pre-generated hidden states; reports rounds/s of body + head + verify")
     ap.add_argument("--policy", type=int, default=0, help="weight policy (0 softmax of 1/e, 1 static, 2 two-draft grid, 3 random)")
     ap.add_argument("--distance", type=int, default=0, help="0 KL, 1 total variation")
     ap.add_argument("--drafts", type=int, default=0, help="override the workload's number of drafts n (2 for --policy 2)")
@@ -220,6 +223,26 @@ def main():
         Ls = gen_leaf_logits(wl, Ws, Hs, args.tree_width, device)
     upd_first = buf.prepare_update_weights(True)
     upd = buf.prepare_update_weights(False)
+    body = None
+    if args.draft_body != "none":
+        if tree or wl.w_dtype != 1:
+            sys.exit("bench.py: --draft-body needs a bf16 workload and --tree-width 1")
+        import numpy as np
+        bc = synth.scaled_body(synth.BODIES[args.draft_body], d=wl.d, V=wl.V)
+        bw = synth.make_body_weights(bc, 0)
+        as_dev = lambda a: torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(device)
+        tensors = {k: ([as_dev(a) for a in v] if isinstance(v, list) else as_dev(v)) for k, v in bw.items()}
+        bcfg = binding.make_body_cfg(layers=bc.layers, d=bc.d, heads=bc.heads, d_ff=bc.d_ff, V=bc.V, max_ctx=bc.max_ctx,
+                                     rope_theta=bc.rope_theta, rms_eps=bc.rms_eps)
+        body = binding.BodyBuffers(bcfg, wl.n * wl.B, tensors, device)
+        g = torch.Generator(device="cpu").manual_seed(11)
+        # contexts of a few hundred tokens (prompt, image or caption tokens, what was generated so far), different
+        # for every drafting method of a sequence; the caches hold unit-variance keys and values up to there
+        body.ctx_base.copy_(torch.randint(256, 768, (wl.n * wl.B,), generator=g, dtype=torch.int32))
+        body.ctx_len.copy_(body.ctx_base)
+        body.kcache.normal_()
+        body.vcache.normal_()
+        first_tokens = torch.randint(0, wl.V, (args.pool, wl.B), generator=g, dtype=torch.int32).to(device)
     def make_slots(per_step_rotation):
         out = []
         for r in range(args.pool):
@@ -228,13 +251,21 @@ def main():
                 # default: one W copy per round (a round's gamma calls find W where the previous call left it,
                 # as they would with a 68M-class draft body between them); per-step: every call a fresh copy
                 W = Ws[(r * wl.gamma + pos) % len(Ws)] if per_step_rotation else Ws[r % len(Ws)]
-                drafts.append(buf.prepare_draft_step(0, pos, W, Hs[r][pos], temp))
+                if body is not None:
+                    # position 0 is fed the round's first token, position i > 0 the token drafted at i - 1
+                    drafts.append(body.prepare_step(first_tokens[r], 0, 1, wl.n) if pos == 0 else
+                                  body.prepare_step(buf.draft_tokens, pos - 1, wl.gamma, wl.n))
+                drafts.append(buf.prepare_draft_step(0, pos, W, body.H if body is not None else Hs[r][pos], temp))
                 if tree:
                     drafts.append(buf.prepare_draft_siblings(0, pos, temp))
             ver = (buf.prepare_verify_tree(0, Ts[r], Ls[r], temp) if tree else
                    buf.prepare_verify(0, Ts[r], temp, fused_update=not args.separate_update))
             out.append((drafts, ver))
         return out
+
+    # after verification the caches keep the accepted prefix.  ctx_base stays what it was at the start of the run
+    # (a serving loop would move it on by the tokens emitted), so that every round works at the recipe's context length
+    rollback = body.prepare_rollback(wl.n, wl.gamma, buf.accept_len) if body is not None else None
 
     slots = make_slots(False)
 
@@ -253,6 +284,8 @@ def main():
             c()
         ver.set_round(s)
         ver()
+        if rollback is not None:
+            rollback()
         state["step"] = s + 1
 
     def timed(k):
@@ -268,7 +301,7 @@ def main():
     torch.cuda.synchronize()
 
     launch = args.launch
-    every = [upd, upd_first] + [c for drafts, ver in slots for c in drafts + [ver]]
+    every = [upd, upd_first] + [c for drafts, ver in slots for c in drafts + [ver]] + ([rollback] if rollback else [])
 
     def set_stream(handle):
         import ctypes as C
@@ -342,6 +375,9 @@ def main():
         "resid": n_sampling * (1 + wl.n) * wl.V * 4,                              # one target row + n draft rows
         "dist": wl.B * wl.gamma * (1 + wl.n) * wl.V * 4,
     }
+    body_weight_bytes = 0
+    if body is not None:                       # what a body step must stream: every layer's matrices once
+        body_weight_bytes = bc.layers * 2 * (3 * bc.d * bc.d + bc.d * bc.d + 3 * bc.d * bc.d_ff)
     lm_bytes = alg_bytes["lmhead"]
     lm_flops = 2.0 * M * wl.d * wl.V
     if not args.no_kernel_timing:
@@ -357,6 +393,11 @@ def main():
                 name = binding.tabed_kernel_name(kid)
                 us = ms / cnt * 1e3
                 kernels[name] = {"avg_us": us, "launches": cnt}
+                if name == "body":                 # all kernels of one tabed_draft_body_step together
+                    kernels[name].update(launches_per_step=cnt / (args.steps * wl.gamma),
+                                         per_step_us=ms * 1e3 / (args.steps * wl.gamma),
+                                         weight_bytes_per_step=body_weight_bytes,
+                                         weights_gbs=body_weight_bytes / (ms * 1e-3 / (args.steps * wl.gamma)) / 1e9)
                 if name in alg_bytes:
                     gbs = alg_bytes[name] / (us * 1e-6) / 1e9
                     kernels[name].update(algorithmic_bytes=alg_bytes[name], achieved_gbs=gbs,
@@ -399,7 +440,7 @@ def main():
         + (alg_bytes["dist"] if (args.distance != 0 or args.policy == 2) else 0)
     out = {
         "metric": ("ensemble-draft+verify steps/sec at V=32k,n=4,B=16; HBM GB/s & MFMA % of peak"
-                   if wl.name == "serving" and not tree else "ensemble-draft+verify steps/sec"),
+                   if wl.name == "serving" and not tree and body is None else "ensemble-draft+verify steps/sec"),
         "value": args.steps / dt, "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -407,9 +448,10 @@ def main():
         "config": {"workload": f"{wl.name}: V={wl.V} d={wl.d} n={wl.n} B={wl.B} gamma={wl.gamma} h={wl.h} "
                                f"temperature={wl.temperature} policy={args.policy} distance={args.distance}",
                    "pool_rounds": args.pool, "w_copies": args.w_copies,
-                   "calls_per_step": (2 if args.separate_update else 1) + wl.gamma * (2 if tree else 1), "launch": launch,
+                   "calls_per_step": (2 if args.separate_update else 1) + wl.gamma * (2 if tree or body is not None else 1)
+                                     + (1 if body is not None else 0), "launch": launch,
                    "window_update": "separate call" if args.separate_update else "fused into tabed_verify",
-                   "tree_width": args.tree_width},
+                   "tree_width": args.tree_width, "draft_body": args.draft_body},
         "roofline": roofline,
         "cpu_baseline": None,
         "detail": {"kernels": kernels, "mean_tokens_per_round": emitted,

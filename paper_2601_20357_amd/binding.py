@@ -421,12 +421,53 @@ class PreparedCall:
 
     def set_round(self, rnd: int):
         """Change the SD round number (the Philox counter) the next call passes."""
-        self.round_arg.value = rnd
+        if self.round_arg is not None:
+            self.round_arg.value = rnd
 
     def __call__(self):
         rc = self.fn(*self.args)
         if rc != 0:
             _check(rc, self.what)
+
+
+class BodyBuffers:
+    """Device buffers of the draft-model body for `rows` rows (allocation only; no arithmetic here): weight table,
+    scratch, key / value caches, positions and the hidden states H the LM head reads."""
+
+    def __init__(self, bcfg: TabedBodyCfg, rows: int, tensors: dict, device="cuda:0"):
+        import torch
+        self.cfg, self.rows, self.tensors = bcfg, rows, tensors
+        self.table = make_body_weights(bcfg, tensors)
+        need = tabed_body_workspace_bytes(bcfg, rows)
+        if need == 0:
+            raise TabedError("invalid body configuration")
+        self.ws = torch.empty(need, dtype=torch.uint8, device=device)
+        tabed_body_workspace_init(bcfg, rows, self.ws)
+        self.kcache = torch.zeros((bcfg.layers, rows, bcfg.max_ctx, bcfg.d), dtype=torch.bfloat16, device=device)
+        self.vcache = torch.zeros_like(self.kcache)
+        self.ctx_len = torch.zeros(rows, dtype=torch.int32, device=device)
+        self.ctx_base = torch.zeros(rows, dtype=torch.int32, device=device)
+        self.H = torch.zeros((rows, bcfg.d), dtype=torch.bfloat16, device=device)
+
+    def prepare_step(self, token_src, token_offset, token_stride, rows_per_token, stream=None) -> PreparedCall:
+        import torch
+        need = token_offset + ((self.rows - 1) // rows_per_token) * token_stride + 1
+        if token_src.dtype != torch.int32 or not token_src.is_cuda or not token_src.is_contiguous() or token_src.numel() < need:
+            raise TabedError("token_src must be a contiguous int32 GPU tensor covering every token read")
+        vp = C.c_void_p
+        args = [C.byref(self.cfg), C.byref(self.table), vp(self.ws.data_ptr()), C.c_int32(self.rows),
+                vp(token_src.data_ptr() + 4 * token_offset), C.c_int32(token_stride), C.c_int32(rows_per_token),
+                vp(self.ctx_len.data_ptr()), vp(self.kcache.data_ptr()), vp(self.vcache.data_ptr()), vp(self.H.data_ptr()),
+                vp(_stream(stream))]
+        return PreparedCall(load().tabed_draft_body_step, args, "tabed_draft_body_step")
+
+    def prepare_rollback(self, rows_per_seq, gamma, accept_len, stream=None) -> PreparedCall:
+        import torch
+        vp = C.c_void_p
+        nseq = (self.rows + rows_per_seq - 1) // rows_per_seq
+        args = [C.c_int32(self.rows), C.c_int32(rows_per_seq), C.c_int32(gamma), vp(self.ctx_base.data_ptr()),
+                vp(_ptr(accept_len, torch.int32, nseq, "accept_len")), vp(self.ctx_len.data_ptr()), vp(_stream(stream))]
+        return PreparedCall(load().tabed_draft_body_rollback, args, "tabed_draft_body_rollback")
 
 
 class RoundBuffers:

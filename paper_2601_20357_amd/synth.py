@@ -183,7 +183,14 @@ class BodyConfig:
     rms_eps: float = 1e-5
 
 
-BODY_68M = BodyConfig()
+BODY_68M = BodyConfig()                  # the 68M-class draft: 2 layers of width 768 (Sec. 4.1, Target and Draft Models)
+BODY_160M = BodyConfig(layers=12)        # the 160M-class draft: 12 layers of the same width
+BODIES = {"68m": BODY_68M, "160m": BODY_160M}
+
+
+def scaled_body(bc: BodyConfig, d: int, V: int) -> BodyConfig:
+    """The same depth at another hidden size and vocabulary: heads of 64, an MLP four times as wide."""
+    return replace(bc, d=d, heads=d // 64, d_ff=4 * d, V=V)
 
 
 def make_body_weights(bc: BodyConfig, seed: int = 0) -> dict:
