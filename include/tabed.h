@@ -279,12 +279,14 @@ int tabed_update_weights(const tabed_cfg* cfg, void* ws, uint64_t round, const f
  *   kcache, vcache [layers,rows,max_ctx,d] bf16 in/out  entry ctx_len[r] of every row and layer is written
  *   H              [rows,d] bf16 out
  * `ws` is scratch of tabed_body_workspace_bytes(cfg, rows) bytes prepared once by tabed_body_workspace_init.
+ * Every pointer is 16-byte aligned (TABED_EALIGN otherwise); a ctx_len entry outside [0, max_ctx) is clamped into
+ * the range, so nothing is written outside a row's cache.
  */
 #define TABED_BODY_MAX_LAYERS 16
 typedef struct tabed_body_cfg {
     int32_t layers;   /* 1..TABED_BODY_MAX_LAYERS                                   */
-    int32_t d;        /* hidden size, multiple of 8                                 */
-    int32_t heads;    /* d / heads = head_dim, 8..128 and a multiple of 8           */
+    int32_t d;        /* hidden size, multiple of 8, at most 8192                   */
+    int32_t heads;    /* d / heads = head_dim, one of 8, 16, 32, 64, 128            */
     int32_t d_ff;     /* MLP width, multiple of 8                                   */
     int32_t V;        /* vocabulary of the embedding table                          */
     int32_t max_ctx;  /* cache length per row, 1..8192                              */

@@ -319,10 +319,11 @@ int tabed_draft_body_step(const tabed_body_cfg* cfg, const tabed_body_weights* w
             !weights->wdown[l])
             return TABED_ENULL;
         if (misaligned(weights->wqkv[l]) || misaligned(weights->wo[l]) || misaligned(weights->wgu[l]) ||
-            misaligned(weights->wdown[l]))
+            misaligned(weights->wdown[l]) || misaligned(weights->g_attn[l]) || misaligned(weights->g_mlp[l]))
             return TABED_EALIGN;
     }
-    if (misaligned(ws) || misaligned(kcache) || misaligned(vcache) || misaligned(H) || misaligned(weights->embed))
+    if (misaligned(ws) || misaligned(kcache) || misaligned(vcache) || misaligned(H) || misaligned(weights->embed) ||
+        misaligned(weights->g_final))
         return TABED_EALIGN;
     const hipError_t e = launch_body_step(*cfg, *weights, static_cast<char*>(ws), rows, token_src, token_stride, rows_per_token,
                                           ctx_len, static_cast<uint16_t*>(kcache), static_cast<uint16_t*>(vcache),

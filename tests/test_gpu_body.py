@@ -108,6 +108,7 @@ CASES = [
     ("tiny_generic", synth.BodyConfig(layers=2, d=64, heads=4, d_ff=72, V=50, max_ctx=24), 5),
     ("head128", synth.BodyConfig(layers=1, d=256, heads=2, d_ff=512, V=300, max_ctx=40), 33),
     ("d48_three_layers", synth.BodyConfig(layers=3, d=48, heads=3, d_ff=80, V=17, max_ctx=12), 7),
+    ("wide_ragged_20_rows", synth.BodyConfig(layers=1, d=256, heads=4, d_ff=1032, V=100, max_ctx=20), 20),
     ("d512_skinny", synth.BodyConfig(layers=2, d=512, heads=8, d_ff=1536, V=1000, max_ctx=300), 64),
 ]
 
@@ -161,7 +162,7 @@ def test_body_rejects_bad_configurations():
     torch, binding = _gpu()
     ok = dict(layers=2, d=64, heads=4, d_ff=72, V=50, max_ctx=24)
     assert binding.tabed_body_workspace_bytes(binding.make_body_cfg(**ok), 8) > 0
-    for bad in (dict(layers=0), dict(layers=17), dict(d=60), dict(heads=3), dict(heads=16), dict(d_ff=70), dict(V=0),
+    for bad in (dict(layers=0), dict(layers=17), dict(d=60), dict(heads=3), dict(heads=16), dict(d=48, heads=2), dict(d_ff=70), dict(V=0),
                 dict(max_ctx=0), dict(max_ctx=8193), dict(rope_theta=0.0), dict(rms_eps=0.0)):
         assert binding.tabed_body_workspace_bytes(binding.make_body_cfg(**{**ok, **bad}), 8) == 0, bad
     assert binding.tabed_body_workspace_bytes(binding.make_body_cfg(**ok), 0) == 0
