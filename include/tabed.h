@@ -174,6 +174,8 @@ int tabed_draft_step_static(const tabed_cfg* cfg, uint64_t round, int32_t pos,
  *                 D(p_i, (1-c/10) q_i^(1) + (c/10) q_i^(2)) for c = 0..10 (DW = 11); meaningful for i < n_valid[b]
  *   n_valid       [B]       int32 out  min(k+1, gamma): positions whose distances enter the window
  *   flags         [B,gamma+1] uint8 out flags of the accept test at i and of the sample emitted at i
+ *                 (hard labels with the two-draft grid: TABED_FLAG_SAMPLE_MARGIN at a labelled position i <= k also
+ *                 when the two largest entries of a candidate mixture there are closer than 1e-6 relative)
  *   ring, ring_head, ring_count, next_weights: optional, all four or all NULL.  When given, the call also
  *                 performs the tabed_update_weights() that would open round + 1 (same arguments, same
  *                 result: the window takes the n_valid verified positions and next_weights [B,n] receives the

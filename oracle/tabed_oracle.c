@@ -327,6 +327,9 @@ void oracle_verify(int V, int n, int B, int gamma, int distance, int n_cand,
         for (int i = 0; i <= gamma; ++i) fl[i] = 0;
         /* hard labels (distance 2): arg-max token of every candidate distribution at every position */
         int* pred = (int*)malloc((size_t)gamma * 64 * sizeof(int));
+        /* reading: a mixture's arg-max whose runner-up is within the margin flags the position it labels (the
+         * arg-max of a single draft is decided by its fp32 logits, the same on every implementation: no flag) */
+        uint8_t* near_tie = (uint8_t*)calloc((size_t)gamma * 64, 1);
 
         int k = 0, rejected = 0;
         for (int i = 0; i < gamma; ++i) {
@@ -347,7 +350,12 @@ void oracle_verify(int V, int n, int B, int gamma, int distance, int n_cand,
                     f[v] = w0 * q[v] + w1 * q[(size_t)V + v];
                     mixlog[v] = log(f[v]);
                 }
-                if (distance == 2) { pred[i * 64 + c] = oracle_argmax(f, V, NULL); continue; }
+                if (distance == 2) {
+                    uint32_t tie = 0;
+                    pred[i * 64 + c] = oracle_argmax(f, V, &tie);
+                    near_tie[i * 64 + c] = tie ? 1 : 0;
+                    continue;
+                }
                 double D = distance == 0 ? oracle_kl(p, logp, mixlog, V) : oracle_tvd(p, f, V);
                 dev[((size_t)b * gamma + i) * DW + c] = (float)D;
             }
@@ -417,9 +425,10 @@ void oracle_verify(int V, int n, int B, int gamma, int distance, int n_cand,
                 for (int c = 0; c < DW; ++c) {
                     const int label = i <= k ? out_tokens[(size_t)b * (gamma + 1) + i] : -1;
                     dev[((size_t)b * gamma + i) * DW + c] = (pred[i * 64 + c] == label) ? 0.0f : 1.0f;
+                    if (i <= k && near_tie[i * 64 + c]) fl[i] |= ORACLE_FLAG_SAMPLE_MARGIN;
                 }
         }
-        free(p); free(logp); free(q); free(logq); free(f); free(mixlog); free(pred);
+        free(p); free(logp); free(q); free(logq); free(f); free(mixlog); free(pred); free(near_tie);
     }
 }
 

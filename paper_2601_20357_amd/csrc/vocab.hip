@@ -752,7 +752,8 @@ __global__ __launch_bounds__(kBlock) void k_stats(StatsArgs a) {
 //   MODE 3: arg-max_v q_j(v)                  per draft j                (hard labels; needs no target row)
 //   MODE 4: arg-max_v mix_c(v)                per candidate c            (hard labels, n = 2)
 // with mix_c = (1 - c/10) q_1 + (c/10) q_2.  Chunk sums go to dist[b][i][c][chunk][0] (k_finish adds them);
-// chunk arg-maxes go to dist[b][i][c][chunk][0..1] as (value, index), lowest index on ties.
+// chunk arg-maxes go to dist[b][i][c][chunk][0..1] as ((value, runner-up value) as two floats, index), lowest
+// index on ties.
 // =====================================================================================================
 struct DistArgs {
     int V, n, B, gamma, C3, RS, DW, Cd;
@@ -773,6 +774,7 @@ __global__ __launch_bounds__(kBlock) void k_dist(DistArgs a) {
     __shared__ float s_hi[TABED_MAX_N], s_oml[TABED_MAX_N];
     __shared__ double s_sum[kWavesPerBlock][TABED_MAX_N];
     __shared__ ArgMax s_amx[kWavesPerBlock][TABED_MAX_N];
+    __shared__ float s_sec[kWavesPerBlock][TABED_MAX_N];      // runner-up value beside every arg-max (mixtures only)
 
     const float* trow = a.target + ((size_t)b * (gamma + 1) + i) * V;
     const float* qbase = a.dlogits + (((size_t)i * a.B + b) * n) * V;
@@ -795,7 +797,8 @@ __global__ __launch_bounds__(kBlock) void k_dist(DistArgs a) {
                         if (v < V) am = argmax_merge(am, ArgMax{f4get(y[u], e), v});
                     }
                 am = wave_argmax(am);
-                if (lane == 0) s_amx[wave][j] = am;
+                // fp32 logits compare exactly on both sides of any check: no runner-up is needed for these
+                if (lane == 0) { s_amx[wave][j] = am; s_sec[wave][j] = -INFINITY; }
             }
         } else {
             if (tid < 2) {
@@ -822,22 +825,37 @@ __global__ __launch_bounds__(kBlock) void k_dist(DistArgs a) {
                 }
             for (int k = 0; k < NC; ++k) {
                 const float w1 = (float)k / (float)(NC - 1), w0 = 1.f - w1;
+                // the mixture is evaluated in fp32 here and in fp64 by a checker: the runner-up travels with the
+                // arg-max so that a near-tie can be flagged where the label is known
                 ArgMax am{-INFINITY, 0x7fffffff};
+                float sec = -INFINITY;
 #pragma unroll
                 for (int x = 0; x < 16; ++x) {
                     const int v = cb + ((x >> 2) * kBlock + tid) * 4 + (x & 3);
-                    if (v < V) am = argmax_merge(am, ArgMax{w0 * q0[x] + w1 * q1[x], v});
+                    if (v < V) {
+                        const ArgMax cand{w0 * q0[x] + w1 * q1[x], v};
+                        const ArgMax win = argmax_merge(am, cand);
+                        sec = fmaxf(sec, win.i == cand.i ? am.v : cand.v);      // the loser's value
+                        am = win;
+                    }
                 }
-                am = wave_argmax(am);
-                if (lane == 0) s_amx[wave][k] = am;
+                const ArgMax wam = wave_argmax(am);
+                const float wsec = wave_max((am.i == wam.i) ? sec : am.v);
+                if (lane == 0) { s_amx[wave][k] = wam; s_sec[wave][k] = wsec; }
             }
         }
         __syncthreads();
         if (tid < a.DW) {
             ArgMax t = s_amx[0][tid];
-            for (int w = 1; w < kWavesPerBlock; ++w) t = argmax_merge(t, s_amx[w][tid]);
+            float sec = s_sec[0][tid];
+            for (int w = 1; w < kWavesPerBlock; ++w) {
+                const ArgMax o = s_amx[w][tid];
+                const ArgMax win = argmax_merge(t, o);
+                sec = fmaxf(fmaxf(sec, s_sec[w][tid]), (win.i == o.i && o.i != t.i) ? t.v : o.v);
+                t = win;
+            }
             double* rec = a.dist + ((((size_t)b * gamma + i) * a.DW + tid) * a.Cd + c) * 2;
-            rec[0] = (double)t.v;
+            rec[0] = __builtin_bit_cast(double, make_float2(t.v, sec));       // (arg-max value, runner-up value)
             rec[1] = (double)t.i;
         }
         return;
@@ -990,6 +1008,7 @@ struct FinishArgs {
     int DW, Cd;
     float dist_scale;     // 0.5 for total variation, 1 for KL
     int hard;             // 1: dist holds chunk arg-maxes and the distance is the token-mismatch indicator
+    int hard_margin;      // 1: those arg-maxes are of fp32 mixtures: a near-tie flags the position
     int fuse;             // 1: the call also advances every sequence's window and writes the next weights
     WindowArgs win;
     double* tstate;       // token tree: [B][kTsSlots] record of every sequence's walk, or nullptr (chain)
@@ -1075,10 +1094,19 @@ __device__ __forceinline__ void resid_eval(const ResidRow& r, int n, int V, cons
         }
 }
 
-// Arg-max over the chunk arg-maxes of one (position, candidate): records are (value, index) pairs.
-__device__ __forceinline__ int hard_pred(const double* rec, int Cd) {
+// Arg-max over the chunk arg-maxes of one (position, candidate): records are ((value, runner-up), index).
+// *near: the runner-up over the whole row is within the margin of the winner.
+__device__ __forceinline__ int hard_pred(const double* rec, int Cd, bool* near) {
     ArgMax am{-INFINITY, 0x7fffffff};
-    for (int cc = 0; cc < Cd; ++cc) am = argmax_merge(am, ArgMax{(float)rec[cc * 2], (int)rec[cc * 2 + 1]});
+    float sec = -INFINITY;
+    for (int cc = 0; cc < Cd; ++cc) {
+        const float2 vs = __builtin_bit_cast(float2, rec[cc * 2]);
+        const ArgMax o{vs.x, (int)rec[cc * 2 + 1]};
+        const ArgMax win = argmax_merge(am, o);
+        sec = fmaxf(fmaxf(sec, vs.y), (win.i == o.i && o.i != am.i) ? am.v : o.v);
+        am = win;
+    }
+    *near = (am.v - sec) < kMargin * fabsf(am.v);
     return am.i;
 }
 
@@ -1257,9 +1285,12 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
                 const int ii = q / a.DW;
                 if (ii == k && !greedy) continue;
                 const int label = ii < k ? s_y[ii] : (ii == k ? s_rowam[k] : -1);
-                publish_store(&a.dev[(size_t)b * gamma * a.DW + q],
-                              hard_pred(a.dist + ((size_t)b * gamma * a.DW + q) * a.Cd * 2, a.Cd) == label ? 0.f : 1.f);
+                bool near;
+                const int pred = hard_pred(a.dist + ((size_t)b * gamma * a.DW + q) * a.Cd * 2, a.Cd, &near);
+                publish_store(&a.dev[(size_t)b * gamma * a.DW + q], pred == label ? 0.f : 1.f);
+                if (near && a.hard_margin && ii <= k) atomicOr(&s_aflag[ii], (uint32_t)TABED_FLAG_SAMPLE_MARGIN);
             }
+            __syncthreads();                               // (uniform: book and a.hard are) the flags are complete
         }
         if (tid <= gamma) {
             // accepted prefix, -1 padding, flags of the tests that were evaluated; slot k belongs to the sampler
@@ -1320,15 +1351,22 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
     if (!s_last) return;
     if (a.fuse && !a.hard && tid < n) a.win.weights[(size_t)b * n + tid] = published_load(&a.wstage[(size_t)b * n + tid]);
     // hard labels: the rejected position's distances and the window update wait for the corrected token
-    auto finish_hard = [&](int tok) {                      // wave 0 only
+    // returns the flag bit of a near-tie among the mixtures' arg-maxes at position k
+    auto finish_hard = [&](int tok) -> uint32_t {          // wave 0 only
+        bool any = false;
         if (k < gamma)
-            for (int cidx = lane; cidx < a.DW; cidx += kWave)
-                publish_store(&a.dev[((size_t)b * gamma + k) * a.DW + cidx],
-                              hard_pred(a.dist + (((size_t)b * gamma + k) * a.DW + cidx) * a.Cd * 2, a.Cd) == tok ? 0.f : 1.f);
+            for (int cidx = lane; cidx < a.DW; cidx += kWave) {
+                bool near;
+                const int pred = hard_pred(a.dist + (((size_t)b * gamma + k) * a.DW + cidx) * a.Cd * 2, a.Cd, &near);
+                publish_store(&a.dev[((size_t)b * gamma + k) * a.DW + cidx], pred == tok ? 0.f : 1.f);
+                any = any || near;
+            }
+        const uint32_t extra = (a.hard_margin && __ballot(any)) ? (uint32_t)TABED_FLAG_SAMPLE_MARGIN : 0u;
         if (a.fuse) {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's published distances are acknowledged
             window_update<true>(a.win, b, lane, a.dev, nv_k, s_wpart, s_wx);
         }
+        return extra;
     };
 
     // ---- last workgroup of sequence b: locate the segment, then the token
@@ -1400,6 +1438,11 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
     if (cross) pick = __ffsll((long long)cross) - 1;
     else if (live) { pick = 63 - __clzll((long long)live); flag |= TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE; }
     else { pick = 0; flag |= TABED_FLAG_SAMPLE_MARGIN | TABED_FLAG_DEGENERATE; }
+    if (a.hard) {
+        const int e = cross ? hit : (live ? lastlive : 0);
+        const int mine = (v + e < V) ? v + e : V - 1;
+        flag |= finish_hard(__builtin_amdgcn_readlane(mine, pick));
+    }
     if (lane == pick) {
         const int e = cross ? hit : (live ? lastlive : 0);
         const int tok = v + e;
@@ -1410,11 +1453,6 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
         if (tok > 0 && fabs((hi_edge - fe) - target) < tol) flag |= TABED_FLAG_SAMPLE_MARGIN;
         a.out_tokens[out_idx] = tok < V ? tok : V - 1;
         a.flags[out_idx] = (uint8_t)flag;
-    }
-    if (a.hard) {
-        const int e = cross ? hit : (live ? lastlive : 0);
-        const int mine = (v + e < V) ? v + e : V - 1;
-        finish_hard(__builtin_amdgcn_readlane(mine, pick));
     }
 }
 
@@ -1479,6 +1517,7 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
     a.stats = reinterpret_cast<const double*>(ws + L.off_stats);
     a.dist = second_pass ? reinterpret_cast<const double*>(ws + L.off_dist) : nullptr;
     a.DW = L.DW; a.Cd = L.Cd; a.dist_scale = (c.distance == 1) ? 0.5f : 1.f; a.hard = (c.distance == 2) ? 1 : 0;
+    a.hard_margin = (c.distance == 2 && c.policy == 2) ? 1 : 0;
     a.fuse = (ring != nullptr) ? 1 : 0;
     a.win = window_args(c, round + 1, ring, ring_head, ring_count, next_weights);   // the weights of the NEXT round
     a.wstage = reinterpret_cast<float*>(ws + L.off_wstage);

@@ -256,8 +256,9 @@ def compare_round(g, o, wl, tally: Tally, check_logits=True, hard=False, margins
         assert np.array_equal(g["out_tokens"][b, :ko], o["out_tokens"][b, :ko])
         assert np.all(g["out_tokens"][b, ko + 1:] == -1)
         tally.decisions += 1
+        # (with hard labels the bit at ko can also stand for a near-tie among the mixtures' arg-maxes: no margin check)
         tally.count_flag(g["flags"][b, ko] & SM, o["flags"][b, ko] & SM,
-                         (lambda b=b, ko=ko: margins.emitted(b, ko)) if margins else None)
+                         (lambda b=b, ko=ko: margins.emitted(b, ko)) if margins and not hard else None)
         if g["out_tokens"][b, ko] != o["out_tokens"][b, ko]:
             flagged = (g["flags"][b, ko] | o["flags"][b, ko]) & SM
             assert flagged, f"unflagged emitted-token mismatch b={b} k={ko}: {g['out_tokens'][b]} vs {o['out_tokens'][b]}"
@@ -266,7 +267,14 @@ def compare_round(g, o, wl, tally: Tally, check_logits=True, hard=False, margins
             if hard:
                 lock = False
         elif hard:
-            assert np.array_equal(d_g, d_o), (b, d_g, d_o)       # mismatch indicators: exact
+            # mismatch indicators: exact, except at a labelled position one side flagged for a near-tie between the
+            # two largest entries of a candidate mixture (evaluated in fp32 on one side, fp64 on the other)
+            differ = np.any(d_g != d_o, axis=1)
+            tied = ((g["flags"][b, :gamma] | o["flags"][b, :gamma]) & SM) != 0
+            assert not np.any(differ & ~tied), (b, d_g, d_o, g["flags"][b], o["flags"][b])
+            if np.any(differ):
+                tally.flagged_divergences += 1
+                lock = False
     return lock
 
 

@@ -184,6 +184,52 @@ def test_out_of_range_draft_token_is_rejected_not_dereferenced(oracle):
     assert 0 <= buf.out_tokens[1, 0].item() < wl.V
 
 
+def test_hard_label_near_tie_of_a_mixture_is_flagged(oracle):
+    """Two-draft grid with hard labels, hand-made logits handed to tabed_verify: a mixture whose two largest entries
+    tie (in one 4096-wide chunk for sequence 0, across chunks for sequence 1) flags the labelled position on both
+    sides, not the positions after the rejection; distances and tokens agree exactly."""
+    V, gamma, B = 9000, 4, 2
+    wl = synth.scaled(SERVING, V=V, d=64, n=2, B=B, gamma=gamma, h=4, cfg_id=55)
+    gpu = harness.GpuSide(wl, policy=2, distance=2)
+    W = synth.make_lm_head(wl)
+    H, target0 = synth.make_round(wl, W, 0)
+    temp = np.array([0.0, 1.0], np.float32)                    # sequence 0 greedy, sequence 1 sampling
+    gpu.round(0, harness.to_dev_store(W, wl.w_dtype), H, target0, temp)
+    buf = gpu.buf
+    logq = np.full((gamma, B, 2, V), -3.0, np.float32)
+    logq[:, :, :, 3] = 1.0                                     # both drafts: mode on token 3
+    logq[1, 0, :, 7] = 1.0                                     # position 1: a second token ties with it (same chunk)
+    logq[1, 1, :, 5000] = 1.0                                  # ... (another chunk)
+    logq[3, :, :, 7] = 1.0                                     # position 3 comes after the rejection
+    logp = np.full((B, gamma + 1, V), -3.0, np.float32)
+    logp[:, 0, 3] = logp[:, 1, 3] = 4.0                        # the target agrees at 0 and 1, wants token 5 at 2
+    logp[:, 2, 5] = 4.0
+    tok = np.full((B, gamma), 3, np.int32)
+    q_y = np.array([[oracle.softmax(logq[i, b, 0], 1.0)[0][3] for i in range(gamma)] for b in range(B)], np.float32)
+    lse = np.log(np.exp(logq.astype(np.float64)).sum(axis=-1))
+    u_acc = np.array([[0.01, 0.01, 0.9, 0.9]] * B, np.float32)
+    u_res = np.array([0.5, 0.5], np.float32)
+    buf.draft_logits.copy_(torch.from_numpy(logq))
+    buf.draft_lse.copy_(torch.from_numpy(lse))
+    buf.draft_tokens.copy_(torch.from_numpy(tok))
+    buf.draft_q.copy_(torch.from_numpy(q_y))
+    dev_t = lambda a: torch.from_numpy(a).to(DEV)
+    buf.verify(1, dev_t(logp), dev_t(temp), dev_t(u_acc), dev_t(u_res))
+    torch.cuda.synchronize()
+    weights = buf.weights.cpu().numpy()
+    o = oracle.verify(V=V, n=2, B=B, gamma=gamma, distance=2, seed=0, rnd=1, n_cand=oracle.GRID_CANDIDATES,
+                      target_logits=logp, draft_logits=logq, draft_tokens=tok, draft_q=q_y, weights=weights,
+                      temperature=temp, u_acc=u_acc, u_res=u_res)
+    SM = binding.FLAG_SAMPLE_MARGIN
+    g_flags = buf.verify_flags.cpu().numpy()
+    assert np.array_equal(buf.accept_len.cpu().numpy(), o["accept_len"]) and np.all(o["accept_len"] == 2)
+    assert np.array_equal(buf.out_tokens.cpu().numpy(), o["out_tokens"])
+    assert np.array_equal(buf.dev.cpu().numpy(), o["dev"])
+    for b in range(B):
+        for side in (g_flags, o["flags"]):
+            assert side[b, 1] & SM and not side[b, 0] & SM and not side[b, 3] & SM, (b, side[b])
+
+
 # ------------------------------------------------------------------ the window / weights kernel alone
 def test_update_weights_alone_matches_oracle_bitwise_state(oracle):
     rng = np.random.default_rng(60)

@@ -485,3 +485,30 @@ def test_hard_label_distance_counts_token_mismatches(oracle):
     wts = oracle.update_weights(n=2, B=1, gamma=3, h=8, policy=2, tau_w=1.0, eps=1e-6, dev=dev,
                                 n_valid=np.array([3], np.int32), ring=ring, ring_head=head, ring_count=count)
     np.testing.assert_allclose(wts[0], [0.4, 0.6], atol=1e-7)
+
+
+def test_hard_label_near_tie_of_a_mixture_flags_its_position(oracle):
+    """distance 2 with the two-draft grid: a candidate mixture whose two largest entries are closer than the margin
+    flags every labelled position (i <= k) it occurs at and none after the rejected one; single drafts (n_cand = 0)
+    are decided by their fp32 logits and never flag."""
+    V, gamma = 12, 4
+    SM = 2
+    logq = np.full((gamma, 2, V), -3.0, np.float32)
+    for i in range(gamma):
+        logq[i, :, 3] = 1.0                    # both drafts put their mode on token 3 ...
+    logq[1, :, 7] = 1.0                        # ... at position 1 token 7 ties with it in every mixture
+    logq[3, :, 7] = 1.0                        # also at position 3, which comes after the rejection below
+    logp = np.full((gamma + 1, V), -3.0, np.float32)
+    logp[0, 3] = logp[1, 3] = 4.0              # the target agrees at positions 0 and 1,
+    logp[2, 5] = 4.0                           # rejects at 2 (wants token 5)
+    tok = np.full((1, gamma), 3, np.int32)
+    args = dict(V=V, n=2, B=1, gamma=gamma, distance=2, seed=0, rnd=0, target_logits=logp[None],
+                draft_logits=np.ascontiguousarray(logq[:, None]), draft_tokens=tok,
+                draft_q=np.ones((1, gamma), np.float32), weights=np.full((1, 2), 0.5, np.float32),
+                temperature=np.zeros(1, np.float32))
+    out = oracle.verify(n_cand=oracle.GRID_CANDIDATES, **args)
+    assert int(out["accept_len"][0]) == 2
+    assert [int(f) & SM for f in out["flags"][0]] == [0, SM, 0, 0, 0]
+    assert np.all(out["dev"][0, 1] == 0.0)     # the tie goes to the lower index, which is the label
+    plain = oracle.verify(n_cand=0, **args)
+    assert not np.any(plain["flags"][0] & SM)
