@@ -7,9 +7,9 @@
  * verify gamma drafted tokens by speculative sampling.  This library is the
  * part of one such round that sits behind the two models' transformer bodies:
  *
- *   tabed_update_weights   Alg. 1 lines 2-3 with the many-draft policy of
+ *   tabed_update_weights   Alg. 1 (weight-selection step) with the many-draft policy of
  *                          App. B.2 (w = softmax(1/e; tau)), incl. the window.
- *   tabed_draft_step       Alg. 1 lines 5-7 for one in-block position: LM head
+ *   tabed_draft_step       Alg. 1 (loop body: draft forward, W-Avg, Sample) for one in-block position: LM head
  *                          of the n drafts as one batched GEMM, per-draft
  *                          softmax, weighted-average ensemble, next token.
  *   tabed_verify           Sec. 3 items 2-3: accept each drafted token with
@@ -114,7 +114,7 @@ const char* tabed_strerror(int code);
 int tabed_last_hip_error(void);
 
 /*
- * Alg. 1 lines 5-7 at in-block position `pos` (0 <= pos < gamma) for all B
+ * Alg. 1 (loop body: draft forward, W-Avg, Sample) at in-block position `pos` (0 <= pos < gamma) for all B
  * sequences:  L = H W^T for the n*B rows, q^(j) = softmax(L_j / T),
  * q = sum_j w_j q^(j), y ~ Sample(q) (arg-max for greedy rows).
  *
@@ -240,7 +240,7 @@ int tabed_verify_tree(const tabed_cfg* cfg, void* ws, uint64_t round, int32_t tr
                       float* ring, int32_t* ring_head, int32_t* ring_count, float* next_weights, void* stream);
 
 /*
- * Alg. 1 lines 2-3 with the policy of App. B.2: push the distances of the
+ * Alg. 1 (weight-selection step) with the policy of App. B.2: push the distances of the
  * n_valid[b] verified positions of the finished block into the window, then
  * w = softmax((1 / max(e_j, eps)) / tau_w) with e_j the window sum (policy 0), or the candidate
  * [1-c/10, c/10] with the smallest window sum, lowest c on ties (policy 2).  An empty

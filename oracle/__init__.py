@@ -153,7 +153,7 @@ def tvd(p, q):
 # ---------------------------------------------------------------- the three calls
 def draft_step(*, V, d, n, B, gamma, w_dtype, seed, rnd, pos, W, H, weights, temperature,
                draft_logits, draft_lse, draft_tokens, draft_q, flags, u_draft=None):
-    """Alg. 1 lines 5-7 at in-block position `pos`; writes slot/column `pos` of the outputs in place."""
+    """Alg. 1 (loop body: draft forward, W-Avg, Sample) at in-block position `pos`; writes slot/column `pos` of the outputs in place."""
     assert draft_logits.dtype == np.float32 and draft_logits.shape == (gamma, B, n, V)
     assert draft_lse.dtype == np.float64 and draft_lse.shape == (gamma, B, n)
     assert draft_tokens.dtype == np.int32 and draft_tokens.shape == (B, gamma)
@@ -208,7 +208,7 @@ def verify(*, V, n, B, gamma, distance, seed, rnd, target_logits, draft_logits, 
 
 
 def update_weights(*, n, B, gamma, h, policy, tau_w, eps, dev, n_valid, ring, ring_head, ring_count, seed=0, rnd=0):
-    """Alg. 1 lines 2-3 (App. B.2 policy); ring state is updated in place; returns weights [B,n]."""
+    """Alg. 1 (weight-selection step) (App. B.2 policy); ring state is updated in place; returns weights [B,n]."""
     assert ring.dtype == np.float32 and ring.shape == (B, max(h, 1), dev_width(n, policy))   # h = 0: window ALL
     assert policy != 2 or n == 2
     assert ring_head.dtype == np.int32 and ring_count.dtype == np.int32

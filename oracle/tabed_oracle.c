@@ -19,7 +19,7 @@
  *   - App. B.2: the many-draft policy w = softmax([1/e^(1)..1/e^(m)]; tau),
  *     tau = 1, and the two-draft policy that scores the fixed candidates
  *     w^c = [1 - c/10, c/10] by the accumulated distance of the MIXTURE
- *     q(.; w^c) from the target and takes the arg-min (Alg. 1 line 3);
+ *     q(.; w^c) from the target and takes the arg-min (Alg. 1 (arg-min step));
  *     Sec. 5.1 last paragraph: TVD as the alternative distance; Sec. 5.1:
  *     selection by hard labels (token matches) instead of soft labels.
  *   - Eq. 1: speedup = block_eff / (gamma * Tq/Tp + 1).
@@ -102,7 +102,7 @@ double oracle_speedup(double block_eff, double gamma, double tq_over_tp)
 }
 
 /* ------------------------------------------------------------------ */
-/* LM head (Alg. 1 line 5, last layer of M_q): L[r,v] = sum_k H[r,k] W[v,k]. */
+/* LM head (Alg. 1 (draft forward), last layer of M_q): L[r,v] = sum_k H[r,k] W[v,k]. */
 /* Storage values (fp32 or bf16) are upcast exactly; fp64 accumulation in    */
 /* k order; one rounding to fp32 at the end.                                  */
 /* ------------------------------------------------------------------ */
@@ -160,7 +160,7 @@ double oracle_softmax(const float* logits, int V, double T_eff, double* p, doubl
     return lse;
 }
 
-/* W-Avg (Alg. 1 line 6): probability-space weighted average of n rows. */
+/* W-Avg (Alg. 1 (W-Avg step)): probability-space weighted average of n rows. */
 void oracle_ensemble(int n, int V, const double* q, const float* w, double* q_ens)
 {
     for (int v = 0; v < V; ++v) {
@@ -234,7 +234,7 @@ double oracle_tvd(const double* p, const double* q, int V)
 }
 
 /* ------------------------------------------------------------------ */
-/* Alg. 1 lines 5-7 for one in-block position, all B sequences.        */
+/* Alg. 1 (loop body: draft forward, W-Avg, Sample) for one in-block position, all B sequences.        */
 /* ------------------------------------------------------------------ */
 /* Layouts: W [V,d], H [B,n,d] (w_dtype 0 fp32 / 1 bf16), weights [B,n],
  * temperature [B] (0 => greedy row), u_draft [B,gamma] or NULL (=> Philox),
@@ -280,7 +280,7 @@ void oracle_draft_step(int V, int d, int n, int B, int gamma, int w_dtype,
 }
 
 /* ------------------------------------------------------------------ */
-/* Sec. 3 items 2-3 + the per-position distances of Alg. 1 line 3.     */
+/* Sec. 3 items 2-3 + the per-position distances of Alg. 1 (arg-min step).     */
 /* ------------------------------------------------------------------ */
 /* target_logits [B,gamma+1,V]; u_acc [B,gamma] / u_res [B] or NULL (=> Philox).
  * Outputs: accept_len [B] = k; out_tokens [B,gamma+1] = the k accepted draft
@@ -433,7 +433,7 @@ void oracle_verify(int V, int n, int B, int gamma, int distance, int n_cand,
 }
 
 /* ------------------------------------------------------------------ */
-/* Alg. 1 lines 2-3 with the App. B.2 many-draft policy.               */
+/* Alg. 1 (weight-selection step) with the App. B.2 many-draft policy.               */
 /* ------------------------------------------------------------------ */
 /* ring [B,h,n] holds the last <= h per-position distance vectors of each
  * sequence; ring_head [B] is the next slot to overwrite, ring_count [B] the
@@ -536,7 +536,7 @@ void oracle_update_weights(int n, int B, int gamma, int h, int policy,
  * reading (the paper names the tree width, 2 or 3, and nothing else): at every
  * in-block position i the draft proposes `width` sibling candidates for the
  * same prefix, all taken from the ensembled distribution q_i of that position:
- * candidate 0 is the token Alg. 1 line 7 samples (the "trunk": the only one
+ * candidate 0 is the token Alg. 1 (Sample step) samples (the "trunk": the only one
  * the draft model extends to position i+1), candidates 1..width-1 are leaves.
  * A sampling row draws the siblings independently from q_i (inverse CDF, own
  * uniform each); a greedy row takes the next-largest entries of q_i (lowest

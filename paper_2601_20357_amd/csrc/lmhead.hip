@@ -1,4 +1,4 @@
-// LM head of the n batched drafts (Alg. 1 line 5, last layer of the shared draft model):
+// LM head of the n batched drafts (Alg. 1 (draft forward), last layer of the shared draft model):
 //   L[r, v] = sum_k H[r, k] * W[v, k],   r = b*n + j  (M = n*B rows),
 // with the first half of the per-draft softmax fused into the epilogue: for every row and every 32-wide
 // vocabulary tile the kernel also writes  pm = max_v s(v)  and  ps = sum_v exp(s(v) - pm),  s = L / T_b.

@@ -1,6 +1,6 @@
-// Vocabulary-wide passes of a TABED round on gfx950: ensemble + draft token (Alg. 1 lines 6-7),
+// Vocabulary-wide passes of a TABED round on gfx950: ensemble + draft token (Alg. 1 (W-Avg and Sample steps)),
 // target statistics + per-draft KL + accept chain (Sec. 3 items 2-3, Sec. 5.1), corrected / bonus token
-// (Sec. 3 item 3), window + weights (Alg. 1 lines 2-3, App. B.2).  All of them are HBM- or latency-bound:
+// (Sec. 3 item 3), window + weights (Alg. 1 (weight-selection step), App. B.2).  All of them are HBM- or latency-bound:
 // DPP lane exchanges and a few LDS words do the reductions, fp64 carries the cross-wave and cross-workgroup
 // sums, and partial results cross workgroups through device-scope atomic stores that are waited for before an
 // arrival counter moves (no cache-flushing fences).
@@ -555,7 +555,7 @@ __global__ __launch_bounds__(kBlock) void k_sample(SampleArgs a) {
     a.flags[out_idx] = (uint8_t)flag;
 }
 
-// sib = 0: the trunk token of Alg. 1 line 7.  sib >= 1 (token tree of `width`): sibling `sib` of the position, from
+// sib = 0: the trunk token of Alg. 1 (Sample step).  sib >= 1 (token tree of `width`): sibling `sib` of the position, from
 // the same softmax partials; the output arrays are then the [B,gamma,width-1] sibling arrays.
 static hipError_t launch_sample_any(const tabed_cfg& c, const WsLayout& L, char* ws, uint64_t round, int pos,
                                     const float* logits, const float* weights, const float* temperature,

@@ -234,7 +234,7 @@ def test_tvd_distance_option(oracle):
             assert abs(out["dev"][0, i, j] - 0.5 * np.abs(p[i] - qj[i, j]).sum()) < 1e-6
 
 
-# ------------------------------------------------------------------ weights (Alg. 1 lines 2-3, App. B.2)
+# ------------------------------------------------------------------ weights (Alg. 1 (weight-selection step), App. B.2)
 def _fresh_ring(B, h, n):
     return np.zeros((B, h, n), np.float32), np.zeros(B, np.int32), np.zeros(B, np.int32)
 
@@ -322,7 +322,7 @@ def test_weights_follow_the_draft_that_matches_the_target(oracle):
         assert np.all(np.abs(w.sum(axis=1) - 1) < 1e-6)
 
 
-# ------------------------------------------------------------------ two-draft grid policy (App. B.2, Alg. 1 line 3)
+# ------------------------------------------------------------------ two-draft grid policy (App. B.2, Alg. 1 (arg-min step))
 def _grid_verify(oracle, logq, logp, distance, T=1.0):
     gamma, n, V = logq.shape
     dl = np.ascontiguousarray(logq.astype(np.float32)[:, None])      # [gamma,1,n,V]
