@@ -503,17 +503,19 @@ __global__ __launch_bounds__(kSkinnyThreads) void k_lmhead_skinny_kc(int M, int 
 
 // ---------------------------------------------------------------- bf16, many rows (M > 64): MFMA-bound tiled GEMM
 // With hundreds of rows (stress shape: n*B = 512) the LM head is a real GEMM: 2*M*d*V flops against one
-// pass over W.  Workgroup tile 256 (rows) x 256 (vocabulary) x 32 (k), 8 waves, each wave a 128 (rows) x 64
+// pass over W.  Workgroup tile 256 (rows) x 256 (vocabulary) x 64 (k), 8 waves, each wave a 128 (rows) x 64
 // (vocabulary) block (2 x 4 MFMA 32x32x16 tiles, W as the row operand so the accumulator is
 // [vocabulary][row] and the cheap transposed epilogue applies).  Both operands are staged through LDS in two
 // buffers; the operand fragments of k-step s+1 are read from LDS while the MFMAs of k-step s run, and the
-// global loads of k-blocks i+2 and i+3 are in flight (two register sets) while k-block i is multiplied --
-// one barrier per k-block.  Rows padded by 16 bytes against bank conflicts.  Workgroups are numbered so that
+// global loads of k-block i+1 are in flight (one register set) while k-block i-1 and i are multiplied --
+// one barrier per k-block.  A k-block of 64 is one whole 128-byte line of every row (measured 4.5 % faster than
+// k-blocks of 32 with two register sets: 318 against 334 us at the stress shape).  Rows padded by 16 bytes
+// against bank conflicts.  Workgroups are numbered so that
 // the row blocks that share a vocabulary block run back to back on the same XCD (workgroup w goes to XCD
 // w % 8): W is then read from HBM once and from L2 afterwards.
-constexpr int kLBM = 256, kLBN = 256, kLBK = 32, kLRow = (kLBK + 8) * 2;   // LDS row stride in bytes (80)
+constexpr int kLBM = 256, kLBN = 256, kLBK = 64, kLRow = (kLBK + 8) * 2;   // LDS row stride in bytes (144)
 constexpr int kLCh = kLBK / 8;                                              // 16-byte chunks per row of a k-block
-constexpr int kLargeStage = (kLBM + kLBN) * kLRow;                          // bytes per buffer (40960)
+constexpr int kLargeStage = (kLBM + kLBN) * kLRow;                          // bytes per buffer (73728)
 
 // Eight waves per workgroup, each 128 rows x 64 vocabulary entries, two waves per SIMD.  (Four waves of 128 x 128 with
 // register staging spill ~300 registers; four waves fed by global_load_lds measured no faster: the loop is bound by
@@ -545,43 +547,38 @@ __global__ __launch_bounds__(kLargeWaves * 64) void k_lmhead_large(int M, int d,
     const int wn = (NW == 8) ? wave & 3 : wave & 1;       // vocabulary v0 + 32*WNT*wn ..
     if (tid < kLBM && m0 + tid < M) s_invt[tid] = row_inv_temperature(temperature, m0 + tid, n);
 
-    // ---- global -> register staging: two register sets, so that the loads of k-block kb+2 and kb+3 are in
-    //      flight while k-block kb is multiplied (one k-block is only ~1000 cycles of MFMA work per SIMD,
-    //      less than an L2 round trip).  kLWPieces of W and kLHPieces of H per thread and set (16 bytes each).
-    u32x4 rw[2][kLWPieces], rh[2][kLHPieces];
-    auto fetch = [&](int kb, auto set_c) {
-        constexpr int S = decltype(set_c)::value;
+    // ---- global -> register staging: kLWPieces of W and kLHPieces of H per thread (16 bytes each), one k-block
+    //      ahead of the one in LDS.
+    u32x4 rw[kLWPieces], rh[kLHPieces];
+    auto fetch = [&](int kb) {
         const int k = kb * kLBK;
 #pragma unroll
         for (int t = 0; t < kLWPieces; ++t) {
             const int q = tid + t * kLargeThreads, row = q / kLCh, c = q % kLCh;
             const int v = min(v0 + row, V - 1);           // clamped rows are masked in the epilogue
-            rw[S][t] = *reinterpret_cast<const u32x4*>(W + (size_t)v * d + k + c * 8);
+            rw[t] = *reinterpret_cast<const u32x4*>(W + (size_t)v * d + k + c * 8);
         }
 #pragma unroll
         for (int t = 0; t < kLHPieces; ++t) {
             const int q = tid + t * kLargeThreads, row = q / kLCh, c = q % kLCh;
             const int m = min(m0 + row, M - 1);
-            rh[S][t] = *reinterpret_cast<const u32x4*>(H + (size_t)m * d + k + c * 8);
+            rh[t] = *reinterpret_cast<const u32x4*>(H + (size_t)m * d + k + c * 8);
         }
     };
-    auto stash = [&](int buf, auto set_c) {
-        constexpr int S = decltype(set_c)::value;
+    auto stash = [&](int buf) {
         unsigned char* sW = lds + buf * kLargeStage;
         unsigned char* sH = sW + kLBN * kLRow;
 #pragma unroll
         for (int t = 0; t < kLWPieces; ++t) {
             const int q = tid + t * kLargeThreads, row = q / kLCh, c = q % kLCh;
-            *reinterpret_cast<u32x4*>(sW + row * kLRow + c * 16) = rw[S][t];
+            *reinterpret_cast<u32x4*>(sW + row * kLRow + c * 16) = rw[t];
         }
 #pragma unroll
         for (int t = 0; t < kLHPieces; ++t) {
             const int q = tid + t * kLargeThreads, row = q / kLCh, c = q % kLCh;
-            *reinterpret_cast<u32x4*>(sH + row * kLRow + c * 16) = rh[S][t];
+            *reinterpret_cast<u32x4*>(sH + row * kLRow + c * 16) = rh[t];
         }
     };
-    using Set0 = std::integral_constant<int, 0>;
-    using Set1 = std::integral_constant<int, 1>;
 
     f32x16 acc[WNT][4];                                   // [vocabulary tile][row tile]
 #pragma unroll
@@ -618,21 +615,17 @@ __global__ __launch_bounds__(kLargeWaves * 64) void k_lmhead_large(int M, int d,
         }
     };
 
-    // k-block j lives in register set j & 1 until it is written to LDS buffer j & 1.  KB is even (d % 64 == 0).
+    // k-block kb+1 is requested while k-block kb-1 is multiplied and written to LDS after k-block kb: its loads have
+    // one multiply (about 2000 MFMA cycles per SIMD, more than an L2 round trip) to arrive.
     const int KB = d / kLBK;
-    fetch(0, Set0{});
-    stash(0, Set0{});
-    fetch(1, Set1{});
-    if (2 < KB) fetch(2, Set0{});
+    fetch(0);
+    stash(0);
+    if (1 < KB) fetch(1);
     lds_barrier();
-    for (int kb = 0; kb < KB; kb += 2) {
-        multiply(0);                                      // k-block kb
-        if (kb + 1 < KB) stash(1, Set1{});                // k-block kb+1 (requested two iterations ago)
-        if (kb + 3 < KB) fetch(kb + 3, Set1{});
-        lds_barrier();
-        if (kb + 1 < KB) multiply(1);                     // k-block kb+1
-        if (kb + 2 < KB) stash(0, Set0{});                // k-block kb+2
-        if (kb + 4 < KB) fetch(kb + 4, Set0{});
+    for (int kb = 0; kb < KB; ++kb) {
+        multiply(kb & 1);
+        if (kb + 1 < KB) stash((kb + 1) & 1);
+        if (kb + 2 < KB) fetch(kb + 2);
         lds_barrier();
     }
     // ---- epilogue: every wave turns its four 32x32 blocks through a private patch carved from buffer 0
