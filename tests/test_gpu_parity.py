@@ -138,7 +138,7 @@ def test_window_all(oracle):
         wl = synth.scaled(SERVING, V=4100, d=64, n=n, B=6, gamma=4, h=0, cfg_id=80 + policy)
         tally = harness.run_rounds(oracle, wl, 12, synth.make_temperature(wl, "one"), policy=policy)
         _say(tally)
-        assert tally.flagged_divergences <= 3
+        assert tally.flagged_divergences <= 1
 
 
 # ------------------------------------------------------------------ explicit uniforms, including the edges of [0,1)
@@ -275,18 +275,18 @@ def test_two_runs_are_bitwise_identical(oracle):
 # ------------------------------------------------------------------ full size, in the launch configuration bench.py times
 def test_serving_full_size_rounds(oracle):
     _say("serving full size")
-    tally = harness.run_rounds(oracle, SERVING, 3, synth.make_temperature(SERVING))
+    tally = harness.run_rounds(oracle, SERVING, 24, synth.make_temperature(SERVING))     # the h = 8 window wraps many times
     _say(tally)
-    assert tally.flagged_divergences <= 4
+    assert tally.flagged_divergences <= 2
 
 
 def test_llava_full_size_greedy_and_sampling(oracle):
     wl = synth.WORKLOADS["llava"]
     for mode in ("greedy", "one"):
         _say(f"llava {mode}")
-        tally = harness.run_rounds(oracle, wl, 4, synth.make_temperature(wl, mode))
+        tally = harness.run_rounds(oracle, wl, 16, synth.make_temperature(wl, mode))
         _say(tally)
-        assert tally.flagged_divergences <= 2
+        assert tally.flagged_divergences <= 1
 
 
 def test_lvlm_full_size(oracle):
