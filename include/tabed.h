@@ -18,6 +18,14 @@
  *                          distances D(p, q^(j)) of Sec. 5.1 that feed the
  *                          next tabed_update_weights.
  *
+ * Around that path:
+ *
+ *   tabed_draft_siblings,  Sec. 6.1 "Verification: Integrating Token Tree" (App. D): sibling candidates of a
+ *   tabed_verify_tree      position and their verification by multi-round rejection sampling.
+ *   tabed_draft_body_step, Sec. 5.1 "Ensemble learning via Batched Inference", Sec. 4.1 "Target and Draft
+ *   tabed_draft_body_rollback   Models": one decode step of the shared LLaMA-style draft model for the n * B rows.
+ *   tabed_draft_step_static     tabed_draft_step for callers that cannot allocate device memory.
+ *
  * Notation: n = number of drafting methods (the paper's m), B independent
  * sequences, V vocabulary size, d draft hidden size, gamma block length,
  * h observation window (in verified positions).
