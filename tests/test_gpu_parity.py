@@ -230,6 +230,82 @@ def test_hard_label_near_tie_of_a_mixture_is_flagged(oracle):
             assert side[b, 1] & SM and not side[b, 0] & SM and not side[b, 3] & SM, (b, side[b])
 
 
+# ------------------------------------------------------------------ the lossless property, on the GPU path alone
+@pytest.mark.parametrize("width", [1, 2, 3], ids=["chain", "tree2", "tree3"])
+def test_emitted_tokens_follow_the_target_distribution(width):
+    """Speculative sampling is lossless (Sec. 3 item 3): whatever the drafts propose, the first token a round emits
+    is distributed as p_0, and so is the token at position 1 when the round gets that far -- also with a token tree,
+    whose extra candidates only raise the chance of keeping a drafted token.  No oracle here: 64 sequences with the
+    same inputs and their own Philox streams, 400 rounds, chi-square of the emitted tokens against softmax of the
+    target logits (V = 12; the drafts are deliberately far from the target so that every branch of the rule runs)."""
+    from scipy.stats import chi2
+    V, d, n, B, gamma, R = 12, 16, 2, 64, 3, 400
+    cfg = binding.make_cfg(V=V, d=d, n=n, B=B, gamma=gamma, h=4, w_dtype=1, policy=1, seed=1234)
+    buf = binding.RoundBuffers(cfg, DEV)
+    S = width - 1
+    rng = np.random.default_rng(77)
+    W = harness.to_dev_store(synth.bf16_bits(rng.standard_normal((V, d), dtype=np.float32) * 0.4), 1)
+    H1 = rng.standard_normal((gamma, n, d), dtype=np.float32)
+    Hs = [harness.to_dev_store(synth.bf16_bits(np.broadcast_to(H1[i], (B, n, d)).copy()), 1) for i in range(gamma)]
+    t1 = (rng.standard_normal((gamma + 1, V)) * 1.2).astype(np.float32)
+    target = torch.from_numpy(np.broadcast_to(t1, (B, gamma + 1, V)).copy()).to(DEV)
+    l1 = (rng.standard_normal((gamma, max(S, 1), V)) * 1.2).astype(np.float32)
+    leaves = torch.from_numpy(np.broadcast_to(l1, (B, gamma, max(S, 1), V)).copy()).to(DEV)
+    temp = torch.ones(B, device=DEV)
+    sib_tok = torch.zeros((B, gamma, max(S, 1)), dtype=torch.int32, device=DEV)
+    sib_q = torch.zeros((B, gamma, max(S, 1)), dtype=torch.float32, device=DEV)
+    sib_fl = torch.zeros((B, gamma, max(S, 1)), dtype=torch.uint8, device=DEV)
+    leaf = torch.zeros(B, dtype=torch.int32, device=DEV)
+    n_out = torch.zeros(B, dtype=torch.int32, device=DEV)
+    buf.update_weights(True)
+    first = np.zeros(V)
+    second = np.zeros(V)
+    after_leaf = np.zeros((gamma, max(S, 1), V))
+    kept = 0
+    for rnd in range(R):
+        for pos in range(gamma):
+            buf.draft_step(rnd, pos, W, Hs[pos], temp)
+            if S:
+                binding.tabed_draft_siblings(cfg, buf.ws, rnd, pos, width, buf.draft_logits, buf.draft_tokens, buf.weights, temp,
+                                             sib_tok, sib_q, sib_fl)
+        if S:
+            binding.tabed_verify_tree(cfg, buf.ws, rnd, width, target, leaves, buf.draft_logits, buf.draft_lse, buf.draft_tokens,
+                                      buf.draft_q, sib_tok, sib_q, buf.weights, temp, buf.accept_len, buf.out_tokens, buf.dev,
+                                      buf.n_valid, buf.verify_flags, leaf, n_out)
+        else:
+            buf.verify(rnd, target, temp)
+        torch.cuda.synchronize()
+        out, k = buf.out_tokens.cpu().numpy(), buf.accept_len.cpu().numpy()
+        lf = leaf.cpu().numpy() if S else np.zeros(B, np.int32)
+        first += np.bincount(out[:, 0], minlength=V)
+        # position 1 is reached when the token at 0 was kept as the TRUNK token (a leaf ends the round's drafted part)
+        reached = (k >= 1)
+        second += np.bincount(out[reached, 1], minlength=V)
+        kept += int(k.sum())
+        for b in np.nonzero(lf > 0)[0]:                     # the token after an accepted leaf follows that leaf's row
+            after_leaf[k[b], lf[b] - 1, out[b, k[b] + 1]] += 1
+
+    def check(counts, logits, what):
+        p = np.exp(logits.astype(np.float64) - logits.max())
+        p /= p.sum()
+        N = counts.sum()
+        assert N > 1500, (what, N)
+        rare = N * p < 8                                    # bins too small for the chi-square approximation: one bin
+        obs = np.append(counts[~rare], counts[rare].sum())
+        exp = np.append(N * p[~rare], N * p[rare].sum())
+        obs, exp = obs[exp > 0], exp[exp > 0]
+        stat = float(((obs - exp) ** 2 / exp).sum())
+        assert stat < chi2.ppf(1 - 1e-6, len(exp) - 1), (what, stat, obs, exp)
+
+    check(first, t1[0], "first emitted token")
+    check(second, t1[1], "token at position 1")
+    assert 0 < kept < R * B * gamma                         # both accepting and rejecting happened
+    if S:
+        tot = after_leaf.sum(axis=-1)
+        i, s_ = np.unravel_index(np.argmax(tot), tot.shape)
+        check(after_leaf[i, s_], l1[i, s_], f"token after leaf {s_ + 1} of position {i}")
+
+
 # ------------------------------------------------------------------ the window / weights kernel alone
 def test_update_weights_alone_matches_oracle_bitwise_state(oracle):
     rng = np.random.default_rng(60)
