@@ -167,3 +167,64 @@ def test_body_rejects_bad_configurations():
         assert binding.tabed_body_workspace_bytes(binding.make_body_cfg(**{**ok, **bad}), 8) == 0, bad
     assert binding.tabed_body_workspace_bytes(binding.make_body_cfg(**ok), 0) == 0
     assert binding.tabed_body_workspace_bytes(binding.make_body_cfg(**ok), 65536) == 0
+
+
+def test_rounds_with_the_body_in_the_loop_are_reproducible_bit_for_bit():
+    """Body step -> LM head + ensemble + token -> ... -> verify -> rollback, three rounds, run twice from the same
+    state: every output identical (the projections' partial sums are added in a fixed order, no atomics), and the
+    positions follow the accepted prefix."""
+    torch, binding = _gpu()
+    bc = synth.BodyConfig(layers=2, d=256, heads=4, d_ff=1024, V=3000, max_ctx=64)
+    n, B, gamma = 3, 5, 4
+    rows = n * B
+    w = synth.make_body_weights(bc, 5)
+    dev = dict(embed=_to_dev(torch, w["embed"]), g_final=torch.from_numpy(w["g_final"]).cuda())
+    for key in ("wqkv", "wo", "wgu", "wdown"):
+        dev[key] = [_to_dev(torch, a) for a in w[key]]
+    for key in ("g_attn", "g_mlp"):
+        dev[key] = [torch.from_numpy(a).cuda() for a in w[key]]
+    bcfg = binding.make_body_cfg(layers=bc.layers, d=bc.d, heads=bc.heads, d_ff=bc.d_ff, V=bc.V, max_ctx=bc.max_ctx)
+    cfg = binding.make_cfg(V=bc.V, d=bc.d, n=n, B=B, gamma=gamma, h=4, w_dtype=1, seed=9)
+    g = torch.Generator().manual_seed(3)
+    Wlm = (torch.randn(bc.V, bc.d, generator=g) * 0.05).to(torch.bfloat16).cuda()
+    target = (torch.randn(3, B, gamma + 1, bc.V, generator=g) * 2.0).cuda()
+    first_tok = torch.randint(0, bc.V, (3, B), generator=g, dtype=torch.int32).cuda()
+    base = torch.randint(0, 20, (rows,), generator=g, dtype=torch.int32).cuda()
+    temp = torch.tensor([1.0, 0.0, 0.7, 1.0, 0.0]).cuda()
+
+    def run():
+        body = binding.BodyBuffers(bcfg, rows, dev)
+        buf = binding.RoundBuffers(cfg)
+        body.kcache.copy_(torch.randn(body.kcache.shape, generator=torch.Generator().manual_seed(4)).to(torch.bfloat16))
+        body.vcache.copy_(torch.randn(body.vcache.shape, generator=torch.Generator().manual_seed(5)).to(torch.bfloat16))
+        body.ctx_base.copy_(base)
+        body.ctx_len.copy_(base)
+        trace = []
+        for rnd in range(3):
+            buf.update_weights(rnd == 0, rnd=rnd)
+            for pos in range(gamma):
+                if pos == 0:
+                    binding.tabed_draft_body_step(bcfg, body.table, body.ws, rows, first_tok[rnd], 1, n, body.ctx_len,
+                                                  body.kcache, body.vcache, body.H)
+                else:
+                    binding.tabed_draft_body_step(bcfg, body.table, body.ws, rows, (buf.draft_tokens.view(-1), pos - 1), gamma, n,
+                                                  body.ctx_len, body.kcache, body.vcache, body.H)
+                buf.draft_step(rnd, pos, Wlm, body.H, temp)
+            torch.cuda.synchronize()
+            assert torch.equal(body.ctx_len, body.ctx_base + gamma)
+            buf.verify(rnd, target[rnd], temp)
+            binding.tabed_draft_body_rollback(rows, n, gamma, body.ctx_base, buf.accept_len, body.ctx_len)
+            torch.cuda.synchronize()
+            kept = torch.clamp(buf.accept_len + 1, max=gamma).repeat_interleave(n)
+            assert torch.equal(body.ctx_len, body.ctx_base + kept)
+            trace.append([t.clone() for t in (body.H.view(torch.int16), buf.draft_tokens, buf.draft_q, buf.draft_logits,
+                                              buf.accept_len, buf.out_tokens, buf.dev, body.ctx_len)])
+            body.ctx_base.copy_(body.ctx_len)             # the next round starts where this one stopped
+        trace.append([body.kcache.view(torch.int16).clone(), body.vcache.view(torch.int16).clone()])
+        return trace
+
+    one, two = run(), run()
+    for a, b in zip(one, two):
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
+    assert all(torch.isfinite(t[2]).all() for t in one[:3])
