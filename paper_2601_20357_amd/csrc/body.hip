@@ -1,10 +1,11 @@
 // Draft-model body in front of the LM head (Sec. 5.1 "Ensemble learning via Batched Inference", Sec. 4.1 "Target and
 // Draft Models"): one decode step of a LLaMA-style decoder for the n*B rows of the batch of drafting methods, each
-// with its own key / value cache.  At 64 rows every projection streams its weights once (a few megabytes) and is
-// launch-bound: they run through the LM head's W-streaming kernels (any [rows,K] x [N,K]^T -> fp32).  What is new
-// here are the small kernels between them: embedding + RMSNorm, rotary embedding + cache append + attention over
-// the row's own cache, residual + RMSNorm, SwiGLU.  Storage points: bf16 for weights, caches and everything that
-// feeds a projection; fp32 for the residual stream and the projections' results.
+// with its own key / value cache.  At 64 rows every projection streams a few megabytes of weights and is bound by
+// launch and latency, not bandwidth: the contraction is split into ranges so that a few hundred workgroups have
+// their loads in flight at once, the partial sums go to slabs that the consumer of the projection (rotary
+// embedding + cache append + attention, residual + RMSNorm, SwiGLU) adds in a fixed order.  Storage points: bf16 for
+// weights, caches and everything that feeds a projection; fp32 for the residual stream and the projections'
+// results.  Shapes the split kernels do not take go through the LM head's kernels (any [rows,K] x [N,K]^T -> fp32).
 #include <hip/hip_bf16.h>
 
 #include "device_utils.h"

@@ -109,6 +109,8 @@ CASES = [
     ("head128", synth.BodyConfig(layers=1, d=256, heads=2, d_ff=512, V=300, max_ctx=40), 33),
     ("d48_three_layers", synth.BodyConfig(layers=3, d=48, heads=3, d_ff=80, V=17, max_ctx=12), 7),
     ("wide_ragged_20_rows", synth.BodyConfig(layers=1, d=256, heads=4, d_ff=1032, V=100, max_ctx=20), 20),
+    ("rows_130_many_rows_kernels", synth.BodyConfig(layers=2, d=64, heads=4, d_ff=128, V=90, max_ctx=10), 130),
+    ("rows_70_ragged_k", synth.BodyConfig(layers=1, d=72, heads=9, d_ff=200, V=33, max_ctx=8), 70),
     ("d512_skinny", synth.BodyConfig(layers=2, d=512, heads=8, d_ff=1536, V=1000, max_ctx=300), 64),
 ]
 
