@@ -57,6 +57,21 @@ __global__ void k_read_resident(const float4* __restrict__ a, float* out, size_t
 // sustain when nothing else is in the way.
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+// The operand walk of a GEMM whose operands are K-contiguous: a workgroup owns a tile of `rows` rows that are
+// `stride` bytes apart and reads, step after step, the next 128 bytes of every row (8 lanes x 16 bytes per row).
+__global__ __launch_bounds__(256) void k_walk(const unsigned char* __restrict__ base, size_t stride, int rows, int steps,
+                                              size_t tile_stride, float* out) {
+    const unsigned char* tile = base + (size_t)blockIdx.x * tile_stride;
+    const int lane8 = threadIdx.x & 7, r0 = threadIdx.x >> 3;       // 32 rows per pass
+    float acc = 0.f;
+    for (int s = 0; s < steps; ++s)
+        for (int r = r0; r < rows; r += 32) {
+            const float4 v = *reinterpret_cast<const float4*>(tile + (size_t)r * stride + (size_t)s * 128 + lane8 * 16);
+            acc += v.x + v.w;
+        }
+    if (acc == 1234.5f) out[0] = acc;
+}
+
 __global__ __launch_bounds__(256) void k_mfma_peak(int iters, float* out) {
     bf16x8_t a, b;
     for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(threadIdx.x * 0.001f + i); b[i] = (__bf16)(i * 0.5f); }
@@ -149,6 +164,16 @@ int main() {
         char nm[96];
         snprintf(nm, sizeof nm, "%d workgroups each read the same %zu MiB %d times", wgs, mb, passes);
         printf("%-58s %9.2f   %7.2f TB/s out of the L2s\n", nm, us, (double)wgs * passes * mb * 1048576.0 / us * 1e-6);
+    }
+    for (int same_tile : {1, 0}) {
+        // 1008 workgroups x 256 rows x 32 steps of 128 bytes (k = 2048 in bf16, rows 4096 bytes apart): 1.06 GB
+        const int wgs = 1008, rows = 256, steps = 32;
+        const size_t stride = 4096, tile_stride = same_tile ? 0 : rows * stride;        // the last tile ends at 1008 MiB
+        const double us = time_us([&] {
+            hipLaunchKernelGGL(k_walk, dim3(wgs), dim3(256), 0, 0, (const unsigned char*)a, stride, rows, steps, tile_stride, (float*)out);
+        }, 5);
+        printf("%-58s %9.2f   %7.2f TB/s\n", same_tile ? "GEMM operand walk (256 rows x 4 KB), all the same tile" :
+               "GEMM operand walk (256 rows x 4 KB), a tile per workgroup", us, (double)wgs * rows * steps * 128.0 / us * 1e-6);
     }
     {
         const int iters = 20000;
