@@ -37,7 +37,7 @@ WsLayout ws_layout(const tabed_cfg& c) {
     L.C3max = (c.V + kBlock * 4 - 1) / (kBlock * 4);
     L.NSEG = (c.V + kSegV - 1) / kSegV;
     L.C5 = (c.V + kResidChunkV - 1) / kResidChunkV;
-    L.RS = kStatHdr + c.n;
+    L.RS = kStatHdr + ((c.policy == 2 && TABED_GRID_CANDIDATES > c.n) ? TABED_GRID_CANDIDATES : c.n);   // A sums: per draft, or per mixture
     L.DW = (c.policy == 2) ? TABED_GRID_CANDIDATES : c.n;
     L.Cd = (c.V + kChunkV - 1) / kChunkV;
     size_t off = 0;

@@ -36,7 +36,7 @@ struct WsLayout {
     size_t off_pm;       // float  [M][NT] tile maxima of scaled logits
     size_t off_ps;       // float  [M][NT] tile sums of exp(scaled logit - tile max)
     size_t off_cand;     // Top2Rec [B][C2]
-    size_t off_stats;    // double [B][gamma+1][C3max][RS]
+    size_t off_stats;    // double [B][gamma+1][C3max][RS]: header + one KL sum per draft (or per grid candidate)
     size_t off_seg;      // double [B][2][NSEG] segment masses: residual, target
     size_t off_wstage;   // float [B][n] next weights staged by the fused window update
     size_t off_dist;     // double [B][gamma][DW][Cd][2] chunk sums, or chunk arg-maxes (value, index), of the second pass

@@ -631,12 +631,17 @@ hipError_t launch_siblings(const tabed_cfg& c, const WsLayout& L, char* ws, uint
 //     A_jc = sum exp(st - m_c) * (st - s_j)  for every draft j }.
 // Since KL(p || q_j) = sum_v p (st - s_j) - lse_p + lse_j, the records of a row combine exactly (fp64, chunk
 // order) in the kernel that follows.  N is the number of drafts when known at compile time (0 = run time).
+// Two-draft grid policy with KL: the same pass leaves, instead of the A_jc, the sums of the 11 candidate mixtures
+//   A_kc = sum exp(st - m_c) * (st - log mix_k),   mix_k = (1 - k/10) q_1 + (k/10) q_2,   KL(p || mix_k) = A_k / Z - lse_p,
+// so that the distances of that policy cost no pass of their own either.
 // =====================================================================================================
 struct StatsArgs {
     int V, n, B, gamma, C3, RS;
     int with_drafts;      // 0: only the target-row part of the records (distances come from k_dist)
+    int grid;             // 1 (two drafts): the A sums are those of the 11 candidate mixtures, not of the drafts
     const float* target;
     const float* dlogits;
+    const double* dlse;   // [gamma,B,n]; read only for the mixtures
     const float* temperature;
     double* stats;
 };
@@ -652,11 +657,19 @@ __global__ __launch_bounds__(kBlock) void k_stats(StatsArgs a) {
     __shared__ double s_redd[kWavesPerBlock];
     __shared__ ArgMax s_am[kWavesPerBlock];
     __shared__ double s_A[kWavesPerBlock][TABED_MAX_N];
+    __shared__ float s_qhi[2], s_qoml[2];                // the two drafts' log-sum-exp as fp32 head + (1 - tail)
 
     const float* trow = a.target + ((size_t)b * (gamma + 1) + i) * V;
     const float* qbase = a.dlogits + (((size_t)i * a.B + b) * n) * V;   // only dereferenced when i < gamma
     const int cb = c * (kBlock * 4 * U);
     const bool drafts = (i < gamma) && a.with_drafts;
+    const bool grid = (N == 2) && drafts && a.grid;
+    if (N == 2 && grid && tid < 2) {                     // published by the barriers of the maximum below
+        const double l = a.dlse[((size_t)i * a.B + b) * 2 + tid];
+        const float hi = (float)l;
+        s_qhi[tid] = hi;
+        s_qoml[tid] = (float)(1.0 - (l - (double)hi));
+    }
 
     float4 tx[U];
     float4 dx[(N > 0) ? N : 1][U];
@@ -695,7 +708,37 @@ __global__ __launch_bounds__(kBlock) void k_stats(StatsArgs a) {
     am = wave_argmax(am);
     if (lane == 0) s_am[wave] = am;
 
-    if (drafts) {
+    if (N == 2 && grid) {
+        // both drafts' probabilities of this thread's elements, then one candidate mixture at a time.  The sums are
+        // taken about the chunk maximum (st - m_c <= 0 where exp(st - m_c) matters) and m_c Z_c is added back in
+        // fp64 when the record is written.  Bare v_log_f32 (log2): its ~1e-7 relative error is random per element
+        // and averages out under the sum; a mixture below the normal range only occurs where p is negligible too.
+        float q0[U * 4], q1[U * 4];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float a0 = f4get(dx[0][u], e), a1 = f4get(dx[(N > 1) ? 1 : 0][u], e);
+                const float p0 = (a0 > -INFINITY) ? __expf(a0 * invT - s_qhi[0]) * s_qoml[0] : 0.f;
+                const float p1 = (a1 > -INFINITY) ? __expf(a1 * invT - s_qhi[1]) * s_qoml[1] : 0.f;
+                q0[u * 4 + e] = p0;
+                q1[u * 4 + e] = p1;
+            }
+        constexpr int NC = TABED_GRID_CANDIDATES;
+        float tl[U * 4];                                   // log2 of exp(st - m_c), shared by the candidates
+#pragma unroll
+        for (int x = 0; x < U * 4; ++x) tl[x] = (ex[x] > 0.f) ? (st[x] - mc) * 1.44269504f : 0.f;
+#pragma unroll
+        for (int k = 0; k < NC; ++k) {
+            const float w1 = (float)k / (float)(NC - 1), w0 = 1.f - w1;
+            float acc = 0.f;
+#pragma unroll
+            for (int x = 0; x < U * 4; ++x)                // a term with p = 0 is 0 (tl is 0 there and the logarithm finite)
+                acc += ex[x] * (tl[x] - __builtin_amdgcn_logf(fmaxf(fmaf(w1, q1[x], w0 * q0[x]), 1e-37f)));
+            const double Ak = wave_sum((double)(acc * 0.693147181f));
+            if (lane == 0) s_A[wave][k] = Ak;
+        }
+    } else if (drafts) {
         if (N > 0) {
 #pragma unroll
             for (int j = 0; j < N; ++j) {
@@ -738,7 +781,13 @@ __global__ __launch_bounds__(kBlock) void k_stats(StatsArgs a) {
         rec[2] = (double)t.v;
         rec[3] = (double)t.i;
     }
-    if (drafts && tid < n) rec[kStatHdr + tid] = (s_A[0][tid] + s_A[1][tid]) + (s_A[2][tid] + s_A[3][tid]);
+    if (grid) {
+        if (tid < TABED_GRID_CANDIDATES)
+            rec[kStatHdr + tid] = ((s_A[0][tid] + s_A[1][tid]) + (s_A[2][tid] + s_A[3][tid])) +
+                                  (double)mc * ((s_redd[0] + s_redd[1]) + (s_redd[2] + s_redd[3]));
+    } else if (drafts && tid < n) {
+        rec[kStatHdr + tid] = (s_A[0][tid] + s_A[1][tid]) + (s_A[2][tid] + s_A[3][tid]);
+    }
 }
 
 // =====================================================================================================
@@ -1009,6 +1058,7 @@ struct FinishArgs {
     float dist_scale;     // 0.5 for total variation, 1 for KL
     int hard;             // 1: dist holds chunk arg-maxes and the distance is the token-mismatch indicator
     int hard_margin;      // 1: those arg-maxes are of fp32 mixtures: a near-tie flags the position
+    int grid_kl;          // 1: the records of k_stats hold the KL sums of the DW candidate mixtures (no second pass)
     int fuse;             // 1: the call also advances every sequence's window and writes the next weights
     WindowArgs win;
     double* tstate;       // token tree: [B][kTsSlots] record of every sequence's walk, or nullptr (chain)
@@ -1259,15 +1309,17 @@ __global__ __launch_bounds__(kBlock) void k_finish(FinishArgs a) {
 
     if (book) {
         if (a.dist == nullptr) {
-            // ---- distances: thread per (position, draft), chunks in order with the scales computed above
-            for (int q = tid; q < gamma * n; q += kBlock) {
-                const int ii = q / n, j = q % n;
+            // ---- distances: thread per (position, draft or candidate mixture), chunks in order with the scales
+            //      computed above.  KL(p || q_j) = A_j / Z - lse_p + lse_j; a mixture's sums already hold its logarithm.
+            const int dw = a.grid_kl ? a.DW : n;
+            for (int q = tid; q < gamma * dw; q += kBlock) {
+                const int ii = q / dw, j = q % dw;
                 const double* r0 = sb + (size_t)ii * C3 * RS + kStatHdr + j;
                 double A = 0.0;
 #pragma unroll 8
                 for (int cc = 0; cc < C3; ++cc) A += r0[(size_t)cc * RS] * s_scale[ii * C3 + cc];
-                const double kl = A / s_rowZ[ii] - s_rowlse[ii] + a.dlse[((size_t)ii * a.B + b) * n + j];
-                publish_store(&a.dev[((size_t)b * gamma + ii) * n + j], (float)kl);
+                const double kl = A / s_rowZ[ii] - s_rowlse[ii] + (a.grid_kl ? 0.0 : a.dlse[((size_t)ii * a.B + b) * n + j]);
+                publish_store(&a.dev[((size_t)b * gamma + ii) * dw + j], (float)kl);
             }
         } else if (!a.hard) {
             // ---- distances from the second pass: add the chunk sums in chunk order
@@ -1463,7 +1515,9 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
                          int32_t* out_tokens, float* dev, int32_t* n_valid, uint8_t* flags, float* ring,
                          int32_t* ring_head, int32_t* ring_count, float* next_weights, bool tree, hipStream_t s) {
     const bool vec = (c.V % 4 == 0);
-    const bool second_pass = (c.distance != 0 || c.policy == 2);   // distances that take a pass of their own
+    // the KL of the two-draft grid's mixtures rides in the statistics pass (vectorised rows only)
+    const bool grid_in_stats = (c.policy == 2 && c.distance == 0 && vec);
+    const bool second_pass = (c.distance != 0 || (c.policy == 2 && !grid_in_stats));   // distances that take a pass of their own
     const int ncomp = (vec && (c.n == 2 || c.n == 4 || c.n == 8)) ? c.n : 0;   // compile-time draft counts
     const int U = pick_stats_unroll(c, ncomp == 8 ? 2 : 4);
     const int C3 = (c.V + kBlock * 4 * U - 1) / (kBlock * 4 * U);
@@ -1472,7 +1526,8 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
         StatsArgs a;
         a.V = c.V; a.n = c.n; a.B = c.B; a.gamma = c.gamma; a.RS = L.RS; a.C3 = C3;
         a.with_drafts = second_pass ? 0 : 1;
-        a.target = target_logits; a.dlogits = draft_logits; a.temperature = temperature;
+        a.grid = grid_in_stats ? 1 : 0;
+        a.target = target_logits; a.dlogits = draft_logits; a.dlse = draft_lse; a.temperature = temperature;
         a.stats = reinterpret_cast<double*>(ws + L.off_stats);
         const dim3 grid(C3, c.gamma + 1, c.B);
         if (!vec) launch_stats_n<false, 0>(&prof, U, grid, s, a);
@@ -1518,6 +1573,7 @@ hipError_t launch_verify(const tabed_cfg& c, const WsLayout& L, char* ws, uint64
     a.dist = second_pass ? reinterpret_cast<const double*>(ws + L.off_dist) : nullptr;
     a.DW = L.DW; a.Cd = L.Cd; a.dist_scale = (c.distance == 1) ? 0.5f : 1.f; a.hard = (c.distance == 2) ? 1 : 0;
     a.hard_margin = (c.distance == 2 && c.policy == 2) ? 1 : 0;
+    a.grid_kl = grid_in_stats ? 1 : 0;
     a.fuse = (ring != nullptr) ? 1 : 0;
     a.win = window_args(c, round + 1, ring, ring_head, ring_count, next_weights);   // the weights of the NEXT round
     a.wstage = reinterpret_cast<float*>(ws + L.off_wstage);
