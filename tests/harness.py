@@ -200,22 +200,38 @@ class Margins:
         return self._cdf_margin(f, float(u), int(self.o["out_tokens"][b, k]))
 
 
-def compare_round(g, o, wl, tally: Tally, check_logits=True, hard=False, margins: Margins | None = None):
+def compare_round(g, o, wl, tally: Tally, check_logits=True, hard=False, margins: Margins | None = None, grid_tie=None):
     """Element-by-element comparison of one round (wl: the workload of the sequences compared).  Returns True
     if every sequence stayed in lock-step; False if a flagged decision diverged (the caller then resyncs the
-    window state)."""
+    window state).
+
+    grid_tie(b, c_gpu, c_oracle): two-draft grid policy only.  Its weights are an arg-min over 11 window sums of fp32
+    distances that differ between the two sides in their last bits; when two candidates' sums are closer than the
+    tolerance of the distances themselves the arg-min may legitimately differ.  The callback says whether the
+    oracle-side sums of the two candidates are that close; the sequence is then not compared in this round."""
     B, n, gamma = wl.B, wl.n, wl.gamma
     SM, AM = binding.FLAG_SAMPLE_MARGIN, binding.FLAG_ACCEPT_MARGIN
-    np.testing.assert_allclose(g["weights"], o["weights"], rtol=1e-5, atol=1e-6)
-    tally.max_w_err = max(tally.max_w_err, float(np.max(np.abs(g["weights"] - o["weights"]))))
+    skip = set()
+    if grid_tie is not None:
+        for b in range(B):
+            if not np.array_equal(g["weights"][b], o["weights"][b]):
+                c_g, c_o = int(round(float(g["weights"][b, 1]) * 10)), int(round(float(o["weights"][b, 1]) * 10))
+                assert abs(float(g["weights"][b, 1]) - c_g / 10) < 1e-6 and grid_tie(b, c_g, c_o), \
+                    f"grid weights differ without a tie b={b}: {g['weights'][b]} vs {o['weights'][b]}"
+                skip.add(b)
+                tally.flagged_divergences += 1
+    same = [b for b in range(B) if b not in skip]
+    np.testing.assert_allclose(g["weights"][same], o["weights"][same], rtol=1e-5, atol=1e-6)
+    if same:
+        tally.max_w_err = max(tally.max_w_err, float(np.max(np.abs(g["weights"][same] - o["weights"][same]))))
     if check_logits:
         scale = float(np.max(np.abs(o["draft_logits"])))
         err = float(np.max(np.abs(g["draft_logits"] - o["draft_logits"])))
         tally.max_logit_err = max(tally.max_logit_err, err)
         assert err <= 1e-5 * max(scale, 1.0) and err <= 2e-2, (err, scale)
     np.testing.assert_allclose(g["draft_lse"], o["draft_lse"], rtol=0, atol=2e-6)
-    lock = True
-    for b in range(B):
+    lock = not skip
+    for b in same:
         alive = True      # this sequence still comparable in this round
         for pos in range(gamma):
             tally.decisions += 1
@@ -315,7 +331,13 @@ def run_rounds(oracle, wl, rounds, temp, seed=0, policy=0, check_logits=True, un
                        u_res=np.array([oracle.uniform(seed, rnd, int(b), g_, 0) for b in b_index], np.float32))
         o = orc.round(rnd, W, H_o, target_o, temp_o, **u_o)
         margins = Margins(oracle, wl_o, o, target_o, temp_o, seed, rnd, b_index, **{k: u_o.get(k) for k in ("u_draft", "u_acc", "u_res")})
-        if not compare_round(g, o, wl_o, tally, check_logits, hard=(distance == 2), margins=margins):
+        grid_tie = None
+        if policy == 2:
+            def grid_tie(b, c_g, c_o, orc=orc):
+                live = orc.ring[b, :max(int(orc.count[b]), 1)].astype(np.float64) if wl.h > 0 else orc.ring[b, :1].astype(np.float64)
+                e = live.sum(axis=0)
+                return abs(e[c_g] - e[c_o]) <= 1e-5 * abs(e[c_o]) + 1e-6 * live.shape[0]
+        if not compare_round(g, o, wl_o, tally, check_logits, hard=(distance == 2), margins=margins, grid_tie=grid_tie):
             gpu.resync_from(orc, rows)
         if on_round is not None:
             on_round(rnd, g, o)
