@@ -1,11 +1,17 @@
 """GPU parity of the draft-model body (tabed_draft_body_step) against the fp64 oracle with the same storage points.
 
 The two sides differ by the accumulation precision of the projections (fp32 MFMA against fp64) and by fp32
-reductions in the norms and in attention.  A value that lands within that error of a bf16 rounding boundary can
-come out one bf16 step apart, and such a flip feeds the following layers with a 2^-8 relative change of one of
-d inputs.  The bar, derived from that: at most 1 % of the hidden-state entries differ at all by more than one bf16
-step (2^-7 relative, with an absolute floor for entries near zero), none by more than 2^-5 of the row's largest
-magnitude; cache entries written by the step obey the same bar; positions advance exactly."""
+reductions in the norms and in attention.  A value that lands within that error of a bf16 rounding boundary comes
+out one bf16 step apart, and such a flip is a real 2^-8 perturbation of one input of the following layers, where it
+causes further flips: with depth the two results drift apart until they differ by about the rounding noise of the
+format itself (measured: relative RMS difference 2.7e-4 after one layer, 6e-4 after two, 2.4e-3 after twelve, 3.7e-3
+= one bf16 step after sixteen), and no further.  The bars, from that:
+  * at any depth: relative RMS difference of a tensor at most 2^-7 (two bf16 steps), no entry further than 2^-6 of
+    its row's largest magnitude;
+  * up to two layers, where the flips are still few: at most 1 % of the entries more than one bf16 step apart
+    (2^-7 relative, with an absolute floor for entries near zero);
+cache entries written by the step obey the same bars, every other cache entry is untouched, positions advance
+exactly.  Each step is judged from a common state."""
 import numpy as np
 import pytest
 
@@ -31,17 +37,21 @@ def _from_dev(t):
     return t.cpu().numpy().view(np.uint16)
 
 
-def _close_bf16(got_bits, want_bits, what):
+def _close_bf16(got_bits, want_bits, what, layers_before=1):
+    """layers_before: how many layers' worth of rounding points lie between the common state and this tensor."""
     got = synth.bf16_to_f32(got_bits).astype(np.float64)
     want = synth.bf16_to_f32(want_bits).astype(np.float64)
     assert np.isfinite(got).all(), what
     row_max = np.abs(want).reshape(want.shape[0], -1).max(axis=1).reshape((-1,) + (1,) * (want.ndim - 1))
     diff = np.abs(got - want)
-    one_step = 2.0 ** -7 * np.maximum(np.abs(want), 2.0 ** -6 * row_max) + 1e-30
-    frac = float((diff > one_step).mean())
-    assert frac <= 0.01, f"{what}: {frac:.4f} of the entries are more than one bf16 step apart"
-    assert (diff <= 2.0 ** -5 * row_max + 1e-30).all(), f"{what}: max diff {diff.max()} (row max {row_max.max()})"
-    return float((diff > 0).mean())
+    assert (diff <= 2.0 ** -6 * row_max + 1e-30).all(), f"{what}: max diff {diff.max()} (row max {row_max.max()})"
+    rel_rms = float(np.sqrt((diff ** 2).mean() / max((want ** 2).mean(), 1e-60)))
+    assert rel_rms <= 2.0 ** -7, f"{what}: relative RMS difference {rel_rms:.2e}"
+    if layers_before <= 2:
+        one_step = 2.0 ** -7 * np.maximum(np.abs(want), 2.0 ** -6 * row_max) + 1e-30
+        frac = float((diff > one_step).mean())
+        assert frac <= 0.01, f"{what}: {frac:.4f} of the entries are more than one bf16 step apart"
+    return rel_rms
 
 
 class BodyPair:
@@ -86,14 +96,14 @@ class BodyPair:
         torch.cuda.synchronize()
         assert np.array_equal(self.d_ctx.cpu().numpy(), self.ctx)
         H_g = _from_dev(self.d_H).reshape(self.rows, bc.d)
-        changed = _close_bf16(H_g, H_o, "H")
+        changed = _close_bf16(H_g, H_o, "H", bc.layers)
         # the cache rows the step wrote, and nothing else
         kg = _from_dev(self.d_kc).reshape(self.kc.shape)
         vg = _from_dev(self.d_vc).reshape(self.vc.shape)
         r = np.arange(self.rows)
         for name, got, want in (("kcache", kg, self.kc), ("vcache", vg, self.vc)):
             for l in range(bc.layers):
-                _close_bf16(got[l, r, before], want[l, r, before], f"{name} layer {l}")
+                _close_bf16(got[l, r, before], want[l, r, before], f"{name} layer {l}", l + 1)
             mask = np.ones(want.shape, dtype=bool)
             mask[:, r, before] = False
             assert np.array_equal(got[mask], want[mask]), f"{name}: an entry outside the appended row changed"
@@ -133,6 +143,16 @@ def test_body_68m_shape_64_rows(oracle):
     g = np.random.default_rng(6)
     for _ in range(2):
         pair.step(g.integers(0, bc.V, size=rows))
+
+
+def test_body_twelve_layers_stay_within_the_rounding_noise_of_the_format(oracle):
+    """The depth of the 160M-class draft: the two sides have drifted apart by then, but by no more than bf16's own
+    rounding noise (see the module comment)."""
+    bc = synth.BodyConfig(layers=12, d=768, heads=12, d_ff=3072, V=2000, max_ctx=40)
+    rows = 12
+    pair = BodyPair(oracle, bc, rows, seed=8, fill=lambda g: g.integers(0, 36, size=rows))
+    rms = pair.step(np.random.default_rng(2).integers(0, bc.V, size=rows))
+    assert rms > 0.0                                   # they do differ: the test is not comparing a copy
 
 
 def test_body_tokens_read_from_the_block_of_drafted_tokens(oracle):
