@@ -85,6 +85,8 @@ SHAPES = [
     # shapes that take the many-rows LM-head kernel (bf16, n*B > 64, d % 64 == 0)
     (4099,   256, 8, 40, 2,    3, 1, "one"),        # 320 rows: two row blocks, V % 4 != 0 (element-wise epilogue)
     (3000,   128, 8, 70, 1,    3, 1, "mixed07"),    # 560 rows: three row blocks, ragged last vocabulary block
+    (900,    64,  8, 20, 1,    2, 1, "one"),        # 160 rows, one k-block in all
+    (262144, 64,  2, 2, 1,     2, 1, "mixed07"),    # the largest vocabulary the library takes
 ]
 
 
