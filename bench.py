@@ -317,7 +317,9 @@ def main():
             # uniforms repeat with the pool, like the inputs do; the window state still evolves across replays.
             side = torch.cuda.Stream()
             set_stream(side.cuda_stream)
-            full, rem = args.steps // args.pool, args.steps % args.pool
+            # (a short run, K <= 128, is one graph of its own: a single launch for all K steps)
+            unit = args.steps if args.steps <= 128 else args.pool
+            full, rem = args.steps // unit, args.steps % unit
             graph, graph_rem = torch.cuda.CUDAGraph(), (torch.cuda.CUDAGraph() if rem else None)
             with torch.cuda.stream(side):
                 state["step"] = args.pool * ((state["step"] + args.pool - 1) // args.pool)   # a replay starts at slot 0
@@ -325,13 +327,13 @@ def main():
                     step()                        # once eagerly on the side stream
                 side.synchronize()
                 with torch.cuda.graph(graph, stream=side):
-                    for _ in range(args.pool):
+                    for _ in range(unit):
                         step()
                 if rem:
                     with torch.cuda.graph(graph_rem, stream=side):
                         for _ in range(rem):
                             step()
-                    state["step"] += args.pool - rem
+                    state["step"] += unit - rem
             torch.cuda.synchronize()
             graph.replay()
             torch.cuda.synchronize()
