@@ -78,6 +78,12 @@ def threads() -> int:
     return int(omp.omp_get_max_threads())
 
 
+def set_threads(count: int) -> None:
+    """Number of OpenMP threads for the calls that follow (timing the oracle on one core and on all of them)."""
+    omp = C.CDLL("libgomp.so.1")
+    omp.omp_set_num_threads(C.c_int(int(count)))
+
+
 # ---------------------------------------------------------------- primitives
 def philox4x32_10(ctr, key):
     c = np.ascontiguousarray(ctr, dtype=np.uint32)
